@@ -1,0 +1,149 @@
+"""fp64 CPU oracle for the MatKV hot path: ctypes front end.  TEST INFRASTRUCTURE ONLY.
+
+The arithmetic lives in ``matkv_oracle.c`` (plain double-precision loops).  This
+module compiles it with gcc, loads it, and offers numpy-level wrappers plus the
+trivial glue the definition needs: concatenating chunk KVs and the tail into one
+flat key list (the paper's cache assembly, Section IV "Avoiding Prefill Using KV
+in SSD": loaded chunk KVs combined with the query's KVs as the past cache).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+module; it imports nothing from the HIP package and the HIP package never
+imports it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "matkv_oracle.c")
+_LIB = os.path.join(_HERE, "libmatkv_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no fast-math: summation order is the source's)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.oracle_threads.restype = ctypes.c_int
+        lib.oracle_rope.argtypes = [dp, ctypes.c_int, ctypes.c_double, ctypes.c_double]
+        lib.oracle_rope.restype = None
+        lib.oracle_materialize.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_double, ctypes.c_double, dp, dp]
+        lib.oracle_materialize.restype = None
+        lib.oracle_attn.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_double, dp, dp, dp]
+        lib.oracle_attn.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)) if a is not None else None
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle's parallel loops use."""
+    return int(_load().oracle_threads())
+
+
+def rope(x, pos: float, base: float):
+    """Rotate one head vector x[D] to position ``pos`` (half-split pairing)."""
+    x = _f64(x).copy()
+    assert x.ndim == 1 and x.shape[0] % 2 == 0
+    _load().oracle_rope(_p(x), x.shape[0], float(pos), float(base))
+    return x
+
+
+def materialize(X, Wk, Wv, n_kv_heads: int, head_dim: int, pos0: float, base: float):
+    """K = RoPE(X Wk^T, pos0 + i), V = X Wv^T for one layer.
+
+    X [T, Hd]; Wk, Wv [Hkv*D, Hd].  Returns K, V as [Hkv, T, D] float64.
+    A chunk uses pos0 = 0 (Section III-B: every document starts at the first
+    input position)."""
+    X, Wk, Wv = _f64(X), _f64(Wk), _f64(Wv)
+    T, Hd = X.shape
+    assert Wk.shape == (n_kv_heads * head_dim, Hd) and Wv.shape == Wk.shape
+    K = np.empty((n_kv_heads, T, head_dim), dtype=np.float64)
+    V = np.empty_like(K)
+    _load().oracle_materialize(_p(X), _p(Wk), _p(Wv), T, Hd, n_kv_heads, head_dim,
+                               float(pos0), float(base), _p(K), _p(V))
+    return K, V
+
+
+def attn(Q, K, V, n_ctx: int, row0: int, scale: float | None = None,
+         want_lse: bool = False, want_probs: bool = False):
+    """Attention of R rows over a flat key list (see ``oracle_attn`` in the C file).
+
+    Q [R, Hq, D]; K, V [Hkv, Nk, D]; first n_ctx keys unmasked, the rest causal
+    with row r seeing tail keys j <= row0 + r.  Returns O [R, Hq, D] (and lse
+    [R, Hq], probs [R, Hq, Nk] when asked)."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    R, Hq, D = Q.shape
+    Hkv, Nk, D2 = K.shape
+    assert D2 == D and V.shape == K.shape and Hq % Hkv == 0
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    O = np.empty((R, Hq, D), dtype=np.float64)
+    lse = np.empty((R, Hq), dtype=np.float64) if want_lse else None
+    probs = np.empty((R, Hq, Nk), dtype=np.float64) if want_probs else None
+    _load().oracle_attn(_p(Q), _p(K), _p(V), R, Hq, Hkv, D, Nk, int(n_ctx), int(row0),
+                        float(scale), _p(O), _p(lse), _p(probs))
+    out = [O]
+    if want_lse:
+        out.append(lse)
+    if want_probs:
+        out.append(probs)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def assemble(chunks, tail_k, tail_v):
+    """Flat key list of one instance and one layer: chunk KVs in the given order,
+    then the tail (question tokens, then generated tokens).
+
+    chunks: list of (K, V) each [Hkv, L_c, D]; tail_k/tail_v [Hkv, T_tail, D].
+    Returns K, V [Hkv, N + T_tail, D] and n_ctx = N."""
+    ks = [_f64(k) for k, _ in chunks] + [_f64(tail_k)]
+    vs = [_f64(v) for _, v in chunks] + [_f64(tail_v)]
+    K = np.concatenate(ks, axis=1)
+    V = np.concatenate(vs, axis=1)
+    n_ctx = int(sum(k.shape[1] for k, _ in chunks))
+    return K, V, n_ctx
+
+
+def prefill_attn(Q, chunks, tail_k, tail_v, scale=None):
+    """Question sub-prefill (Section V-A "Prefill time"): row i of the Lq-token
+    question attends to every chunk token and to question tokens j <= i.
+    tail_k/tail_v hold exactly the Lq question tokens."""
+    K, V, n_ctx = assemble(chunks, tail_k, tail_v)
+    assert np.asarray(Q).shape[0] == np.asarray(tail_k).shape[1]
+    return attn(Q, K, V, n_ctx, 0, scale)
+
+
+def decode_attn(q, chunks, tail_k, tail_v, scale=None):
+    """One decode step: the newest token (last tail row) attends to every chunk
+    token and to the whole tail including itself.  q [Hq, D] -> o [Hq, D]."""
+    K, V, n_ctx = assemble(chunks, tail_k, tail_v)
+    t_tail = np.asarray(tail_k).shape[1]
+    o = attn(np.asarray(q)[None], K, V, n_ctx, t_tail - 1, scale)
+    return o[0]
