@@ -1,0 +1,200 @@
+/*
+ * libmatkv - the inference-time hot path of MatKV on one MI355X (gfx950).
+ *
+ * MatKV (paper Section III) precomputes the key/value tensors of every RAG
+ * chunk once ("materialization"), stores them, and at query time loads them
+ * instead of recomputing them; the question's tokens and every generated token
+ * then attend over a cache assembled from the loaded chunk KVs followed by their
+ * own KVs.  This library is that path and nothing else:
+ *
+ *   matkv_materialize       K = RoPE(X Wk^T), V = X Wv^T of one layer   (III-B steps 1-3)
+ *   matkv_load              pinned-host KV blob -> HBM slot, side stream (IV, load_KV)
+ *   matkv_assemble          page table of a batch, no data movement      (IV, put_KV)
+ *   matkv_prefill_attn      question rows over [chunks | question]       (V-A "prefill time")
+ *   matkv_decode_attn       newest token over [chunks | tail]            (V-A "decode time")
+ *
+ * Conventions
+ *   - Plain C ABI.  Pointers are DEVICE pointers unless the name or the comment
+ *     says "host".  The library allocates no device memory: slots, tails, Q/O,
+ *     the workspace and cache tables belong to the caller.
+ *   - All compute entry points enqueue on the compute stream given at creation
+ *     and return without waiting; matkv_load enqueues on the load stream.
+ *   - Every entry point returns a matkv_status; nothing aborts or prints.  After
+ *     a failure matkv_last_error() holds a one-line reason.  Arguments are
+ *     validated before anything is enqueued.
+ *   - Element type (config.dtype): MATKV_BF16 (bf16 storage, fp32 arithmetic,
+ *     one round-to-nearest-even on store) or MATKV_F32.
+ *
+ * Layouts (s = bytes per element)
+ *   blob / slot   [layer][K|V][Hkv][n_tokens][D]        dense, no header; one chunk is
+ *                 one contiguous copy and each (layer, K|V, head) is a contiguous stream
+ *   tail (layer)  [max_batch][Hkv][max_tail_tokens][D]  one buffer for K, one for V;
+ *                 holds the question's and the generated tokens' KVs
+ *   Q, O prefill  [sum of question lengths][Hq][D]      instances back to back
+ *   Q, O decode   [batch][Hq][D]
+ *   hidden        [tokens][hidden]   weights [Hkv*D][hidden] (row = output feature)
+ *
+ * Positions: a chunk is materialized with pos0 = 0 whatever its place in the
+ * prompt (Section III-B: documents always start at the first input position);
+ * tail token j of instance b sits at position pos_base[b] + j.  Attention takes
+ * Q already rotated.
+ */
+#ifndef MATKV_H
+#define MATKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct matkv_ctx matkv_ctx;      /* opaque, host memory, owned by the library */
+typedef struct matkv_graph matkv_graph;  /* opaque captured command sequence */
+
+typedef enum {
+    MATKV_OK = 0,
+    MATKV_EINVAL = 1,        /* bad argument (null, misaligned, out of range, wrong size) */
+    MATKV_EUNSUPPORTED = 2,  /* valid but not built (head_dim, group size, dtype) */
+    MATKV_ENOTREADY = 3,     /* a page's load has neither completed nor been waited for */
+    MATKV_EBUSY = 4,         /* resource in use (capture already open, ticket ring full) */
+    MATKV_EHIP = 5,          /* a HIP call failed; sticky until the context is destroyed */
+    MATKV_ENOMEM = 6         /* host allocation failed or caller's buffer too small */
+} matkv_status;
+
+typedef enum { MATKV_F32 = 0, MATKV_BF16 = 1 } matkv_dtype;
+
+typedef struct {
+    int32_t n_layers;
+    int32_t n_q_heads;        /* Hq, multiple of n_kv_heads; Hq/Hkv in {1,2,4,8} */
+    int32_t n_kv_heads;       /* Hkv */
+    int32_t head_dim;         /* D in {64, 128} */
+    int32_t hidden;           /* Hd, multiple of 64 */
+    int32_t dtype;            /* matkv_dtype */
+    float rope_base;          /* theta_j = rope_base^(-2j/D), half-split pairing (j, j+D/2) */
+    float softmax_scale;      /* 0 selects 1/sqrt(D) */
+    int32_t max_batch;        /* instances per cache table */
+    int32_t max_pages;        /* chunks per instance */
+    int32_t max_tail_tokens;  /* question + generated tokens per instance, multiple of 8 */
+    int32_t split_tokens;     /* tokens per decode work item; 0 = chosen per table */
+} matkv_config;
+
+/* One loaded chunk: the device slot that holds its blob and its token count (host struct). */
+typedef struct {
+    const void* slot;
+    int32_t n_tokens;
+    int32_t reserved;
+} matkv_page;
+
+typedef struct { uint64_t id; } matkv_ticket;
+
+/* ---- sizes (pure host arithmetic; usable without a GPU) ------------------------------ */
+
+/* Bytes of one chunk blob: n_layers * 2 * Hkv * n_tokens * D * s.  0 on a bad config. */
+size_t matkv_blob_bytes(const matkv_config* cfg, int32_t n_tokens);
+/* Bytes of one layer's tail buffer (K or V): max_batch * Hkv * max_tail_tokens * D * s. */
+size_t matkv_tail_bytes(const matkv_config* cfg);
+/* Device bytes the caller must provide as workspace (split partials and counters). */
+size_t matkv_workspace_bytes(const matkv_config* cfg);
+/* Device bytes of one cache table (matkv_assemble's output). */
+size_t matkv_table_bytes(const matkv_config* cfg);
+/* MATKV_OK if the configuration is supported, else EINVAL / EUNSUPPORTED. */
+matkv_status matkv_config_check(const matkv_config* cfg);
+const char* matkv_status_string(matkv_status s);
+
+/* ---- context -------------------------------------------------------------------------- */
+
+/* Creates a context on the current device.  workspace: device buffer of at least
+ * matkv_workspace_bytes(cfg), 256-byte aligned, zeroed by this call (on the compute
+ * stream) and owned by the caller for the context's lifetime.  compute_stream and
+ * load_stream are hipStream_t handles (0 = the null stream); they must differ for loads
+ * to overlap compute and must both have default priority. */
+matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t workspace_bytes,
+                          void* compute_stream, void* load_stream, matkv_ctx** out);
+/* Waits for both streams, destroys events and open graphs, frees host bookkeeping. */
+matkv_status matkv_destroy(matkv_ctx* ctx);
+/* Reason of the last failure on this context ("" if none).  Valid until the next call. */
+const char* matkv_last_error(const matkv_ctx* ctx);
+
+/* ---- M: materialization (Section III-B steps 2-3; Section IV store_KV's compute half) --- */
+
+/* One layer, n_tokens rows:  K[g][i][:] = RoPE(Wk_g hidden[i], pos0 + i),
+ * V[g][i][:] = Wv_g hidden[i].  k_out / v_out point at element [0][0][0] of a
+ * [Hkv][token_stride][D] region (inside a blob, a slot or a private buffer); rows
+ * 0..n_tokens-1 of each head are written.  A chunk uses pos0 = 0.  No bias, no norm:
+ * hidden is whatever the layer would feed its K/V projections. */
+matkv_status matkv_materialize(matkv_ctx* ctx, const void* hidden, const void* w_k,
+                               const void* w_v, int32_t n_tokens, int64_t pos0,
+                               void* k_out, void* v_out, int64_t token_stride);
+
+/* The same projection for the newest tail rows of every instance of a cache table
+ * (question tokens at prefill, the generated token at each decode step); where rows go
+ * and which positions they take is read on the device from the table, so the call can
+ * be captured and replayed.  rows_per_instance < 0: instance b contributes its whole
+ * question (q_len[b] rows, hidden = [sum q_len][Hd], written to tail rows 0..q_len[b]-1);
+ * rows_per_instance = r > 0: every instance contributes r rows (hidden = [batch*r][Hd])
+ * written to tail rows tail_len[b]-r .. tail_len[b]-1.  Row j takes position
+ * pos_base[b] + j.  tail_k / tail_v: this layer's tail buffers. */
+matkv_status matkv_materialize_tail(matkv_ctx* ctx, const void* hidden, const void* w_k,
+                                    const void* w_v, const void* table,
+                                    int32_t rows_per_instance, void* tail_k, void* tail_v);
+
+/* ---- L: load (Section IV load_KV, host-memory-to-HBM half) ------------------------------ */
+
+/* Asynchronous byte-exact copy of one blob, pinned host memory -> device slot, on the load
+ * stream.  host_blob must be pinned (hipHostMalloc) and stay valid until the ticket
+ * completes; bytes must equal matkv_blob_bytes(cfg, n_tokens) and fit slot_bytes.  If the
+ * slot was referenced by an earlier matkv_assemble, the copy is ordered after all compute
+ * work enqueued so far.  Errors: EINVAL (null, size mismatch, not pinned, slot too small),
+ * EBUSY (more than 4096 tickets outstanding), EHIP. */
+matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int32_t n_tokens,
+                        void* device_slot, size_t slot_bytes, matkv_ticket* out);
+/* Makes the compute stream wait for the ticket's copy (does not block the host). */
+matkv_status matkv_wait(matkv_ctx* ctx, matkv_ticket t);
+/* MATKV_OK if the copy has finished, MATKV_ENOTREADY if not; never blocks. */
+matkv_status matkv_query(matkv_ctx* ctx, matkv_ticket t);
+/* Blocks the host until the ticket's copy has finished. */
+matkv_status matkv_sync(matkv_ctx* ctx, matkv_ticket t);
+
+/* ---- A: cache assembly (Section IV put_KV) ---------------------------------------------- */
+
+/* Builds the cache table of a batch: per instance the ordered list of loaded pages followed
+ * by its tail.  No KV bytes move.  pages_host [batch][cfg.max_pages] and n_pages_host,
+ * q_len_host [batch] are host arrays; pos_base_host [batch] may be NULL (then the first
+ * question token of instance b takes position sum of its pages' n_tokens).  The table's
+ * tail_len starts at q_len.  Every page whose slot was a matkv_load target must have been
+ * waited for or completed, else MATKV_ENOTREADY.  table: device buffer of
+ * matkv_table_bytes(cfg), written on the compute stream. */
+matkv_status matkv_assemble(matkv_ctx* ctx, const matkv_page* pages_host,
+                            const int32_t* n_pages_host, const int32_t* q_len_host,
+                            const int64_t* pos_base_host, int32_t batch, void* table);
+/* tail_len[b] += n for every instance of the table (a one-wave kernel; capturable). */
+matkv_status matkv_advance(matkv_ctx* ctx, void* table, int32_t n);
+
+/* ---- P / D: attention over the assembled cache (one layer, whole batch) ------------------- */
+
+/* Question row i of instance b, head h (KV head h / (Hq/Hkv)):
+ *   softmax over { every token of every page } U { tail tokens j <= i } of scale * q.k,
+ *   times V.  q/out: [sum q_len][Hq][D] in the table's instance order. */
+matkv_status matkv_prefill_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
+                                const void* tail_k, const void* tail_v, void* out);
+/* The newest token of each instance: all page tokens and tail tokens 0..tail_len[b]-1.
+ * q/out: [batch][Hq][D]. */
+matkv_status matkv_decode_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
+                               const void* tail_k, const void* tail_v, void* out);
+
+/* ---- command capture: replay a fixed sequence of the calls above without host cost ------ */
+
+/* Between begin and end, calls to materialize_tail / advance / prefill_attn / decode_attn
+ * are recorded from the compute stream instead of executed.  Captured work reads tail
+ * lengths and positions from the table on the device, so one recording of a decode step
+ * serves every step. */
+matkv_status matkv_graph_begin(matkv_ctx* ctx);
+matkv_status matkv_graph_end(matkv_ctx* ctx, matkv_graph** out);
+matkv_status matkv_graph_launch(matkv_ctx* ctx, matkv_graph* g);
+matkv_status matkv_graph_destroy(matkv_ctx* ctx, matkv_graph* g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MATKV_H */

@@ -117,6 +117,23 @@ def attn(Q, K, V, n_ctx: int, row0: int, scale: float | None = None,
     return out[0] if len(out) == 1 else tuple(out)
 
 
+def store_round(a, dtype: str):
+    """Storage rounding of materialized K/V (the paper stores the KV tensors as raw
+    16-bit values; here bf16): one round-to-nearest-even of the fp64 value to the
+    storage type, returned widened to float64.  "f32" rounds to single precision."""
+    a = _f64(a)
+    if dtype == "f32":
+        return a.astype(np.float32).astype(np.float64)
+    assert dtype == "bf16"
+    # bf16 keeps the sign, the exponent and the top 7 of fp64's 52 mantissa bits: drop the low
+    # 45 bits with round-to-nearest-even on the integer pattern (a carry moves into the
+    # exponent as it should).  Magnitudes below bf16's normal range (2^-126) do not occur here.
+    u = a.view(np.uint64)
+    bias = np.uint64((1 << 44) - 1) + ((u >> np.uint64(45)) & np.uint64(1))
+    r = (u + bias) & ~np.uint64((1 << 45) - 1)
+    return r.view(np.float64)
+
+
 def assemble(chunks, tail_k, tail_v):
     """Flat key list of one instance and one layer: chunk KVs in the given order,
     then the tail (question tokens, then generated tokens).

@@ -1,0 +1,263 @@
+"""ctypes binding of libmatkv.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; this module turns torch
+tensors into device pointers, owns nothing but the ctypes handles, and raises
+``MatKVError`` on any non-OK status.  There is no CPU fallback: if the library has
+not been built the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import (POINTER, Structure, byref, c_char_p, c_float, c_int32, c_int64, c_size_t,
+                    c_uint64, c_void_p)
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmatkv.so")
+
+OK, EINVAL, EUNSUPPORTED, ENOTREADY, EBUSY, EHIP, ENOMEM = range(7)
+F32, BF16 = 0, 1
+
+EXPORTS = [
+    "matkv_blob_bytes", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
+    "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
+    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load",
+    "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
+    "matkv_prefill_attn", "matkv_decode_attn", "matkv_graph_begin", "matkv_graph_end",
+    "matkv_graph_launch", "matkv_graph_destroy",
+]
+
+
+class Config(Structure):
+    _fields_ = [("n_layers", c_int32), ("n_q_heads", c_int32), ("n_kv_heads", c_int32),
+                ("head_dim", c_int32), ("hidden", c_int32), ("dtype", c_int32),
+                ("rope_base", c_float), ("softmax_scale", c_float),
+                ("max_batch", c_int32), ("max_pages", c_int32), ("max_tail_tokens", c_int32),
+                ("split_tokens", c_int32)]
+
+
+class Page(Structure):
+    _fields_ = [("slot", c_void_p), ("n_tokens", c_int32), ("reserved", c_int32)]
+
+
+class Ticket(Structure):
+    _fields_ = [("id", c_uint64)]
+
+
+class MatKVError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        name = _lib.matkv_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__(f"{where}: {name}" + (f" ({detail})" if detail else ""))
+
+
+def _load_library():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "libmatkv has no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    cfgp = POINTER(Config)
+    lib.matkv_blob_bytes.argtypes = [cfgp, c_int32]; lib.matkv_blob_bytes.restype = c_size_t
+    lib.matkv_tail_bytes.argtypes = [cfgp]; lib.matkv_tail_bytes.restype = c_size_t
+    lib.matkv_workspace_bytes.argtypes = [cfgp]; lib.matkv_workspace_bytes.restype = c_size_t
+    lib.matkv_table_bytes.argtypes = [cfgp]; lib.matkv_table_bytes.restype = c_size_t
+    lib.matkv_config_check.argtypes = [cfgp]; lib.matkv_config_check.restype = c_int32
+    lib.matkv_status_string.argtypes = [c_int32]; lib.matkv_status_string.restype = c_char_p
+    lib.matkv_create.argtypes = [cfgp, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p)]
+    lib.matkv_create.restype = c_int32
+    lib.matkv_destroy.argtypes = [c_void_p]; lib.matkv_destroy.restype = c_int32
+    lib.matkv_last_error.argtypes = [c_void_p]; lib.matkv_last_error.restype = c_char_p
+    lib.matkv_materialize.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int64,
+                                      c_void_p, c_void_p, c_int64]
+    lib.matkv_materialize.restype = c_int32
+    lib.matkv_materialize_tail.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32,
+                                           c_void_p, c_void_p]
+    lib.matkv_materialize_tail.restype = c_int32
+    lib.matkv_load.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p, c_size_t, POINTER(Ticket)]
+    lib.matkv_load.restype = c_int32
+    for fn in (lib.matkv_wait, lib.matkv_query, lib.matkv_sync):
+        fn.argtypes = [c_void_p, Ticket]; fn.restype = c_int32
+    lib.matkv_assemble.argtypes = [c_void_p, POINTER(Page), POINTER(c_int32), POINTER(c_int32),
+                                   POINTER(c_int64), c_int32, c_void_p]
+    lib.matkv_assemble.restype = c_int32
+    lib.matkv_advance.argtypes = [c_void_p, c_void_p, c_int32]; lib.matkv_advance.restype = c_int32
+    for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
+        fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        fn.restype = c_int32
+    lib.matkv_graph_begin.argtypes = [c_void_p]; lib.matkv_graph_begin.restype = c_int32
+    lib.matkv_graph_end.argtypes = [c_void_p, POINTER(c_void_p)]; lib.matkv_graph_end.restype = c_int32
+    lib.matkv_graph_launch.argtypes = [c_void_p, c_void_p]; lib.matkv_graph_launch.restype = c_int32
+    lib.matkv_graph_destroy.argtypes = [c_void_p, c_void_p]; lib.matkv_graph_destroy.restype = c_int32
+    return lib
+
+
+_lib = None
+_lib = _load_library()
+
+
+def lib():
+    """The loaded ctypes library (for tests of the raw boundary)."""
+    return _lib
+
+
+def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, hidden, dtype, rope_base,
+                max_batch, max_pages, max_tail_tokens, softmax_scale=0.0, split_tokens=0) -> Config:
+    if isinstance(dtype, torch.dtype):
+        dtype = F32 if dtype == torch.float32 else BF16
+    elif isinstance(dtype, str):
+        dtype = F32 if dtype == "f32" else BF16
+    return Config(n_layers, n_q_heads, n_kv_heads, head_dim, hidden, dtype, rope_base,
+                  softmax_scale, max_batch, max_pages, max_tail_tokens, split_tokens)
+
+
+def blob_bytes(cfg: Config, n_tokens: int) -> int:
+    return int(_lib.matkv_blob_bytes(byref(cfg), n_tokens))
+
+
+def tail_bytes(cfg: Config) -> int:
+    return int(_lib.matkv_tail_bytes(byref(cfg)))
+
+
+def workspace_bytes(cfg: Config) -> int:
+    return int(_lib.matkv_workspace_bytes(byref(cfg)))
+
+
+def table_bytes(cfg: Config) -> int:
+    return int(_lib.matkv_table_bytes(byref(cfg)))
+
+
+def config_check(cfg: Config) -> int:
+    return int(_lib.matkv_config_check(byref(cfg)))
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+class Context:
+    """One matkv_ctx on the current device.  Device buffers are torch tensors owned here only
+    to keep them alive (the library itself allocates no device memory)."""
+
+    def __init__(self, cfg: Config, compute_stream: torch.cuda.Stream | None = None,
+                 load_stream: torch.cuda.Stream | None = None, device="cuda:0"):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.compute_stream = compute_stream or torch.cuda.Stream(device=self.device)
+        self.load_stream = load_stream or torch.cuda.Stream(device=self.device)
+        nbytes = workspace_bytes(cfg)
+        if nbytes == 0:
+            raise MatKVError(config_check(cfg), "matkv_config_check")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.elem = 4 if cfg.dtype == F32 else 2
+        self.torch_dtype = torch.float32 if cfg.dtype == F32 else torch.bfloat16
+        h = c_void_p()
+        torch.cuda.synchronize(self.device)
+        st = _lib.matkv_create(byref(cfg), self.workspace.data_ptr(), nbytes,
+                               self.compute_stream.cuda_stream, self.load_stream.cuda_stream, byref(h))
+        if st != OK:
+            raise MatKVError(st, "matkv_create")
+        self._h = h
+
+    # -- plumbing ---------------------------------------------------------------------------
+    def _check(self, st: int, where: str):
+        if st != OK:
+            raise MatKVError(st, where, _lib.matkv_last_error(self._h).decode())
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.matkv_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def new_table(self) -> torch.Tensor:
+        return torch.empty(table_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+
+    def new_tail(self) -> torch.Tensor:
+        """Tail buffer of all layers: [layer][K|V][max_batch][Hkv][max_tail][D]."""
+        c = self.cfg
+        return torch.zeros((c.n_layers, 2, c.max_batch, c.n_kv_heads, c.max_tail_tokens, c.head_dim),
+                           dtype=self.torch_dtype, device=self.device)
+
+    def new_slot(self, n_tokens: int) -> torch.Tensor:
+        return torch.empty(blob_bytes(self.cfg, n_tokens), dtype=torch.uint8, device=self.device)
+
+    # -- the boundary, same names as the C entry points ---------------------------------------
+    def materialize(self, hidden, w_k, w_v, n_tokens, pos0, k_out, v_out, token_stride):
+        self._check(_lib.matkv_materialize(self._h, _ptr(hidden), _ptr(w_k), _ptr(w_v), n_tokens, pos0,
+                                           _ptr(k_out), _ptr(v_out), token_stride), "matkv_materialize")
+
+    def materialize_tail(self, hidden, w_k, w_v, table, rows_per_instance, tail_k, tail_v):
+        self._check(_lib.matkv_materialize_tail(self._h, _ptr(hidden), _ptr(w_k), _ptr(w_v), _ptr(table),
+                                                rows_per_instance, _ptr(tail_k), _ptr(tail_v)),
+                    "matkv_materialize_tail")
+
+    def load(self, host_blob, n_tokens, device_slot, nbytes=None, slot_bytes=None) -> Ticket:
+        t = Ticket()
+        nb = host_blob.numel() * host_blob.element_size() if nbytes is None else nbytes
+        sb = device_slot.numel() * device_slot.element_size() if slot_bytes is None else slot_bytes
+        self._check(_lib.matkv_load(self._h, _ptr(host_blob), nb, n_tokens, _ptr(device_slot), sb, byref(t)),
+                    "matkv_load")
+        return t
+
+    def wait(self, ticket: Ticket):
+        self._check(_lib.matkv_wait(self._h, ticket), "matkv_wait")
+
+    def query(self, ticket: Ticket) -> bool:
+        st = _lib.matkv_query(self._h, ticket)
+        if st == ENOTREADY:
+            return False
+        self._check(st, "matkv_query")
+        return True
+
+    def sync(self, ticket: Ticket):
+        self._check(_lib.matkv_sync(self._h, ticket), "matkv_sync")
+
+    def assemble(self, pages, q_len, table, pos_base=None):
+        """pages: per instance a list of (slot tensor or address, n_tokens)."""
+        c = self.cfg
+        batch = len(pages)
+        arr = (Page * (max(batch, 1) * max(c.max_pages, 1)))()
+        npg = (c_int32 * batch)(*[len(p) for p in pages])
+        for b, plist in enumerate(pages):
+            for i, (slot, n) in enumerate(plist[:c.max_pages]):
+                arr[b * c.max_pages + i] = Page(_ptr(slot), n, 0)
+        ql = (c_int32 * batch)(*q_len)
+        pb = (c_int64 * batch)(*pos_base) if pos_base is not None else None
+        self._check(_lib.matkv_assemble(self._h, arr, npg, ql, pb, batch, _ptr(table)), "matkv_assemble")
+
+    def advance(self, table, n=1):
+        self._check(_lib.matkv_advance(self._h, _ptr(table), n), "matkv_advance")
+
+    def prefill_attn(self, layer, q, table, tail_k, tail_v, out):
+        self._check(_lib.matkv_prefill_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
+                                            _ptr(out)), "matkv_prefill_attn")
+
+    def decode_attn(self, layer, q, table, tail_k, tail_v, out):
+        self._check(_lib.matkv_decode_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
+                                           _ptr(out)), "matkv_decode_attn")
+
+    def graph_begin(self):
+        self._check(_lib.matkv_graph_begin(self._h), "matkv_graph_begin")
+
+    def graph_end(self):
+        g = c_void_p()
+        self._check(_lib.matkv_graph_end(self._h, byref(g)), "matkv_graph_end")
+        return g
+
+    def graph_launch(self, g):
+        self._check(_lib.matkv_graph_launch(self._h, g), "matkv_graph_launch")
+
+    def graph_destroy(self, g):
+        self._check(_lib.matkv_graph_destroy(self._h, g), "matkv_graph_destroy")

@@ -1,0 +1,204 @@
+// K/V materialization of one layer (paper Section III-B steps 2-3, cut to the K/V projection):
+//   K[g][i][:] = RoPE(Wk_g x_i, pos_i),  V[g][i][:] = Wv_g x_i
+// This file holds the row-streaming form: one wave owns one rotary pair (features j and
+// j + D/2 of one head, K or V) and reads those two weight rows once for a small tile of
+// tokens.  With one token per instance (a decode step) it is a GEMV bound by reading the
+// weights once from HBM; it is also the fp32 path.  The tile-GEMM form for long token
+// runs lives in materialize_mfma.hip.
+#include "matkv_internal.h"
+
+namespace matkv {
+namespace {
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Ld;
+template <> struct Ld<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void get(const float* p, float* f) {
+        const float4 r = *reinterpret_cast<const float4*>(p);
+        f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
+    }
+};
+template <> struct Ld<uint16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void get(const uint16_t* p, float* f) {
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+        f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+    }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Where a row of the hidden-state matrix goes and which position it takes.
+struct RowDest {
+    int64_t pos;        // rotary position
+    size_t elem_off;    // element offset of [head 0][row][0] in the destination
+    bool valid;
+};
+
+__device__ __forceinline__ RowDest resolve_row(const MaterializeArgs& a, int r) {
+    RowDest d;
+    d.valid = false; d.pos = 0; d.elem_off = 0;
+    if (a.table == nullptr) {
+        if (r < a.n_tokens) { d.valid = true; d.pos = a.pos0 + r; d.elem_off = (size_t)r * a.D; }
+        return d;
+    }
+    const InstanceInfo* insts = reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst);
+    int b = -1, j = 0;
+    if (a.rows_per_instance > 0) {
+        if (r < a.batch * a.rows_per_instance) {
+            b = r / a.rows_per_instance;
+            j = insts[b].tail_len - a.rows_per_instance + (r % a.rows_per_instance);
+        }
+    } else {
+        for (int i = 0; i < a.batch; ++i) {
+            const int c0 = insts[i].cu_q;
+            if (r >= c0 && r < c0 + insts[i].q_len) { b = i; j = r - c0; break; }
+        }
+    }
+    if (b < 0 || j < 0 || j >= a.token_stride) return d;
+    d.valid = true;
+    d.pos = insts[b].pos_base + j;
+    d.elem_off = ((size_t)b * a.Hkv * a.token_stride + (size_t)j) * a.D;
+    return d;
+}
+
+template <typename T>
+__device__ __forceinline__ void rope_cs(const RopeEntry& e, int64_t pos, float& c, float& s) {
+    if constexpr (sizeof(T) == 4) {
+        // fp32 path: the angle in double, so that the 1e-5 parity bar holds at any position
+        double sd, cd;
+        sincos((double)pos * e.inv_freq, &sd, &cd);
+        c = (float)cd; s = (float)sd;
+    } else {
+        // bf16 path: the angle in turns, hi/lo split product, whole turns dropped exactly
+        const float p = (float)pos;
+        const float t = p * e.turns_hi;
+        const float err = fmaf(p, e.turns_hi, -t);
+        float fr = t - rintf(t);
+        fr += fmaf(p, e.turns_lo, err);
+        const float ang = fr * 6.283185307179586f;
+        c = cosf(ang); s = sinf(ang);
+    }
+}
+
+constexpr int kWavesPerBlock = 4;
+
+template <typename T, int TT>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_rows_kernel(MaterializeArgs a) {
+    constexpr int N = Ld<T>::N;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int half = a.D / 2;
+    const int task = blockIdx.x * kWavesPerBlock + wave;     // (kv, head, pair)
+    const int n_tasks = 2 * a.Hkv * half;
+    if (task >= n_tasks) return;
+    const int kv = task / (a.Hkv * half);
+    const int head = (task / half) % a.Hkv;
+    const int j = task % half;
+    const int row0 = blockIdx.y * TT;
+
+    const T* w = reinterpret_cast<const T*>(kv == 0 ? a.w_k : a.w_v);
+    const T* w0 = w + ((size_t)head * a.D + j) * a.Hd;
+    const T* w1 = w0 + (size_t)half * a.Hd;
+    const T* x = reinterpret_cast<const T*>(a.hidden) + (size_t)row0 * a.Hd;
+
+    RowDest dest[TT];
+    bool any = false;
+#pragma unroll
+    for (int t = 0; t < TT; ++t) { dest[t] = resolve_row(a, row0 + t); any |= dest[t].valid; }
+    if (!any) return;
+
+    float acc0[TT], acc1[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) { acc0[t] = 0.f; acc1[t] = 0.f; }
+
+    for (int c = lane * N; c < a.Hd; c += 64 * N) {
+        float f0[N], f1[N];
+        Ld<T>::get(w0 + c, f0);
+        Ld<T>::get(w1 + c, f1);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            if (!dest[t].valid) continue;
+            float xf[N];
+            Ld<T>::get(x + (size_t)t * a.Hd + c, xf);
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                acc0[t] = fmaf(f0[e], xf[e], acc0[t]);
+                acc1[t] = fmaf(f1[e], xf[e], acc1[t]);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TT; ++t) { acc0[t] = wave_sum(acc0[t]); acc1[t] = wave_sum(acc1[t]); }
+
+    if (lane < TT) {
+        RowDest d; float r0 = 0.f, r1 = 0.f;
+#pragma unroll
+        for (int t = 0; t < TT; ++t) if (lane == t) { d = dest[t]; r0 = acc0[t]; r1 = acc1[t]; }
+        if (d.valid) {
+            if (kv == 0) {
+                float c, s;
+                rope_cs<T>(a.rope[j], d.pos, c, s);
+                const float k0 = r0 * c - r1 * s;
+                const float k1 = r0 * s + r1 * c;
+                r0 = k0; r1 = k1;
+            }
+            T* out = reinterpret_cast<T*>(kv == 0 ? a.k_out : a.v_out) + d.elem_off +
+                     (size_t)head * a.token_stride * a.D + j;
+            if constexpr (sizeof(T) == 4) { out[0] = r0; out[half] = r1; }
+            else { out[0] = f32_to_bf16_rne(r0); out[half] = f32_to_bf16_rne(r1); }
+        }
+    }
+}
+
+__global__ void advance_kernel(char* table, size_t off_inst, int batch, int n, int max_tail) {
+    InstanceInfo* insts = reinterpret_cast<InstanceInfo*>(table + off_inst);
+    for (int b = threadIdx.x; b < batch; b += blockDim.x) {
+        const int v = insts[b].tail_len + n;
+        insts[b].tail_len = v > max_tail ? max_tail : v;   // never walks off the tail buffer
+    }
+}
+
+template <typename T>
+hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    const int n_tasks = 2 * a.Hkv * (a.D / 2);
+    const int bx = (n_tasks + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (total_rows <= 1) {
+        hipLaunchKernelGGL((materialize_rows_kernel<T, 1>), dim3(bx, 1), dim3(kWavesPerBlock * 64), 0, s, a);
+    } else {
+        constexpr int TT = 4;
+        hipLaunchKernelGGL((materialize_rows_kernel<T, TT>), dim3(bx, (total_rows + TT - 1) / TT),
+                           dim3(kWavesPerBlock * 64), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
+    const int total_rows = a.n_tokens;
+    if (total_rows <= 0) return hipSuccess;
+    if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);
+    return launch_rows<uint16_t>(a, total_rows, s);
+}
+
+hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s) {
+    hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(64), 0, s, table, off_inst, batch, n, max_tail);
+    return hipGetLastError();
+}
+
+}  // namespace matkv

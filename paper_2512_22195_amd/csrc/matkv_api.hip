@@ -1,0 +1,672 @@
+// C-ABI of libmatkv: argument validation, host bookkeeping (tickets, slot states, cache
+// tables, captured graphs) and the enqueue of copies and kernels.  See include/matkv.h for
+// the contract of every entry point.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "matkv_internal.h"
+
+using namespace matkv;
+
+namespace {
+
+constexpr int kTicketRing = 4096;
+constexpr int kStagingRing = 4;
+
+struct Ticket {
+    hipEvent_t ev = nullptr;
+    uint64_t id = 0;          // 0 = never used
+    void* slot = nullptr;
+    bool done = true;         // observed complete
+};
+
+struct SlotState {
+    uint64_t pending = 0;     // ticket id of the last load into the slot (0 = none)
+    bool waited = true;       // compute stream has been ordered after that load
+    bool referenced = false;  // some assembled table points into it
+};
+
+struct TableHost {
+    int batch = 0, n_items = 0, n_dunits = 0, n_punits = 0, total_q = 0, max_q = 0;
+    int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
+    int min_tail_len = 0;
+};
+
+struct Staging {
+    char* host = nullptr;     // pinned
+    hipEvent_t ev = nullptr;
+    bool used = false;
+};
+
+}  // namespace
+
+struct matkv_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    std::vector<std::pair<void*, int>> advances;   // (table, n) recorded during capture
+};
+
+struct matkv_ctx {
+    matkv_config cfg;
+    int device = 0;
+    hipStream_t compute = nullptr, load = nullptr;
+    char* workspace = nullptr;
+    WorkspaceLayout wl;
+    TableLayout tl;
+    float scale_log2e = 0.f;
+    char err[512];
+    bool sticky_hip = false;
+    uint64_t next_ticket = 1;
+    std::vector<Ticket> tickets;
+    std::unordered_map<const void*, SlotState> slots;
+    std::unordered_map<const void*, TableHost> tables;
+    Staging staging[kStagingRing];
+    int staging_next = 0;
+    hipEvent_t fence_ev = nullptr;
+    bool capturing = false;
+    matkv_graph* cap = nullptr;
+    std::vector<matkv_graph*> graphs;
+};
+
+namespace {
+
+matkv_status fail(matkv_ctx* c, matkv_status s, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+matkv_status hip_fail(matkv_ctx* c, hipError_t e, const char* what) {
+    (void)hipGetLastError();
+    if (c) {
+        c->sticky_hip = true;
+        snprintf(c->err, sizeof(c->err), "%s: %s", what, hipGetErrorString(e));
+    }
+    return MATKV_EHIP;
+}
+
+#define HIP_TRY(ctx, call)                                     \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
+    } while (0)
+
+int elem_bytes(const matkv_config& c) { return c.dtype == MATKV_F32 ? 4 : 2; }
+
+matkv_status check_config(const matkv_config* c, const char** why) {
+    static const char* ok = "";
+    *why = ok;
+    if (!c) { *why = "config is null"; return MATKV_EINVAL; }
+    if (c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->hidden < 1 ||
+        c->max_batch < 1 || c->max_pages < 0 || c->max_tail_tokens < 1) {
+        *why = "sizes must be positive"; return MATKV_EINVAL;
+    }
+    if (c->dtype != MATKV_F32 && c->dtype != MATKV_BF16) { *why = "unknown dtype"; return MATKV_EINVAL; }
+    if (c->n_q_heads % c->n_kv_heads) { *why = "n_q_heads not a multiple of n_kv_heads"; return MATKV_EINVAL; }
+    if (!(c->rope_base > 1.0f)) { *why = "rope_base must exceed 1"; return MATKV_EINVAL; }
+    if (c->softmax_scale < 0.f || isnan(c->softmax_scale)) { *why = "softmax_scale negative"; return MATKV_EINVAL; }
+    if (c->hidden % 64) { *why = "hidden must be a multiple of 64"; return MATKV_EINVAL; }
+    if (c->max_tail_tokens % 8) { *why = "max_tail_tokens must be a multiple of 8"; return MATKV_EINVAL; }
+    if (c->split_tokens < 0 || (c->split_tokens % 8)) { *why = "split_tokens must be a non-negative multiple of 8"; return MATKV_EINVAL; }
+    if (c->max_batch > 1024 || c->max_pages > 4096) { *why = "max_batch <= 1024, max_pages <= 4096"; return MATKV_EINVAL; }
+    if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return MATKV_EUNSUPPORTED; }
+    const int g = c->n_q_heads / c->n_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) { *why = "group size must be 1, 2, 4 or 8"; return MATKV_EUNSUPPORTED; }
+    return MATKV_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Tokens per decode work item when the configuration does not fix it: enough workgroups
+// (items x KV heads) to cover 256 compute units several times, pieces not too small.
+int choose_split(const matkv_config& c, long total_page_tokens) {
+    if (c.split_tokens > 0) return c.split_tokens;
+    const long target_wgs = 1024;
+    long s = (total_page_tokens * c.n_kv_heads + target_wgs - 1) / target_wgs;
+    s = (s + 31) / 32 * 32;
+    if (s < 64) s = 64;
+    if (s > 2048) s = 2048;
+    return (int)s;
+}
+
+TableHost* find_table(matkv_ctx* c, const void* t) {
+    auto it = c->tables.find(t);
+    return it == c->tables.end() ? nullptr : &it->second;
+}
+
+matkv_status precheck(matkv_ctx* c) {
+    if (!c) return MATKV_EINVAL;
+    if (c->sticky_hip) return MATKV_EHIP;
+    return MATKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* matkv_status_string(matkv_status s) {
+    switch (s) {
+        case MATKV_OK: return "MATKV_OK";
+        case MATKV_EINVAL: return "MATKV_EINVAL";
+        case MATKV_EUNSUPPORTED: return "MATKV_EUNSUPPORTED";
+        case MATKV_ENOTREADY: return "MATKV_ENOTREADY";
+        case MATKV_EBUSY: return "MATKV_EBUSY";
+        case MATKV_EHIP: return "MATKV_EHIP";
+        case MATKV_ENOMEM: return "MATKV_ENOMEM";
+    }
+    return "MATKV_?";
+}
+
+matkv_status matkv_config_check(const matkv_config* cfg) {
+    const char* why;
+    return check_config(cfg, &why);
+}
+
+size_t matkv_blob_bytes(const matkv_config* cfg, int32_t n_tokens) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK || n_tokens < 0) return 0;
+    return (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * (size_t)n_tokens * cfg->head_dim * elem_bytes(*cfg);
+}
+
+size_t matkv_tail_bytes(const matkv_config* cfg) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK) return 0;
+    return (size_t)cfg->max_batch * cfg->n_kv_heads * (size_t)cfg->max_tail_tokens * cfg->head_dim * elem_bytes(*cfg);
+}
+
+size_t matkv_workspace_bytes(const matkv_config* cfg) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK) return 0;
+    return workspace_layout(*cfg).bytes;
+}
+
+size_t matkv_table_bytes(const matkv_config* cfg) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK) return 0;
+    return table_layout(*cfg).bytes;
+}
+
+matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t workspace_bytes,
+                          void* compute_stream, void* load_stream, matkv_ctx** out) {
+    if (!out) return MATKV_EINVAL;
+    *out = nullptr;
+    const char* why;
+    matkv_status st = check_config(cfg, &why);
+    if (st != MATKV_OK) return st;
+    const WorkspaceLayout wl = workspace_layout(*cfg);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MATKV_EINVAL;
+    if (workspace_bytes < wl.bytes) return MATKV_ENOMEM;
+
+    matkv_ctx* c = new (std::nothrow) matkv_ctx();
+    if (!c) return MATKV_ENOMEM;
+    c->cfg = *cfg;
+    c->err[0] = 0;
+    c->compute = reinterpret_cast<hipStream_t>(compute_stream);
+    c->load = reinterpret_cast<hipStream_t>(load_stream);
+    c->workspace = reinterpret_cast<char*>(workspace);
+    c->wl = wl;
+    c->tl = table_layout(*cfg);
+    const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+    c->scale_log2e = scale * 1.4426950408889634f;
+    c->tickets.resize(kTicketRing);
+
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fence_ev, hipEventDisableTiming);
+    // rotary table: inv_freq in double, and inv_freq / 2pi split into two floats
+    RopeEntry rope[64];
+    const int half = cfg->head_dim / 2;
+    for (int j = 0; j < half; ++j) {
+        const double f = pow((double)cfg->rope_base, -2.0 * j / (double)cfg->head_dim);
+        const double turns = f / 6.283185307179586476925286766559;
+        rope[j].inv_freq = f;
+        rope[j].turns_hi = (float)turns;
+        rope[j].turns_lo = (float)(turns - (double)rope[j].turns_hi);
+    }
+    if (e == hipSuccess) e = hipMemcpy(c->workspace + wl.off_rope, rope, sizeof(RopeEntry) * half, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemsetAsync(c->workspace + wl.off_counters, 0, wl.off_partials - wl.off_counters, c->compute);
+    for (int i = 0; i < kStagingRing && e == hipSuccess; ++i) {
+        e = hipHostMalloc(reinterpret_cast<void**>(&c->staging[i].host), c->tl.bytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->staging[i].ev, hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        matkv_destroy(c);
+        return MATKV_EHIP;
+    }
+    *out = c;
+    return MATKV_OK;
+}
+
+matkv_status matkv_destroy(matkv_ctx* c) {
+    if (!c) return MATKV_EINVAL;
+    (void)hipStreamSynchronize(c->load);
+    (void)hipStreamSynchronize(c->compute);
+    for (matkv_graph* g : c->graphs) {
+        if (g->exec) (void)hipGraphExecDestroy(g->exec);
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        delete g;
+    }
+    for (Ticket& t : c->tickets)
+        if (t.ev) (void)hipEventDestroy(t.ev);
+    for (int i = 0; i < kStagingRing; ++i) {
+        if (c->staging[i].ev) (void)hipEventDestroy(c->staging[i].ev);
+        if (c->staging[i].host) (void)hipHostFree(c->staging[i].host);
+    }
+    if (c->fence_ev) (void)hipEventDestroy(c->fence_ev);
+    (void)hipGetLastError();
+    delete c;
+    return MATKV_OK;
+}
+
+const char* matkv_last_error(const matkv_ctx* c) { return c ? c->err : "context is null"; }
+
+// ------------------------------------------------------------------------------------ M ----
+
+matkv_status matkv_materialize(matkv_ctx* c, const void* hidden, const void* w_k, const void* w_v,
+                               int32_t n_tokens, int64_t pos0, void* k_out, void* v_out,
+                               int64_t token_stride) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!hidden || !w_k || !w_v || !k_out || !v_out) return fail(c, MATKV_EINVAL, "materialize: null pointer");
+    if (!aligned16(hidden) || !aligned16(w_k) || !aligned16(w_v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(c, MATKV_EINVAL, "materialize: pointers must be 16-byte aligned");
+    if (n_tokens < 0 || pos0 < 0 || token_stride < n_tokens)
+        return fail(c, MATKV_EINVAL, "materialize: n_tokens=%d pos0=%lld token_stride=%lld", n_tokens,
+                    (long long)pos0, (long long)token_stride);
+    if (pos0 + n_tokens > (1ll << 24)) return fail(c, MATKV_EINVAL, "materialize: positions beyond 2^24");
+    if (n_tokens == 0) return MATKV_OK;
+    MaterializeArgs a{};
+    a.hidden = hidden; a.w_k = w_k; a.w_v = w_v; a.k_out = k_out; a.v_out = v_out;
+    a.rope = reinterpret_cast<const RopeEntry*>(c->workspace + c->wl.off_rope);
+    a.table = nullptr; a.off_inst = 0;
+    a.pos0 = pos0; a.token_stride = token_stride; a.n_tokens = n_tokens;
+    a.rows_per_instance = 0; a.batch = 1;
+    a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim; a.Hd = c->cfg.hidden;
+    HIP_TRY(c, launch_materialize(a, c->cfg.dtype, c->compute));
+    return MATKV_OK;
+}
+
+matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void* w_k, const void* w_v,
+                                    const void* table, int32_t rows_per_instance, void* tail_k,
+                                    void* tail_v) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!hidden || !w_k || !w_v || !table || !tail_k || !tail_v)
+        return fail(c, MATKV_EINVAL, "materialize_tail: null pointer");
+    if (!aligned16(hidden) || !aligned16(w_k) || !aligned16(w_v) || !aligned16(tail_k) || !aligned16(tail_v))
+        return fail(c, MATKV_EINVAL, "materialize_tail: pointers must be 16-byte aligned");
+    TableHost* th = find_table(c, table);
+    if (!th) return fail(c, MATKV_EINVAL, "materialize_tail: table was not built by matkv_assemble");
+    if (rows_per_instance == 0) return fail(c, MATKV_EINVAL, "materialize_tail: rows_per_instance is 0");
+    if (rows_per_instance > 0 && rows_per_instance > th->min_tail_len)
+        return fail(c, MATKV_EINVAL, "materialize_tail: %d newest rows but a tail holds only %d",
+                    rows_per_instance, th->min_tail_len);
+    MaterializeArgs a{};
+    a.hidden = hidden; a.w_k = w_k; a.w_v = w_v; a.k_out = tail_k; a.v_out = tail_v;
+    a.rope = reinterpret_cast<const RopeEntry*>(c->workspace + c->wl.off_rope);
+    a.table = reinterpret_cast<const char*>(table); a.off_inst = c->tl.off_inst;
+    a.pos0 = 0; a.token_stride = c->cfg.max_tail_tokens;
+    a.rows_per_instance = rows_per_instance; a.batch = th->batch;
+    a.n_tokens = rows_per_instance > 0 ? th->batch * rows_per_instance : th->total_q;
+    a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim; a.Hd = c->cfg.hidden;
+    HIP_TRY(c, launch_materialize(a, c->cfg.dtype, c->compute));
+    return MATKV_OK;
+}
+
+// ------------------------------------------------------------------------------------ L ----
+
+matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32_t n_tokens,
+                        void* device_slot, size_t slot_bytes, matkv_ticket* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!host_blob || !device_slot || !out) return fail(c, MATKV_EINVAL, "load: null pointer");
+    if (n_tokens < 1) return fail(c, MATKV_EINVAL, "load: n_tokens=%d", n_tokens);
+    const size_t want = matkv_blob_bytes(&c->cfg, n_tokens);
+    if (bytes != want) return fail(c, MATKV_EINVAL, "load: %zu bytes given, a %d-token blob has %zu", bytes, n_tokens, want);
+    if (slot_bytes < bytes) return fail(c, MATKV_EINVAL, "load: slot of %zu bytes cannot hold %zu", slot_bytes, bytes);
+    if (!aligned16(device_slot) || !aligned16(host_blob)) return fail(c, MATKV_EINVAL, "load: pointers must be 16-byte aligned");
+    hipPointerAttribute_t attr;
+    hipError_t pe = hipPointerGetAttributes(&attr, host_blob);
+    if (pe != hipSuccess) { (void)hipGetLastError(); return fail(c, MATKV_EINVAL, "load: host blob is not pinned memory"); }
+    if (attr.type != hipMemoryTypeHost) return fail(c, MATKV_EINVAL, "load: host blob is not pinned host memory");
+    pe = hipPointerGetAttributes(&attr, device_slot);
+    if (pe != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(c, MATKV_EINVAL, "load: slot is not device memory");
+    }
+
+    Ticket& t = c->tickets[c->next_ticket % kTicketRing];
+    if (t.id != 0 && !t.done) {
+        hipError_t q = hipEventQuery(t.ev);
+        if (q == hipErrorNotReady) { (void)hipGetLastError(); return fail(c, MATKV_EBUSY, "load: %d tickets outstanding", kTicketRing); }
+        if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
+        t.done = true;
+    }
+    if (!t.ev) HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
+
+    SlotState& s = c->slots[device_slot];
+    if (s.referenced) {
+        // the slot may still be read by compute work enqueued so far: order the copy after it
+        HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
+        HIP_TRY(c, hipStreamWaitEvent(c->load, c->fence_ev, 0));
+        s.referenced = false;
+    }
+    HIP_TRY(c, hipMemcpyAsync(device_slot, host_blob, bytes, hipMemcpyHostToDevice, c->load));
+    HIP_TRY(c, hipEventRecord(t.ev, c->load));
+    t.id = c->next_ticket++;
+    t.slot = device_slot;
+    t.done = false;
+    s.pending = t.id;
+    s.waited = false;
+    out->id = t.id;
+    return MATKV_OK;
+}
+
+static matkv_status ticket_lookup(matkv_ctx* c, matkv_ticket tk, Ticket** out) {
+    if (tk.id == 0 || tk.id >= c->next_ticket) return fail(c, MATKV_EINVAL, "ticket %llu was never issued", (unsigned long long)tk.id);
+    Ticket& t = c->tickets[tk.id % kTicketRing];
+    if (t.id != tk.id) { *out = nullptr; return MATKV_OK; }   // ring slot reused: that copy finished long ago
+    *out = &t;
+    return MATKV_OK;
+}
+
+matkv_status matkv_wait(matkv_ctx* c, matkv_ticket tk) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    Ticket* t;
+    st = ticket_lookup(c, tk, &t);
+    if (st != MATKV_OK || !t) return st;
+    if (!t->done) HIP_TRY(c, hipStreamWaitEvent(c->compute, t->ev, 0));
+    auto it = c->slots.find(t->slot);
+    if (it != c->slots.end() && it->second.pending == tk.id) it->second.waited = true;
+    return MATKV_OK;
+}
+
+matkv_status matkv_query(matkv_ctx* c, matkv_ticket tk) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    Ticket* t;
+    st = ticket_lookup(c, tk, &t);
+    if (st != MATKV_OK || !t) return st;
+    if (t->done) return MATKV_OK;
+    hipError_t q = hipEventQuery(t->ev);
+    if (q == hipErrorNotReady) { (void)hipGetLastError(); return MATKV_ENOTREADY; }
+    if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
+    t->done = true;
+    return MATKV_OK;
+}
+
+matkv_status matkv_sync(matkv_ctx* c, matkv_ticket tk) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    Ticket* t;
+    st = ticket_lookup(c, tk, &t);
+    if (st != MATKV_OK || !t) return st;
+    if (!t->done) { HIP_TRY(c, hipEventSynchronize(t->ev)); t->done = true; }
+    return MATKV_OK;
+}
+
+// ------------------------------------------------------------------------------------ A ----
+
+matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t* n_pages,
+                            const int32_t* q_len, const int64_t* pos_base, int32_t batch, void* table) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (c->capturing) return fail(c, MATKV_EBUSY, "assemble: not allowed while a graph is being captured");
+    if (!n_pages || !q_len || !table) return fail(c, MATKV_EINVAL, "assemble: null pointer");
+    if (!aligned16(table)) return fail(c, MATKV_EINVAL, "assemble: table must be 16-byte aligned");
+    if (batch < 1 || batch > c->cfg.max_batch) return fail(c, MATKV_EINVAL, "assemble: batch=%d, max_batch=%d", batch, c->cfg.max_batch);
+    const matkv_config& cfg = c->cfg;
+    long total_tokens = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (n_pages[b] < 0 || n_pages[b] > cfg.max_pages) return fail(c, MATKV_EINVAL, "assemble: instance %d has %d pages, max_pages=%d", b, n_pages[b], cfg.max_pages);
+        if (n_pages[b] > 0 && !pages) return fail(c, MATKV_EINVAL, "assemble: pages is null");
+        if (q_len[b] < 1 || q_len[b] > cfg.max_tail_tokens) return fail(c, MATKV_EINVAL, "assemble: instance %d question length %d outside 1..%d", b, q_len[b], cfg.max_tail_tokens);
+        if (pos_base && (pos_base[b] < 0 || pos_base[b] + cfg.max_tail_tokens > (1ll << 24))) return fail(c, MATKV_EINVAL, "assemble: instance %d pos_base out of range", b);
+        for (int p = 0; p < n_pages[b]; ++p) {
+            const matkv_page& pg = pages[(size_t)b * cfg.max_pages + p];
+            if (!pg.slot || !aligned16(pg.slot) || pg.n_tokens < 1)
+                return fail(c, MATKV_EINVAL, "assemble: instance %d page %d is invalid", b, p);
+            auto it = c->slots.find(pg.slot);
+            if (it != c->slots.end() && it->second.pending && !it->second.waited) {
+                Ticket& t = c->tickets[it->second.pending % kTicketRing];
+                bool done = (t.id != it->second.pending) || t.done;
+                if (!done) {
+                    hipError_t q = hipEventQuery(t.ev);
+                    if (q == hipSuccess) { t.done = true; done = true; }
+                    else if (q == hipErrorNotReady) (void)hipGetLastError();
+                    else return hip_fail(c, q, "hipEventQuery");
+                }
+                if (!done) return fail(c, MATKV_ENOTREADY, "assemble: instance %d page %d: load neither finished nor waited for", b, p);
+                // finished on the load stream: still order the compute stream after it
+                if (t.id == it->second.pending) HIP_TRY(c, hipStreamWaitEvent(c->compute, t.ev, 0));
+                it->second.waited = true;
+            }
+            total_tokens += pg.n_tokens;
+        }
+    }
+
+    const int split = choose_split(cfg, total_tokens);
+    Staging& sg = c->staging[c->staging_next];
+    c->staging_next = (c->staging_next + 1) % kStagingRing;
+    if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.ev));
+    char* h = sg.host;
+    TableHeader* hdr = reinterpret_cast<TableHeader*>(h);
+    InstanceInfo* insts = reinterpret_cast<InstanceInfo*>(h + c->tl.off_inst);
+    Item* items = reinterpret_cast<Item*>(h + c->tl.off_items);
+    Unit* dunits = reinterpret_cast<Unit*>(h + c->tl.off_dunits);
+    Unit* punits = reinterpret_cast<Unit*>(h + c->tl.off_punits);
+    memset(hdr, 0, sizeof(*hdr));
+    int n_items = 0, n_dunits = 0, n_punits = 0, cu = 0, max_q = 0;
+    TableHost th;
+    th.min_tail_len = cfg.max_tail_tokens;
+    for (int b = 0; b < batch; ++b) {
+        InstanceInfo& in = insts[b];
+        memset(&in, 0, sizeof(in));
+        const int item_begin = n_items;
+        long inst_tokens = 0;
+        // page pieces: even partition of each page in 8-token granules, pieces <= split
+        int local_split = split;
+        for (;;) {
+            long cnt = 1;
+            for (int p = 0; p < n_pages[b]; ++p)
+                cnt += (pages[(size_t)b * cfg.max_pages + p].n_tokens + local_split - 1) / local_split;
+            if (cnt <= kMaxItemsPerInstance) break;
+            local_split *= 2;
+        }
+        for (int p = 0; p < n_pages[b]; ++p) {
+            const matkv_page& pg = pages[(size_t)b * cfg.max_pages + p];
+            const int pieces = (pg.n_tokens + local_split - 1) / local_split;
+            const int granules = (pg.n_tokens + 7) / 8;
+            int g0 = 0;
+            for (int k = 0; k < pieces; ++k) {
+                const int g1 = (int)((long)granules * (k + 1) / pieces);
+                const int t0 = g0 * 8, t1 = g1 * 8 < pg.n_tokens ? g1 * 8 : pg.n_tokens;
+                g0 = g1;
+                if (t1 <= t0) continue;
+                Item& itx = items[n_items++];
+                memset(&itx, 0, sizeof(itx));
+                itx.base = reinterpret_cast<uint64_t>(pg.slot);
+                itx.page_tokens = pg.n_tokens;
+                itx.tok0 = t0;
+                itx.ntok = t1 - t0;
+            }
+            inst_tokens += pg.n_tokens;
+            c->slots[pg.slot].referenced = true;
+        }
+        Item& tail = items[n_items++];
+        memset(&tail, 0, sizeof(tail));
+        tail.base = 0; tail.page_tokens = cfg.max_tail_tokens; tail.tok0 = 0; tail.ntok = cfg.max_tail_tokens;
+        const int count = n_items - item_begin;
+
+        in.pos_base = pos_base ? pos_base[b] : inst_tokens;
+        if (in.pos_base + cfg.max_tail_tokens > (1ll << 24)) return fail(c, MATKV_EINVAL, "assemble: positions beyond 2^24");
+        in.tail_len = q_len[b];
+        in.q_len = q_len[b];
+        in.cu_q = cu;
+        cu += q_len[b];
+        if (q_len[b] > max_q) max_q = q_len[b];
+        if (q_len[b] > th.max_tail_len) th.max_tail_len = q_len[b];
+        if (q_len[b] < th.min_tail_len) th.min_tail_len = q_len[b];
+        // decode: one unit per item
+        in.dunit0 = n_dunits; in.n_dunits = count;
+        for (int k = 0; k < count; ++k) dunits[n_dunits++] = Unit{b, item_begin + k, 1, k};
+        // prefill: runs of items, at most kMaxPrefillUnitsPerInstance per instance
+        const int ipu = (count + kMaxPrefillUnitsPerInstance - 1) / kMaxPrefillUnitsPerInstance;
+        in.punit0 = n_punits; in.n_punits = (count + ipu - 1) / ipu;
+        for (int k = 0, u = 0; k < count; k += ipu, ++u)
+            punits[n_punits++] = Unit{b, item_begin + k, (count - k < ipu ? count - k : ipu), u};
+    }
+    hdr->batch = batch; hdr->n_items = n_items; hdr->n_dunits = n_dunits; hdr->n_punits = n_punits;
+    hdr->total_q = cu; hdr->max_q = max_q;
+
+    char* d = reinterpret_cast<char*>(table);
+    HIP_TRY(c, hipMemcpyAsync(d, h, c->tl.off_inst + sizeof(InstanceInfo) * batch, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d + c->tl.off_items, h + c->tl.off_items, sizeof(Item) * n_items, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d + c->tl.off_dunits, h + c->tl.off_dunits, sizeof(Unit) * n_dunits, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d + c->tl.off_punits, h + c->tl.off_punits, sizeof(Unit) * n_punits, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipEventRecord(sg.ev, c->compute));
+    sg.used = true;
+
+    th.batch = batch; th.n_items = n_items; th.n_dunits = n_dunits; th.n_punits = n_punits;
+    th.total_q = cu; th.max_q = max_q;
+    c->tables[table] = th;
+    return MATKV_OK;
+}
+
+matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    TableHost* th = find_table(c, table);
+    if (!th) return fail(c, MATKV_EINVAL, "advance: table was not built by matkv_assemble");
+    if (n < 1) return fail(c, MATKV_EINVAL, "advance: n=%d", n);
+    if (c->capturing) {
+        c->cap->advances.emplace_back(table, n);
+    } else {
+        if (th->max_tail_len + n > c->cfg.max_tail_tokens)
+            return fail(c, MATKV_EINVAL, "advance: tail would hold %d tokens, max_tail_tokens=%d", th->max_tail_len + n, c->cfg.max_tail_tokens);
+        th->max_tail_len += n; th->min_tail_len += n;
+    }
+    HIP_TRY(c, launch_advance(reinterpret_cast<char*>(table), c->tl.off_inst, th->batch, n, c->cfg.max_tail_tokens, c->compute));
+    return MATKV_OK;
+}
+
+// -------------------------------------------------------------------------------- P / D ----
+
+static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int32_t layer, const void* q,
+                                const void* table, const void* tail_k, const void* tail_v, void* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!q || !table || !tail_k || !tail_v || !out) return fail(c, MATKV_EINVAL, "%s: null pointer", name);
+    if (!aligned16(q) || !aligned16(tail_k) || !aligned16(tail_v) || !aligned16(out))
+        return fail(c, MATKV_EINVAL, "%s: pointers must be 16-byte aligned", name);
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MATKV_EINVAL, "%s: layer %d outside 0..%d", name, layer, c->cfg.n_layers - 1);
+    TableHost* th = find_table(c, table);
+    if (!th) return fail(c, MATKV_EINVAL, "%s: table was not built by matkv_assemble", name);
+    AttnArgs a{};
+    a.q = q; a.out = out; a.tail_k = tail_k; a.tail_v = tail_v;
+    a.table = reinterpret_cast<const char*>(table);
+    a.partials = reinterpret_cast<float*>(c->workspace + c->wl.off_partials);
+    a.counters = reinterpret_cast<int32_t*>(c->workspace + c->wl.off_counters);
+    a.layer = layer; a.n_layers = c->cfg.n_layers;
+    a.Hq = c->cfg.n_q_heads; a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim;
+    a.max_tail = c->cfg.max_tail_tokens;
+    a.prefill = prefill;
+    a.rows = prefill ? th->max_q : 1;
+    a.n_units = prefill ? th->n_punits : th->n_dunits;
+    a.scale_log2e = c->scale_log2e;
+    a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
+    a.off_units = prefill ? c->tl.off_punits : c->tl.off_dunits;
+    HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
+    return MATKV_OK;
+}
+
+matkv_status matkv_prefill_attn(matkv_ctx* c, int32_t layer, const void* q, const void* table,
+                                const void* tail_k, const void* tail_v, void* out) {
+    return attn_common(c, "prefill_attn", 1, layer, q, table, tail_k, tail_v, out);
+}
+
+matkv_status matkv_decode_attn(matkv_ctx* c, int32_t layer, const void* q, const void* table,
+                               const void* tail_k, const void* tail_v, void* out) {
+    return attn_common(c, "decode_attn", 0, layer, q, table, tail_k, tail_v, out);
+}
+
+// -------------------------------------------------------------------------------- graphs ----
+
+matkv_status matkv_graph_begin(matkv_ctx* c) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (c->capturing) return fail(c, MATKV_EBUSY, "graph_begin: a capture is already open");
+    matkv_graph* g = new (std::nothrow) matkv_graph();
+    if (!g) return fail(c, MATKV_ENOMEM, "graph_begin: out of host memory");
+    hipError_t e = hipStreamBeginCapture(c->compute, hipStreamCaptureModeRelaxed);
+    if (e != hipSuccess) { delete g; return hip_fail(c, e, "hipStreamBeginCapture"); }
+    c->capturing = true;
+    c->cap = g;
+    return MATKV_OK;
+}
+
+matkv_status matkv_graph_end(matkv_ctx* c, matkv_graph** out) {
+    if (!c || !out) return MATKV_EINVAL;
+    if (!c->capturing) return fail(c, MATKV_EINVAL, "graph_end: no capture is open");
+    matkv_graph* g = c->cap;
+    c->capturing = false;
+    c->cap = nullptr;
+    hipError_t e = hipStreamEndCapture(c->compute, &g->graph);
+    if (e == hipSuccess) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        delete g;
+        return hip_fail(c, e, "graph_end");
+    }
+    c->graphs.push_back(g);
+    *out = g;
+    return MATKV_OK;
+}
+
+matkv_status matkv_graph_launch(matkv_ctx* c, matkv_graph* g) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!g || !g->exec) return fail(c, MATKV_EINVAL, "graph_launch: null graph");
+    if (c->capturing) return fail(c, MATKV_EBUSY, "graph_launch: a capture is open");
+    // the recorded tail advances must still fit
+    for (auto& adv : g->advances) {
+        TableHost* th = find_table(c, adv.first);
+        if (!th) return fail(c, MATKV_EINVAL, "graph_launch: a recorded table no longer exists");
+        if (th->max_tail_len + adv.second > c->cfg.max_tail_tokens)
+            return fail(c, MATKV_EINVAL, "graph_launch: tail would hold %d tokens, max_tail_tokens=%d", th->max_tail_len + adv.second, c->cfg.max_tail_tokens);
+    }
+    for (auto& adv : g->advances) {
+        TableHost* th = find_table(c, adv.first);
+        th->max_tail_len += adv.second; th->min_tail_len += adv.second;
+    }
+    HIP_TRY(c, hipGraphLaunch(g->exec, c->compute));
+    return MATKV_OK;
+}
+
+matkv_status matkv_graph_destroy(matkv_ctx* c, matkv_graph* g) {
+    if (!c || !g) return MATKV_EINVAL;
+    for (size_t i = 0; i < c->graphs.size(); ++i) {
+        if (c->graphs[i] == g) {
+            (void)hipStreamSynchronize(c->compute);
+            if (g->exec) (void)hipGraphExecDestroy(g->exec);
+            if (g->graph) (void)hipGraphDestroy(g->graph);
+            delete g;
+            c->graphs.erase(c->graphs.begin() + i);
+            return MATKV_OK;
+        }
+    }
+    return fail(c, MATKV_EINVAL, "graph_destroy: unknown graph");
+}
+
+}  // extern "C"

@@ -1,0 +1,149 @@
+// Internal declarations shared by the C-ABI translation unit and the kernel files.
+// Not part of the public boundary (that is include/matkv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "matkv.h"
+
+namespace matkv {
+
+// ---------------------------------------------------------------- cache table (device) ----
+// One table describes the assembled cache of a batch (paper Section IV, put_KV): for each
+// instance its pages cut into work items, then one item for its tail.  Built on the host by
+// matkv_assemble, read by the attention and tail-materialize kernels.
+
+constexpr int kMaxItemsPerInstance = 256;   // page pieces + tail
+constexpr int kMaxPrefillUnitsPerInstance = 32;
+
+struct Item {              // 32 bytes
+    uint64_t base;         // device address of the page's blob; 0 = the instance's tail
+    int32_t page_tokens;   // tokens of the whole page (stride of a head inside the blob)
+    int32_t tok0;          // first token of this piece
+    int32_t ntok;          // tokens of this piece (tail: capacity, clipped by tail_len)
+    int32_t pad[3];
+};
+
+struct Unit {              // 16 bytes: a run of consecutive items of one instance
+    int32_t inst;
+    int32_t item0;         // global item index
+    int32_t n_items;
+    int32_t idx_in_inst;
+};
+
+struct InstanceInfo {      // 48 bytes
+    int64_t pos_base;      // position of tail row 0
+    int32_t tail_len;      // valid tail rows (advanced on the device)
+    int32_t q_len;         // question rows
+    int32_t cu_q;          // first row of this instance in the packed Q / O / hidden
+    int32_t dunit0, n_dunits;   // decode units of this instance (global unit index, count)
+    int32_t punit0, n_punits;   // prefill units
+    int32_t pad[3];
+};
+
+struct TableHeader {       // 64 bytes
+    int32_t batch;
+    int32_t n_items;
+    int32_t n_dunits;
+    int32_t n_punits;
+    int32_t total_q;
+    int32_t max_q;
+    int32_t pad[10];
+};
+
+// Byte offsets of the table's sections, all derived from the configuration.
+struct TableLayout {
+    size_t off_inst, off_items, off_dunits, off_punits, bytes;
+    int max_items, max_dunits, max_punits;
+};
+
+inline TableLayout table_layout(const matkv_config& c) {
+    TableLayout L;
+    L.max_items = c.max_batch * kMaxItemsPerInstance;
+    L.max_dunits = L.max_items;
+    L.max_punits = c.max_batch * kMaxPrefillUnitsPerInstance;
+    size_t o = sizeof(TableHeader);
+    L.off_inst = o;   o += sizeof(InstanceInfo) * (size_t)c.max_batch;
+    o = (o + 63) & ~(size_t)63;
+    L.off_items = o;  o += sizeof(Item) * (size_t)L.max_items;
+    L.off_dunits = o; o += sizeof(Unit) * (size_t)L.max_dunits;
+    L.off_punits = o; o += sizeof(Unit) * (size_t)L.max_punits;
+    L.bytes = (o + 255) & ~(size_t)255;
+    return L;
+}
+
+// ---------------------------------------------------------------- workspace (device) ------
+// [ rope table | counters | partials ]
+struct WorkspaceLayout {
+    size_t off_rope, off_counters, off_partials, bytes;
+    size_t n_counters, partial_floats;
+};
+
+inline int max_q_rows(const matkv_config& c) { return c.max_tail_tokens; }
+
+inline WorkspaceLayout workspace_layout(const matkv_config& c) {
+    WorkspaceLayout W;
+    size_t o = 0;
+    W.off_rope = o;      o += 4096;   // D/2 entries of {double inv_freq; float hi, lo (turns)}
+    W.off_counters = o;
+    W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)max_q_rows(c);
+    o += ((W.n_counters * sizeof(int32_t)) + 255) & ~(size_t)255;
+    W.off_partials = o;
+    size_t stride = (size_t)c.n_q_heads * (c.head_dim + 2);
+    size_t dec = (size_t)c.max_batch * kMaxItemsPerInstance * stride;
+    size_t pre = (size_t)c.max_batch * kMaxPrefillUnitsPerInstance * (size_t)max_q_rows(c) * stride;
+    W.partial_floats = dec > pre ? dec : pre;
+    o += W.partial_floats * sizeof(float);
+    W.bytes = (o + 255) & ~(size_t)255;
+    return W;
+}
+
+struct RopeEntry {         // 16 bytes, one per pair j < D/2
+    double inv_freq;       // base^(-2j/D)                       (fp32 path: angle in fp64)
+    float turns_hi;        // inv_freq / (2 pi), split hi + lo   (bf16 path: fp32 in turns)
+    float turns_lo;
+};
+
+// ---------------------------------------------------------------- kernel launchers ---------
+struct AttnArgs {
+    const void* q;
+    void* out;
+    const void* tail_k;
+    const void* tail_v;
+    const char* table;         // device table
+    float* partials;
+    int32_t* counters;
+    int32_t layer, n_layers;
+    int32_t Hq, Hkv, D;
+    int32_t max_tail;
+    int32_t rows;              // 1 = decode; > 1 = prefill rows (grid.z)
+    int32_t n_units;           // grid.x
+    int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail
+    float scale_log2e;
+    size_t off_inst, off_items, off_units;
+};
+
+hipError_t launch_attn_rows(const AttnArgs& a, int dtype, hipStream_t s);
+
+struct MaterializeArgs {
+    const void* hidden;
+    const void* w_k;
+    const void* w_v;
+    void* k_out;
+    void* v_out;
+    const RopeEntry* rope;
+    const char* table;          // tail form only, else nullptr
+    size_t off_inst;
+    int64_t pos0;
+    int64_t token_stride;       // rows between heads in the destination
+    int32_t n_tokens;           // direct form: rows; tail form: upper bound on total rows
+    int32_t rows_per_instance;  // tail form: <0 ragged question rows, >0 uniform newest rows
+    int32_t batch;              // tail form
+    int32_t Hkv, D, Hd;
+};
+
+hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s);
+
+}  // namespace matkv

@@ -1,0 +1,73 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, and its pure size arithmetic is right.  No compute call is made here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mk():
+    from paper_2512_22195_amd import LIB_PATH, build
+    if not os.path.exists(LIB_PATH):
+        build()
+    from paper_2512_22195_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(mk):
+    header = open(os.path.join(ROOT, "include", "matkv.h")).read()
+    declared = set(re.findall(r"\b(matkv_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found in include/matkv.h"
+    assert declared == set(mk.EXPORTS), declared ^ set(mk.EXPORTS)
+    for name in declared:
+        assert hasattr(mk.lib(), name), f"libmatkv.so does not export {name}"
+
+
+def test_blob_bytes_formula_and_paper_orders_of_magnitude(mk):
+    """n_layers * 2 * Hkv * n_tokens * D * 2 bytes.  The paper (Section II-C) quotes about
+    100 MB per 1000 tokens for a 3B LLaMA and BASELINE's stream config about 1.3 GB for ten
+    1000-token chunks of the 8B shape."""
+    c8 = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, 1, 10, 192)
+    assert mk.blob_bytes(c8, 1000) == 32 * 2 * 8 * 1000 * 128 * 2 == 131_072_000
+    assert abs(10 * mk.blob_bytes(c8, 1000) / 1e9 - 1.3) < 0.02
+    # 3B shape: 28 layers, 8 KV heads, D 128 (its 24 query heads, group 3, do not enter the size)
+    c3 = mk.make_config(28, 8, 8, 128, 3072, "bf16", 500000.0, 1, 10, 192)
+    mb = mk.blob_bytes(c3, 1000) / 1e6
+    assert mb == pytest.approx(114.688) and 80 < mb < 130      # "approximately 100 MB"
+    c70 = mk.make_config(80, 64, 8, 128, 8192, "bf16", 500000.0, 4, 20, 384)
+    assert mk.blob_bytes(c70, 1000) == 327_680_000
+    c1 = mk.make_config(1, 4, 2, 64, 256, "f32", 10000.0, 1, 2, 40)
+    assert mk.blob_bytes(c1, 256) == 262_144
+    assert mk.tail_bytes(c1) == 1 * 2 * 40 * 64 * 4
+    assert mk.blob_bytes(c1, -1) == 0
+
+
+def test_config_check_rejects_what_is_not_built(mk):
+    ok = dict(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, hidden=256, dtype="f32",
+              rope_base=10000.0, max_batch=1, max_pages=2, max_tail_tokens=40)
+    assert mk.config_check(mk.make_config(**ok)) == mk.OK
+    bad = [dict(head_dim=96), dict(n_q_heads=6, n_kv_heads=4), dict(n_q_heads=32, n_kv_heads=2),
+           dict(hidden=100), dict(max_tail_tokens=41), dict(n_layers=0), dict(rope_base=1.0),
+           dict(split_tokens=12), dict(max_batch=0)]
+    for delta in bad:
+        cfg = mk.make_config(**{**ok, **delta})
+        assert mk.config_check(cfg) in (mk.EINVAL, mk.EUNSUPPORTED), delta
+        assert mk.workspace_bytes(cfg) == 0 and mk.table_bytes(cfg) == 0
+    assert mk.config_check(mk.make_config(**{**ok, "head_dim": 96})) == mk.EUNSUPPORTED
+    assert mk.lib().matkv_status_string(3) == b"MATKV_ENOTREADY"
+
+
+def test_workspace_and_table_sizes_are_positive_and_aligned(mk):
+    c = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, 16, 5, 192)
+    assert mk.workspace_bytes(c) % 256 == 0 and mk.workspace_bytes(c) > 0
+    assert mk.table_bytes(c) % 256 == 0 and mk.table_bytes(c) > 0
+
+
+def test_null_context_is_an_error_not_a_crash(mk):
+    assert mk.lib().matkv_destroy(None) == mk.EINVAL
+    assert mk.lib().matkv_advance(None, None, 1) == mk.EINVAL
+    assert mk.lib().matkv_last_error(None) == b"context is null"

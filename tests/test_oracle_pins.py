@@ -294,3 +294,20 @@ def test_decode_row_equals_prefill_row():
 
 def test_oracle_reports_threads():
     assert oracle.threads() >= 1
+
+
+# --------------------------------------------------------------------------- storage rounding
+def test_store_round_bf16_is_round_to_nearest_even():
+    from oracle.matkv_oracle import store_round
+    # representable values stay; exact ties go to the even neighbour; sign symmetric
+    x = np.array([1.0, 1.0 + 2 ** -7, -3.5, 0.0, 2.0 ** -20])
+    np.testing.assert_array_equal(store_round(x, "bf16"), x)
+    ties = np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -(1.0 + 2 ** -8), 2.0 - 2 ** -8])
+    np.testing.assert_array_equal(store_round(ties, "bf16"), [1.0, 1.0 + 2 ** -6, -1.0, 2.0])
+    # just above a tie goes up even though a first rounding to fp32 would land on the tie
+    np.testing.assert_array_equal(store_round(np.array([1.0 + 2 ** -8 + 2 ** -40]), "bf16"), [1.0 + 2 ** -7])
+    a = RNG.standard_normal(10000) * 3
+    r = store_round(a, "bf16")
+    assert (np.abs(r - a) <= 2.0 ** -8 * np.abs(a)).all()    # half an ulp: unit roundoff 2^-8
+    assert ((r.view(np.uint64) & np.uint64((1 << 45) - 1)) == 0).all()           # 7 mantissa bits
+    np.testing.assert_array_equal(store_round(a, "f32"), a.astype(np.float32).astype(np.float64))
