@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the MatKV hot path on one MI355X.
+
+A "step" is one pass of the whole path over one RAG instance batch with its chunk KVs already
+resident in HBM: cache assembly, K/V materialization of the question tokens + prefill attention
+for every layer, then every decode step (K/V materialization of the new token + decode
+attention for every layer, replayed from one captured graph).  ``value`` is generated tokens
+per second over that pass.  Beside it: the decode-attention kernel's achieved HBM bandwidth
+(``roofline``), the pinned-host-to-HBM load rate of the instance's blobs (``kv_load``, never
+part of ``value``), and the fp64 oracle timed on the host cores (``cpu_baseline``).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--split N] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE.json config number (1-based)")
+    ap.add_argument("--split", type=int, default=0, help="tokens per decode work item (0 = library's choice)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
+    ap.add_argument("--decode-only-reps", type=int, default=20)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus above 1 is not supported "
+              "(no collective or sharded path exists in this library).", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2512_22195_amd import binding as mk
+    from workload import CONFIGS, normal, question_lengths, retrieved_chunks
+
+    shape = CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = shape.torch_dtype
+    B, nl, Hq, Hkv, D, Hd = shape.batch, shape.n_layers, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.hidden
+    L = shape.chunk_tokens
+    q_lens = question_lengths(shape)
+    retrieved = retrieved_chunks(shape)
+    chunk_ids = sorted({c for r in retrieved for c in r})
+    max_tail = (max(q_lens) + shape.decode_steps + 7) // 8 * 8
+    steps_dec = shape.decode_steps
+
+    cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B,
+                         max_pages=shape.n_chunks, max_tail_tokens=max_tail, split_tokens=args.split)
+    ctx = mk.Context(cfg, device=dev)
+    cs = ctx.compute_stream
+    vs = shape.value_scale
+
+    # ---------------------------------------------------------------- synthetic inputs -----
+    with torch.cuda.stream(cs):
+        slots = {cid: normal((shape.name, "blob", cid), (nl, 2, Hkv, L, D), vs, tdt, dev) for cid in chunk_ids}
+        w = normal((shape.name, "w"), (nl, 2, Hkv * D, Hd), vs, tdt, dev)
+        total_q = sum(q_lens)
+        x_q = normal((shape.name, "x_q"), (nl, total_q, Hd), vs, tdt, dev)
+        x_dec = normal((shape.name, "x_dec"), (nl, B, Hd), vs, tdt, dev)      # reused every step
+        q_pre = normal((shape.name, "q_pre"), (nl, total_q, Hq, D), vs, tdt, dev)
+        q_dec = normal((shape.name, "q_dec"), (nl, B, Hq, D), vs, tdt, dev)
+        o_pre = torch.empty_like(q_pre)
+        o_dec = torch.empty_like(q_dec)
+        tail = ctx.new_tail()
+        table = ctx.new_table()
+        pages = [[(slots[cid], L) for cid in r] for r in retrieved]
+    cs.synchronize()
+
+    def prefill_phase():
+        ctx.assemble(pages, q_lens, table)
+        for l in range(nl):
+            ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
+            ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+
+    # one decode step of all layers, recorded once, replayed for every step
+    with torch.cuda.stream(cs):
+        ctx.assemble(pages, q_lens, table)
+        ctx.graph_begin()
+        ctx.advance(table, 1)
+        for l in range(nl):
+            ctx.materialize_tail(x_dec[l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
+            ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+        g_step = ctx.graph_end()
+        ctx.graph_begin()
+        for l in range(nl):
+            ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+        g_attn = ctx.graph_end()
+
+    def one_pass():
+        prefill_phase()
+        for _ in range(steps_dec):
+            ctx.graph_launch(g_step)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(cs):
+        for _ in range(args.warmup):
+            one_pass()
+        cs.synchronize()
+        torch.cuda.synchronize()
+        e0, e1, e2 = [], [], []
+        t_wall0 = time.perf_counter()
+        for _ in range(args.steps):
+            a, b, c = ev(), ev(), ev()
+            a.record(cs)
+            prefill_phase()
+            b.record(cs)
+            for _ in range(steps_dec):
+                ctx.graph_launch(g_step)
+            c.record(cs)
+            e0.append(a); e1.append(b); e2.append(c)
+        cs.synchronize()
+        torch.cuda.synchronize()
+        t_wall = time.perf_counter() - t_wall0
+    ms_prefill = sum(a.elapsed_time(b) for a, b in zip(e0, e1)) / args.steps
+    ms_decode = sum(b.elapsed_time(c) for b, c in zip(e1, e2)) / args.steps
+    ms_step = t_wall * 1e3 / args.steps
+    tokens_per_s = B * steps_dec / (ms_step * 1e-3)
+
+    # ------------------------------------------------- roofline of the dominant kernel (D) ---
+    # decode attention alone, all layers back to back (working set = every layer's KV, far
+    # beyond the last-level cache), tail at its mid-run length
+    mid_tail = [q + steps_dec // 2 for q in q_lens]
+    with torch.cuda.stream(cs):
+        ctx.assemble(pages, q_lens, table)
+        ctx.advance(table, steps_dec // 2)
+        for _ in range(3):
+            ctx.graph_launch(g_attn)
+        a, b = ev(), ev()
+        a.record(cs)
+        for _ in range(args.decode_only_reps):
+            ctx.graph_launch(g_attn)
+        b.record(cs)
+        cs.synchronize()
+    us_per_launch = a.elapsed_time(b) * 1e3 / (args.decode_only_reps * nl)
+    kv_tok_bytes = shape.kv_bytes_per_token_layer()
+    n_ctx = [sum(L for _ in r) for r in retrieved]
+    bytes_per_launch = sum((n + t) * kv_tok_bytes for n, t in zip(n_ctx, mid_tail)) + 2 * B * Hq * D * shape.elem_bytes
+    achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "attn_rows_kernel (matkv_decode_attn)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3)}
+
+    # ---------------------------------------------------------- KV load (never in value) -----
+    kv_load = None
+    if not args.no_load:
+        inst_chunks = retrieved[0]
+        nbytes = mk.blob_bytes(cfg, L)
+        host = [torch.empty(nbytes, dtype=torch.uint8).pin_memory() for _ in inst_chunks]
+        for h, cid in zip(host, inst_chunks):
+            h.copy_(slots[cid].view(torch.uint8).reshape(-1))
+        dst = [ctx.new_slot(L) for _ in inst_chunks]
+        torch.cuda.synchronize()
+        best = None
+        for rep in range(3):
+            t0 = time.perf_counter()
+            tickets = [ctx.load(h, L, d) for h, d in zip(host, dst)]
+            ctx.sync(tickets[-1])
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        ok = all(torch.equal(d.cpu(), h) for d, h in zip(dst[:1], host[:1]))
+        kv_load = {"GBps": round(len(host) * nbytes / best / 1e9, 2), "ms_per_instance": round(best * 1e3, 3),
+                   "bytes": len(host) * nbytes, "chunks": len(host), "byte_exact": bool(ok)}
+        del host, dst
+
+    # ------------------------------------------------------------------------ cpu_baseline ---
+    cpu = None
+    if not args.no_cpu:
+        import numpy as np
+        import oracle
+        from workload import to_f64
+        # bounded sample of the same workload: instance 0, layers {0, nl/2, nl-1}: the K/V
+        # projection of one new token and its decode attention at the mid-run tail length
+        b0 = 0
+        layers = sorted({0, nl // 2, nl - 1})
+        cs.synchronize()
+        chunks = {l: [(to_f64(slots[cid][l, 0]), to_f64(slots[cid][l, 1])) for cid in retrieved[b0]] for l in layers}
+        n_t = mid_tail[b0]
+        tails = {l: (to_f64(tail[l, 0, b0, :, :n_t]), to_f64(tail[l, 1, b0, :, :n_t])) for l in layers}
+        wk = {l: (to_f64(w[l, 0]), to_f64(w[l, 1])) for l in layers}
+        xs = {l: to_f64(x_dec[l, b0:b0 + 1]) for l in layers}
+        qs = {l: to_f64(q_dec[l, b0]) for l in layers}
+        reps, t_cpu = 0, 0.0
+        t_begin = time.perf_counter()
+        while t_cpu < 10.0 and reps < 50:
+            for l in layers:
+                t0 = time.perf_counter()
+                oracle.materialize(xs[l], wk[l][0], wk[l][1], Hkv, D, float(n_ctx[b0] + n_t - 1), shape.rope_base)
+                oracle.decode_attn(qs[l], chunks[l], tails[l][0], tails[l][1])
+                t_cpu += time.perf_counter() - t0
+            reps += 1
+        per_layer_step = t_cpu / (reps * len(layers))
+        cpu_tok_s = 1.0 / (per_layer_step * nl)          # one instance: B tokens need B times this
+        cpu = {"value": round(cpu_tok_s / 1.0, 4), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"instance 0, layers {layers}, decode token at tail length {n_t}: K/V projection + decode "
+                         f"attention, {reps} repetitions, {t_cpu:.1f} s of oracle time; tokens/s extrapolated "
+                         f"linearly to {nl} layers (prefill not included)",
+               "seconds_per_layer_step": round(per_layer_step, 5)}
+
+    out = {
+        "metric": "tokens/s over loaded KV (decode-attn HBM GB/s and % of peak in roofline; KV load GB/s in kv_load)",
+        "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"BASELINE config {args.config}: {shape.name}, {B} instance(s) x {shape.n_chunks} chunks x "
+                               f"{L} tokens, {nl} layers, Hq {Hq} / Hkv {Hkv} / D {D}, question {q_lens if B > 1 else q_lens[0]} "
+                               f"tokens, {steps_dec} decode steps",
+                   "batch": B, "cached_tokens": n_ctx if B > 1 else n_ctx[0], "split_tokens": args.split},
+        "phases_ms": {"assemble+materialize+prefill": round(ms_prefill, 3), "decode": round(ms_decode, 3),
+                      "decode_us_per_layer_step": round(ms_decode * 1e3 / (steps_dec * nl), 3)},
+        "roofline": roofline, "kv_load": kv_load, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    ctx.graph_destroy(g_step)
+    ctx.graph_destroy(g_attn)
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
