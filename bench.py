@@ -9,7 +9,7 @@ per second over that pass.  Beside it: the decode-attention kernel's achieved HB
 (``roofline``), the pinned-host-to-HBM load rate of the instance's blobs (``kv_load``, never
 part of ``value``), and the fp64 oracle timed on the host cores (``cpu_baseline``).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--split N] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--units N] [--variant V] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -32,7 +32,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json config number (1-based)")
-    ap.add_argument("--split", type=int, default=0, help="tokens per decode work item (0 = library's choice)")
+    ap.add_argument("--units", type=int, default=0, help="decode workgroups per (instance, KV head); 0 = library's choice")
+    ap.add_argument("--variant", type=int, default=0, help="decode kernel shape (waves*100 + loads in flight); 0 = default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
     ap.add_argument("--decode-only-reps", type=int, default=20)
@@ -63,7 +64,8 @@ def main():
     steps_dec = shape.decode_steps
 
     cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B,
-                         max_pages=shape.n_chunks, max_tail_tokens=max_tail, split_tokens=args.split)
+                         max_pages=shape.n_chunks, max_tail_tokens=max_tail, decode_units=args.units,
+                         decode_variant=args.variant)
     ctx = mk.Context(cfg, device=dev)
     cs = ctx.compute_stream
     vs = shape.value_scale
@@ -224,7 +226,7 @@ def main():
         "config": {"workload": f"BASELINE config {args.config}: {shape.name}, {B} instance(s) x {shape.n_chunks} chunks x "
                                f"{L} tokens, {nl} layers, Hq {Hq} / Hkv {Hkv} / D {D}, question {q_lens if B > 1 else q_lens[0]} "
                                f"tokens, {steps_dec} decode steps",
-                   "batch": B, "cached_tokens": n_ctx if B > 1 else n_ctx[0], "split_tokens": args.split},
+                   "batch": B, "cached_tokens": n_ctx if B > 1 else n_ctx[0], "decode_units": args.units, "decode_variant": args.variant},
         "phases_ms": {"assemble+materialize+prefill": round(ms_prefill, 3), "decode": round(ms_decode, 3),
                       "decode_us_per_layer_step": round(ms_decode * 1e3 / (steps_dec * nl), 3)},
         "roofline": roofline, "kv_load": kv_load, "cpu_baseline": cpu,

@@ -2,12 +2,14 @@
 // Section V-A "decode time"; also the plain-FMA form of the question prefill).
 //
 // No matrix cores: one row against N keys is a bandwidth problem.  A workgroup streams the
-// K rows, then the V rows, of its work unit (a run of page pieces, or the tail) for ONE KV
-// head from HBM with 16-byte loads, serves all G = Hq/Hkv query heads of that KV head from
-// the same registers, and keeps a running (max, sum, accumulator) per head.  Lanes that share
-// a token reduce their partial dot products with DPP adds inside a 16-lane row.  Units of one
-// (instance, KV head, row) are merged by the last workgroup to arrive (atomic ticket), so a
-// layer's attention is one launch.
+// K rows and the V rows of its work unit (page pieces and/or the tail) for ONE KV head from
+// HBM with 16-byte loads, serves all G = Hq/Hkv query heads of that KV head from the same
+// registers, and keeps a running (max, sum, accumulator) per head.  Lanes that share a token
+// reduce their partial dot products with DPP adds inside a 16-lane row.  The next block's
+// loads are issued before the current block is consumed.  Units of one (instance, KV head,
+// row) are merged by the last workgroup to arrive (atomic ticket), so a layer's attention is
+// one launch; partials travel through agent-scope (cache-bypassing) accesses, which keeps
+// the chip's separate L2 slices coherent without flushing them.
 #include "matkv_internal.h"
 
 namespace matkv {
@@ -15,12 +17,13 @@ namespace {
 
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet": finite, so that exp2(m - m) = 1
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 template <typename T> struct ElemTraits;
 template <> struct ElemTraits<float> { static constexpr int kPerLoad = 4; };
 template <> struct ElemTraits<uint16_t> { static constexpr int kPerLoad = 8; };   // bf16 bits
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -28,21 +31,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
-
-// 16 bytes -> kPerLoad floats
-template <typename T> struct Vec16;
-template <> struct Vec16<float> {
-    static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
-        f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
-    }
-};
-template <> struct Vec16<uint16_t> {
-    static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-        f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
-        f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
-    }
-};
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v) {
@@ -62,46 +50,184 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// Value of the lane whose index differs in bit log2(off); off in {32, 16, 8}.
+__device__ __forceinline__ float lane_xor(float v, int off, int lane) {
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    const unsigned x = __float_as_uint(v);
+    if (off == 32) {
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return __uint_as_float((lane & 32) ? r.x : r.y);
+    }
+    if (off == 16) {
+        const u32x2 r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return __uint_as_float((lane & 16) ? r.x : r.y);
+    }
+    return __shfl_xor(v, off);
+}
+
+// 16-byte load through the global address space (a pointer rebuilt from an integer would
+// otherwise be treated as generic and loaded with the slower flat instructions).
+__device__ __forceinline__ uint4 ldg16(const void* p) {
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+    const u32x4 r = *(gptr)(uintptr_t)p;
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+// Agent-scope relaxed accesses: coherent across the chip's L2 slices without cache flushes.
+__device__ __forceinline__ void st_agent2(float* p, float x, float y) {
+    const uint64_t v = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float* p) {
+    const uint64_t r = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
+}
+
+// ---- per-element-type arithmetic on one 16-byte piece of a K or V row -----------------------
+// Q is kept in the form the dot product wants: fp32 for the fp32 path, packed bf16 pairs for
+// the bf16 path (exact: Q arrives as bf16), where v_dot2_f32_bf16 does two multiply-adds per
+// lane and instruction with an fp32 accumulator.
+template <typename T> struct RowMath;
+
+template <> struct RowMath<float> {
+    static constexpr int QREGS = 4;
+    typedef float qreg_t;
+    static __device__ __forceinline__ void load_q(const uint4& raw, qreg_t* q) {
+        q[0] = __uint_as_float(raw.x); q[1] = __uint_as_float(raw.y);
+        q[2] = __uint_as_float(raw.z); q[3] = __uint_as_float(raw.w);
+    }
+    static __device__ __forceinline__ float dot(const qreg_t* q, const uint4& k) {
+        float d = q[0] * __uint_as_float(k.x);
+        d = fmaf(q[1], __uint_as_float(k.y), d);
+        d = fmaf(q[2], __uint_as_float(k.z), d);
+        d = fmaf(q[3], __uint_as_float(k.w), d);
+        return d;
+    }
+};
+
+template <> struct RowMath<uint16_t> {
+    static constexpr int QREGS = 4;
+    typedef uint32_t qreg_t;
+    static __device__ __forceinline__ void load_q(const uint4& raw, qreg_t* q) {
+        q[0] = raw.x; q[1] = raw.y; q[2] = raw.z; q[3] = raw.w;
+    }
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+    }
+    static __device__ __forceinline__ float dot(const qreg_t* q, const uint4& k) {
+        float d = dot2(q[0], k.x, 0.f);
+        d = dot2(q[1], k.y, d);
+        d = dot2(q[2], k.z, d);
+        d = dot2(q[3], k.w, d);
+        return d;
+    }
+};
+
+// acc[g][e] += sum_u p[u][g] * v[u][e]
+template <typename T, int G, int U> struct PV;
+
+template <int G, int U> struct PV<float, G, U> {
+    static __device__ __forceinline__ void run(const uint4* vraw, const float (*p)[G], float (*acc)[4]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float vf[4] = {__uint_as_float(vraw[u].x), __uint_as_float(vraw[u].y),
+                                 __uint_as_float(vraw[u].z), __uint_as_float(vraw[u].w)};
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[g][e] = fmaf(p[u][g], vf[e], acc[g][e]);
+        }
+    }
+};
+
+// bf16: two tokens at a time.  The two rows' elements are interleaved with byte permutes into
+// (token u, token u+1) pairs per element, the two probabilities are rounded to one bf16 pair,
+// and one dot2 per (head, element) adds both tokens.
+template <int G, int U> struct PV<uint16_t, G, U> {
+    static_assert(U % 2 == 0, "tokens are consumed in pairs");
+    static __device__ __forceinline__ void run(const uint4* vraw, const float (*p)[G], float (*acc)[8]) {
+#pragma unroll
+        for (int u = 0; u < U; u += 2) {
+            const uint32_t a[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
+            const uint32_t b[4] = {vraw[u + 1].x, vraw[u + 1].y, vraw[u + 1].z, vraw[u + 1].w};
+            uint32_t ev[4], od[4];     // element 2w of both tokens, element 2w+1 of both tokens
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                ev[w] = __builtin_amdgcn_perm(b[w], a[w], 0x05040100u);   // {a.lo, b.lo}
+                od[w] = __builtin_amdgcn_perm(b[w], a[w], 0x07060302u);   // {a.hi, b.hi}
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const f32x2 pf = {p[u][g], p[u + 1][g]};
+                const uint32_t pp = __builtin_bit_cast(uint32_t, __builtin_convertvector(pf, bf16x2));
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    acc[g][2 * w] = RowMath<uint16_t>::dot2(pp, ev[w], acc[g][2 * w]);
+                    acc[g][2 * w + 1] = RowMath<uint16_t>::dot2(pp, od[w], acc[g][2 * w + 1]);
+                }
+            }
+        }
+    }
+};
+
+struct KernelArgs {
+    const void* __restrict__ q;
+    void* __restrict__ out;
+    const void* __restrict__ tail_k;
+    const void* __restrict__ tail_v;
+    float* __restrict__ partials;
+    int32_t* __restrict__ counters;
+    int32_t layer, Hq, Hkv, max_tail, rows, prefill;
+    float scale_log2e;
+};
+
+// Where a wave's next block of BLK token rows lives.
+template <typename T>
+struct BlockRef {
+    const T* k;      // row 0 of the item's K stream for this head
+    const T* v;
+    int t0;          // first token row of the block
+    int tok_end;     // one past the item's last valid row
+    bool valid;
+};
+
 template <typename T, int D, int G, int NW, int U>
-__global__ __launch_bounds__(NW * 64) void attn_rows_kernel(AttnArgs a) {
+__global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
+        KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
+        const Unit* __restrict__ units) {
     constexpr int EPL = ElemTraits<T>::kPerLoad;        // elements per 16-byte load
     constexpr int LPT = D / EPL;                        // lanes that share one token row
     constexpr int TPW = 64 / LPT;                       // token rows per wave-wide load
-    constexpr int PSTRIDE = D + 2;                      // floats of one partial: acc, m, l
+    constexpr int BLK = TPW * U;                        // token rows one wave handles per step
+    constexpr int NT = NW * 64;
+    constexpr int PSTRIDE = D + 4;                      // floats of one partial row
+    typedef RowMath<T> RM;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps the block walk scalar
+    const int lane = tid & 63;
     const int grp = lane / LPT, sub = lane % LPT;
     const int kvh = blockIdx.y, row = blockIdx.z;
 
-    const InstanceInfo* insts = reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst);
-    const Item* items = reinterpret_cast<const Item*>(a.table + a.off_items);
-    const Unit unit = reinterpret_cast<const Unit*>(a.table + a.off_units)[blockIdx.x];
-    const InstanceInfo inst = insts[unit.inst];
+    const Unit unit = units[blockIdx.x];
 
-    int q_row, tail_visible, n_units_inst, unit0_inst;
+    int q_row, tail_visible = 0;
     if (a.prefill) {
+        const InstanceInfo inst = insts[unit.inst];
         if (row >= inst.q_len) return;                  // whole workgroup leaves together
         q_row = inst.cu_q + row;
         tail_visible = row + 1;
-        n_units_inst = inst.n_punits; unit0_inst = inst.punit0;
     } else {
         q_row = unit.inst;
-        tail_visible = inst.tail_len;
-        n_units_inst = inst.n_dunits; unit0_inst = inst.dunit0;
+        if (unit.has_tail) tail_visible = insts[unit.inst].tail_len;
     }
 
-    // This lane's slice of the G query vectors, scaled so that exp2 can be used.
-    float qf[G][EPL];
+    // This lane's slice of the G query vectors.
+    typename RM::qreg_t qr[G][RM::QREGS];
     {
         const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G) * D + sub * EPL;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint4 raw = *reinterpret_cast<const uint4*>(qp + (size_t)g * D);
-            Vec16<T>::unpack(raw, qf[g]);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) qf[g][e] *= a.scale_log2e;
-        }
+        for (int g = 0; g < G; ++g) RM::load_q(ldg16(qp + (size_t)g * D), qr[g]);
     }
 
     float m[G], l[G], acc[G][EPL];
@@ -112,101 +238,129 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(AttnArgs a) {
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    for (int it = 0; it < unit.n_items; ++it) {
-        const Item item = items[unit.item0 + it];
-        const T* kbase;
-        const T* vbase;
-        int tok_end = item.tok0 + item.ntok;
+    // The unit's items, end to end, form one run of token rows (the tail clipped to what this
+    // row may see).  Each wave takes an equal contiguous share of it, rounded to whole
+    // wave-loads, and walks it in blocks of up to BLK rows that never straddle two items.
+    int total = unit.page_tokens;
+    if (unit.has_tail) total += min(a.max_tail, tail_visible);
+    const int share = ((total + NW - 1) / NW + TPW - 1) / TPW * TPW;
+    int pos = wave * share;                               // next row of this wave, in run coordinates
+    const int pos_end = min(total, pos + share);
+    Item item = unit.first;
+    int item_i = 0, item_pos0 = 0;                        // run coordinate of the item's first row
+    auto item_rows = [&](const Item& it) { return it.base ? it.ntok : min(it.ntok, tail_visible); };
+    auto next_block = [&]() -> BlockRef<T> {
+        BlockRef<T> r;
+        r.valid = false; r.k = nullptr; r.v = nullptr; r.t0 = 0; r.tok_end = 0;
+        if (pos >= pos_end) return r;
+        int rows = item_rows(item);
+        while (pos >= item_pos0 + rows) {
+            item_pos0 += rows;
+            if (++item_i >= unit.n_items) return r;
+            item = items[unit.item0 + item_i];
+            rows = item_rows(item);
+        }
         if (item.base) {
             const size_t head_elems = (size_t)item.page_tokens * D;
             const T* blob = reinterpret_cast<const T*>(item.base);
-            kbase = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
-            vbase = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
         } else {
             const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
-            kbase = reinterpret_cast<const T*>(a.tail_k) + off;
-            vbase = reinterpret_cast<const T*>(a.tail_v) + off;
-            tok_end = min(tok_end, tail_visible);
+            r.k = reinterpret_cast<const T*>(a.tail_k) + off;
+            r.v = reinterpret_cast<const T*>(a.tail_v) + off;
         }
-        for (int t0 = item.tok0 + wave * (TPW * U); t0 < tok_end; t0 += NW * TPW * U) {
-            uint4 kraw[U], vraw[U];
-            bool ok[U];
+        const int in_item = pos - item_pos0;
+        const int n = min(BLK, min(rows - in_item, pos_end - pos));
+        r.t0 = item.tok0 + in_item;
+        r.tok_end = r.t0 + n;
+        r.valid = true;
+        pos += n;
+        return r;
+    };
+    // Rows past the end are clamped to the last valid row (a cached re-read, no extra HBM
+    // traffic) and masked later, so all 2*U loads issue back to back without branches.
+    auto issue = [&](const BlockRef<T>& r, uint4* kraw, uint4* vraw) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int tok = t0 + u * TPW + grp;
-                ok[u] = tok < tok_end;
-                const size_t eoff = (size_t)tok * D + sub * EPL;
-                kraw[u] = ok[u] ? *reinterpret_cast<const uint4*>(kbase + eoff) : make_uint4(0, 0, 0, 0);
-            }
+        for (int u = 0; u < U; ++u) {
+            const size_t eoff = (size_t)min(r.t0 + u * TPW + grp, r.tok_end - 1) * D + sub * EPL;
+            kraw[u] = ldg16(r.k + eoff);
+        }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int tok = t0 + u * TPW + grp;
-                const size_t eoff = (size_t)tok * D + sub * EPL;
-                vraw[u] = ok[u] ? *reinterpret_cast<const uint4*>(vbase + eoff) : make_uint4(0, 0, 0, 0);
-            }
-            float s[U][G];
+        for (int u = 0; u < U; ++u) {
+            const size_t eoff = (size_t)min(r.t0 + u * TPW + grp, r.tok_end - 1) * D + sub * EPL;
+            vraw[u] = ldg16(r.v + eoff);
+        }
+    };
+    auto consume = [&](const BlockRef<T>& r, const uint4* kraw, const uint4* vraw) {
+        float s[U][G];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float kf[EPL];
-                Vec16<T>::unpack(kraw[u], kf);
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float d = 0.f;
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
-                    d = group_sum<LPT>(d);
-                    s[u][g] = ok[u] ? d : kNegBig;
-                }
-            }
+        for (int u = 0; u < U; ++u) {
+            const bool ok = r.t0 + u * TPW + grp < r.tok_end;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                float mn = m[g];
-#pragma unroll
-                for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][g]);
-                const float alpha = exp2f(m[g] - mn);
-                m[g] = mn;
-                float psum = 0.f;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    s[u][g] = ok[u] ? exp2f(s[u][g] - mn) : 0.f;
-                    psum += s[u][g];
-                }
-                l[g] = l[g] * alpha + psum;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+                const float d = group_sum<LPT>(RM::dot(qr[g], kraw[u]));
+                s[u][g] = ok ? d * a.scale_log2e : kNegBig;
             }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float mn = m[g];
+#pragma unroll
+            for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][g]);
+            const float alpha = exp2f(m[g] - mn);
+            m[g] = mn;
+            float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                float vf[EPL];
-                Vec16<T>::unpack(vraw[u], vf);
-#pragma unroll
-                for (int g = 0; g < G; ++g)
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(s[u][g], vf[e], acc[g][e]);
+                const bool ok = r.t0 + u * TPW + grp < r.tok_end;
+                s[u][g] = ok ? exp2f(s[u][g] - mn) : 0.f;
+                psum += s[u][g];
             }
+            l[g] = l[g] * alpha + psum;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+        }
+        PV<T, G, U>::run(vraw, s, acc);
+    };
+
+    {
+        uint4 k0[U], v0[U], k1[U], v1[U];
+        BlockRef<T> r0 = next_block(), r1;
+        if (r0.valid) issue(r0, k0, v0);
+        while (r0.valid) {
+            r1 = next_block();
+            if (r1.valid) issue(r1, k1, v1);
+            consume(r0, k0, v0);
+            if (!r1.valid) break;
+            r0 = next_block();
+            if (r0.valid) issue(r0, k0, v0);
+            consume(r1, k1, v1);
         }
     }
 
     // ---- merge the TPW token groups of the wave (each kept its own running state) ----
+    // Lane exchanges at distance 32 and 16 are register swaps on this chip; distance 8 (only
+    // when a row holds two tokens) goes through the LDS crossbar.
 #pragma unroll
-    for (int off = LPT; off < 64; off <<= 1) {
+    for (int off = 32; off >= LPT; off >>= 1) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float mo = __shfl_xor(m[g], off);
-            const float lo = __shfl_xor(l[g], off);
+            const float mo = lane_xor(m[g], off, lane);
+            const float lo = lane_xor(l[g], off, lane);
             const float mn = fmaxf(m[g], mo);
             const float ca = exp2f(m[g] - mn), cb = exp2f(mo - mn);
             l[g] = l[g] * ca + lo * cb;
             m[g] = mn;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
-                const float ao = __shfl_xor(acc[g][e], off);
+                const float ao = lane_xor(acc[g][e], off, lane);
                 acc[g][e] = acc[g][e] * ca + ao * cb;
             }
         }
     }
 
-    // ---- merge the waves of the workgroup through LDS ----
+    // ---- merge the waves of the workgroup through LDS, write the unit's partial ----
     __shared__ float sm_acc[NW][G][D];
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ int sm_last;
@@ -220,65 +374,117 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(AttnArgs a) {
     }
     __syncthreads();
 
-    const size_t pbase = (((size_t)blockIdx.x * a.rows + row) * a.Hq + (size_t)kvh * G) * PSTRIDE;
-    for (int idx = tid; idx < G * D; idx += NW * 64) {
-        const int g = idx / D, d = idx % D;
+    constexpr int COLS = G * D / 2;                                   // pairs of output elements
+    float* const prow = a.partials + (((size_t)blockIdx.x * a.rows + row) * a.Hq + (size_t)kvh * G) * PSTRIDE;
+    for (int col = tid; col < COLS; col += NT) {
+        const int g = col / (D / 2), d = (col % (D / 2)) * 2;
         float mn = sm_m[0][g];
 #pragma unroll
         for (int w = 1; w < NW; ++w) mn = fmaxf(mn, sm_m[w][g]);
-        float accv = 0.f, lv = 0.f;
+        float ax = 0.f, ay = 0.f, lv = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const float c = exp2f(sm_m[w][g] - mn);
-            accv = fmaf(sm_acc[w][g][d], c, accv);
+            ax = fmaf(sm_acc[w][g][d], c, ax);
+            ay = fmaf(sm_acc[w][g][d + 1], c, ay);
             lv = fmaf(sm_l[w][g], c, lv);
         }
-        float* pp = a.partials + pbase + (size_t)g * PSTRIDE;
-        pp[d] = accv;
-        if (d == 0) { pp[D] = mn; pp[D + 1] = lv; }
+        st_agent2(prow + (size_t)g * PSTRIDE + d, ax, ay);
+        if (d == 0) st_agent2(prow + (size_t)g * PSTRIDE + D, mn, lv);
     }
 
     // ---- the last workgroup of this (instance, KV head, row) merges all units ----
+    // Every thread waits for its own partial stores to complete, the barrier orders them
+    // before thread 0's ticket, and the last arrival reads the partials back from memory.
     const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + row;
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (tid == 0) {
-        const int prev = atomicAdd(&a.counters[cidx], 1);
-        sm_last = (prev == n_units_inst - 1);
+        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = (prev == unit.n_units_inst - 1);
     }
     __syncthreads();
     if (!sm_last) return;
-    __threadfence();
 
-    for (int idx = tid; idx < G * D; idx += NW * 64) {
-        const int g = idx / D, d = idx % D;
-        const size_t hoff = ((size_t)kvh * G + g) * PSTRIDE;
-        const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
-        const float* p0 = a.partials + ((size_t)unit0_inst * a.rows + row) * a.Hq * PSTRIDE + hoff;
-        float mn = kNegBig;
-        for (int u = 0; u < n_units_inst; ++u)
-            mn = fmaxf(mn, p0[(size_t)u * ustride + D]);
-        float accv = 0.f, lv = 0.f;
-        for (int u = 0; u < n_units_inst; ++u) {
-            const float* pu = p0 + (size_t)u * ustride;
-            const float c = exp2f(pu[D] - mn);
-            accv = fmaf(pu[d], c, accv);
-            lv = fmaf(pu[D + 1], c, lv);
+    // One pass, all loads in flight at once: a thread owns one pair of output elements, reads
+    // that pair and the (max, sum) of its head from up to MCH units, then folds them in.
+    constexpr int MCH = 32;
+    const int n_units = unit.n_units_inst;
+    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
+    const float* const p0 = a.partials + (((size_t)unit.unit0_inst * a.rows + row) * a.Hq + (size_t)kvh * G) * PSTRIDE;
+    for (int col = tid; col < COLS; col += NT) {
+        const int g = col / (D / 2), d = (col % (D / 2)) * 2;
+        const float* src = p0 + (size_t)g * PSTRIDE;
+        float M = kNegBig, Lsum = 0.f, ox = 0.f, oy = 0.f;
+        for (int u0 = 0; u0 < n_units; u0 += MCH) {
+            float2 av[MCH], ml[MCH];
+#pragma unroll
+            for (int i = 0; i < MCH; ++i) {
+                const size_t uo = (size_t)min(u0 + i, n_units - 1) * ustride;
+                av[i] = ld_agent2(src + uo + d);
+                ml[i] = ld_agent2(src + uo + D);
+            }
+            float mn = M;
+#pragma unroll
+            for (int i = 0; i < MCH; ++i) mn = fmaxf(mn, (u0 + i < n_units) ? ml[i].x : kNegBig);
+            const float cold = exp2f(M - mn);
+            Lsum *= cold; ox *= cold; oy *= cold;
+            M = mn;
+#pragma unroll
+            for (int i = 0; i < MCH; ++i) {
+                const float c = (u0 + i < n_units) ? exp2f(ml[i].x - mn) : 0.f;
+                Lsum = fmaf(ml[i].y, c, Lsum);
+                ox = fmaf(av[i].x, c, ox);
+                oy = fmaf(av[i].y, c, oy);
+            }
         }
-        const float o = accv / lv;
+        const float inv = 1.0f / Lsum;
         T* op = reinterpret_cast<T*>(a.out) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + d;
-        if constexpr (sizeof(T) == 4) *reinterpret_cast<float*>(op) = o;
-        else *reinterpret_cast<uint16_t*>(op) = f32_to_bf16_rne(o);
+        if constexpr (sizeof(T) == 4) {
+            *reinterpret_cast<float2*>(op) = make_float2(ox * inv, oy * inv);
+        } else {
+            *reinterpret_cast<uint32_t*>(op) =
+                (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
+        }
     }
-    if (tid == 0) a.counters[cidx] = 0;   // ready for the next launch on this stream
+    if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
+template <typename T, int D, int G, int NW, int U>
+hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
+    KernelArgs k;
+    k.q = a.q; k.out = a.out; k.tail_k = a.tail_k; k.tail_v = a.tail_v;
+    k.partials = a.partials; k.counters = a.counters;
+    k.layer = a.layer; k.Hq = a.Hq; k.Hkv = a.Hkv; k.max_tail = a.max_tail; k.rows = a.rows;
+    k.prefill = a.prefill; k.scale_log2e = a.scale_log2e;
+    dim3 grid(a.n_units, a.Hkv, a.rows), block(NW * 64);
+    hipLaunchKernelGGL((attn_rows_kernel<T, D, G, NW, U>), grid, block, 0, s, k,
+                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
+                       reinterpret_cast<const Item*>(a.table + a.off_items),
+                       reinterpret_cast<const Unit*>(a.table + a.off_units));
+    return hipGetLastError();
+}
+
+// variant = NW * 100 + U for the shapes built below; 0 picks the default
 template <typename T, int D, int G>
 hipError_t launch_t(const AttnArgs& a, hipStream_t s) {
-    constexpr int NW = 4, U = 4;
-    dim3 grid(a.n_units, a.Hkv, a.rows), block(NW * 64);
-    hipLaunchKernelGGL((attn_rows_kernel<T, D, G, NW, U>), grid, block, 0, s, a);
-    return hipGetLastError();
+    if constexpr (sizeof(T) == 2 && D == 128 && (G == 4 || G == 8)) {
+        switch (a.variant) {
+            case 402: return launch_v<T, D, G, 4, 2>(a, s);
+            case 408: return launch_v<T, D, G, 4, 8>(a, s);
+            case 802: return launch_v<T, D, G, 8, 2>(a, s);
+            case 804: return launch_v<T, D, G, 8, 4>(a, s);
+            case 202: return launch_v<T, D, G, 2, 2>(a, s);
+            case 204: return launch_v<T, D, G, 2, 4>(a, s);
+            case 208: return launch_v<T, D, G, 2, 8>(a, s);
+            case 102: return launch_v<T, D, G, 1, 2>(a, s);
+            case 104: return launch_v<T, D, G, 1, 4>(a, s);
+            case 108: return launch_v<T, D, G, 1, 8>(a, s);
+            default: break;
+        }
+    }
+    return launch_v<T, D, G, 4, 4>(a, s);
 }
 
 template <typename T, int D>

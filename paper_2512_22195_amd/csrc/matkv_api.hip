@@ -117,7 +117,8 @@ matkv_status check_config(const matkv_config* c, const char** why) {
     if (c->softmax_scale < 0.f || isnan(c->softmax_scale)) { *why = "softmax_scale negative"; return MATKV_EINVAL; }
     if (c->hidden % 64) { *why = "hidden must be a multiple of 64"; return MATKV_EINVAL; }
     if (c->max_tail_tokens % 8) { *why = "max_tail_tokens must be a multiple of 8"; return MATKV_EINVAL; }
-    if (c->split_tokens < 0 || (c->split_tokens % 8)) { *why = "split_tokens must be a non-negative multiple of 8"; return MATKV_EINVAL; }
+    if (c->decode_units < 0 || c->decode_units > kMaxDecodeUnitsPerInstance) { *why = "decode_units outside 0..256"; return MATKV_EINVAL; }
+    if (c->decode_variant < 0) { *why = "decode_variant negative"; return MATKV_EINVAL; }
     if (c->max_batch > 1024 || c->max_pages > 4096) { *why = "max_batch <= 1024, max_pages <= 4096"; return MATKV_EINVAL; }
     if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return MATKV_EUNSUPPORTED; }
     const int g = c->n_q_heads / c->n_kv_heads;
@@ -127,16 +128,77 @@ matkv_status check_config(const matkv_config* c, const char** why) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Tokens per decode work item when the configuration does not fix it: enough workgroups
-// (items x KV heads) to cover 256 compute units several times, pieces not too small.
-int choose_split(const matkv_config& c, long total_page_tokens) {
-    if (c.split_tokens > 0) return c.split_tokens;
-    const long target_wgs = 1024;
-    long s = (total_page_tokens * c.n_kv_heads + target_wgs - 1) / target_wgs;
-    s = (s + 31) / 32 * 32;
-    if (s < 64) s = 64;
-    if (s > 2048) s = 2048;
-    return (int)s;
+// Decode workgroups per (instance, KV head) when the configuration does not fix it: about one
+// workgroup per compute unit over the whole batch, each with at least 128 tokens to stream.
+int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
+    int u = c.decode_units;
+    if (u <= 0) {
+        const int per_head = batch * c.n_kv_heads;
+        u = (256 + per_head - 1) / per_head;
+        const long cap = inst_tokens / 128;
+        if (u > cap) u = (int)cap;
+    }
+    if (u < 1) u = 1;
+    if (u > kMaxDecodeUnitsPerInstance) u = kMaxDecodeUnitsPerInstance;
+    return u;
+}
+
+// Cuts one instance's cache (its pages in order, then its tail) into n_units runs of nearly
+// equal token counts, in 8-token granules.  A run is a list of items (page pieces); the tail
+// is one item and belongs to the last run.  Appends to items / units; returns the number of
+// units made (runs that would hold no tokens are dropped).
+int build_units(const matkv_page* pages, int n_pages, int inst, int n_units, int tail_estimate,
+                int max_tail, Item* items, int* n_items, Unit* units, int* n_units_out) {
+    long page_gran = 0;
+    for (int p = 0; p < n_pages; ++p) page_gran += (pages[p].n_tokens + 7) / 8;
+    const long tail_gran = (tail_estimate + 7) / 8;
+    const long total = page_gran + tail_gran;
+    int made = 0;
+    int p = 0;            // current page
+    long p_g0 = 0;        // first granule (in the instance's page stream) of page p
+    for (int u = 0; u < n_units; ++u) {
+        long g0 = total * u / n_units, g1 = total * (u + 1) / n_units;
+        const bool last = (u == n_units - 1);
+        if (g0 > page_gran) g0 = page_gran;
+        if (g1 > page_gran || last) g1 = page_gran;
+        if (g1 <= g0 && !last) continue;
+        Unit un;
+        memset(&un, 0, sizeof(un));
+        un.inst = inst; un.item0 = *n_items; un.idx_in_inst = made;
+        long g = g0;
+        while (g < g1) {
+            long pg = (pages[p].n_tokens + 7) / 8;
+            while (g >= p_g0 + pg) { p_g0 += pg; ++p; pg = (pages[p].n_tokens + 7) / 8; }
+            const long e = (g1 < p_g0 + pg) ? g1 : p_g0 + pg;
+            Item it;
+            memset(&it, 0, sizeof(it));
+            it.base = reinterpret_cast<uint64_t>(pages[p].slot);
+            it.page_tokens = pages[p].n_tokens;
+            it.tok0 = (int)((g - p_g0) * 8);
+            const int t1 = (int)((e - p_g0) * 8);
+            it.ntok = (t1 < pages[p].n_tokens ? t1 : pages[p].n_tokens) - it.tok0;
+            un.page_tokens += it.ntok;
+            items[(*n_items)++] = it;
+            g = e;
+        }
+        if (last) {
+            Item it;
+            memset(&it, 0, sizeof(it));
+            it.base = 0; it.page_tokens = max_tail; it.tok0 = 0; it.ntok = max_tail;
+            items[(*n_items)++] = it;
+        }
+        un.n_items = *n_items - un.item0;
+        un.has_tail = last ? 1 : 0;
+        un.first = items[un.item0];
+        units[(*n_units_out)++] = un;
+        ++made;
+    }
+    for (int k = 0; k < made; ++k) {
+        Unit& un = units[*n_units_out - made + k];
+        un.n_units_inst = made;
+        un.unit0_inst = *n_units_out - made;
+    }
+    return made;
 }
 
 TableHost* find_table(matkv_ctx* c, const void* t) {
@@ -456,7 +518,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         }
     }
 
-    const int split = choose_split(cfg, total_tokens);
+    (void)total_tokens;
     Staging& sg = c->staging[c->staging_next];
     c->staging_next = (c->staging_next + 1) % kStagingRing;
     if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.ev));
@@ -473,42 +535,12 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     for (int b = 0; b < batch; ++b) {
         InstanceInfo& in = insts[b];
         memset(&in, 0, sizeof(in));
-        const int item_begin = n_items;
+        const matkv_page* pg = pages ? pages + (size_t)b * cfg.max_pages : nullptr;
         long inst_tokens = 0;
-        // page pieces: even partition of each page in 8-token granules, pieces <= split
-        int local_split = split;
-        for (;;) {
-            long cnt = 1;
-            for (int p = 0; p < n_pages[b]; ++p)
-                cnt += (pages[(size_t)b * cfg.max_pages + p].n_tokens + local_split - 1) / local_split;
-            if (cnt <= kMaxItemsPerInstance) break;
-            local_split *= 2;
-        }
         for (int p = 0; p < n_pages[b]; ++p) {
-            const matkv_page& pg = pages[(size_t)b * cfg.max_pages + p];
-            const int pieces = (pg.n_tokens + local_split - 1) / local_split;
-            const int granules = (pg.n_tokens + 7) / 8;
-            int g0 = 0;
-            for (int k = 0; k < pieces; ++k) {
-                const int g1 = (int)((long)granules * (k + 1) / pieces);
-                const int t0 = g0 * 8, t1 = g1 * 8 < pg.n_tokens ? g1 * 8 : pg.n_tokens;
-                g0 = g1;
-                if (t1 <= t0) continue;
-                Item& itx = items[n_items++];
-                memset(&itx, 0, sizeof(itx));
-                itx.base = reinterpret_cast<uint64_t>(pg.slot);
-                itx.page_tokens = pg.n_tokens;
-                itx.tok0 = t0;
-                itx.ntok = t1 - t0;
-            }
-            inst_tokens += pg.n_tokens;
-            c->slots[pg.slot].referenced = true;
+            inst_tokens += pg[p].n_tokens;
+            c->slots[pg[p].slot].referenced = true;
         }
-        Item& tail = items[n_items++];
-        memset(&tail, 0, sizeof(tail));
-        tail.base = 0; tail.page_tokens = cfg.max_tail_tokens; tail.tok0 = 0; tail.ntok = cfg.max_tail_tokens;
-        const int count = n_items - item_begin;
-
         in.pos_base = pos_base ? pos_base[b] : inst_tokens;
         if (in.pos_base + cfg.max_tail_tokens > (1ll << 24)) return fail(c, MATKV_EINVAL, "assemble: positions beyond 2^24");
         in.tail_len = q_len[b];
@@ -518,14 +550,18 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         if (q_len[b] > max_q) max_q = q_len[b];
         if (q_len[b] > th.max_tail_len) th.max_tail_len = q_len[b];
         if (q_len[b] < th.min_tail_len) th.min_tail_len = q_len[b];
-        // decode: one unit per item
-        in.dunit0 = n_dunits; in.n_dunits = count;
-        for (int k = 0; k < count; ++k) dunits[n_dunits++] = Unit{b, item_begin + k, 1, k};
-        // prefill: runs of items, at most kMaxPrefillUnitsPerInstance per instance
-        const int ipu = (count + kMaxPrefillUnitsPerInstance - 1) / kMaxPrefillUnitsPerInstance;
-        in.punit0 = n_punits; in.n_punits = (count + ipu - 1) / ipu;
-        for (int k = 0, u = 0; k < count; k += ipu, ++u)
-            punits[n_punits++] = Unit{b, item_begin + k, (count - k < ipu ? count - k : ipu), u};
+        const int tail_est = q_len[b] + (cfg.max_tail_tokens - q_len[b]) / 2;
+        // decode: fine partition, one workgroup per (unit, KV head)
+        in.dunit0 = n_dunits;
+        in.n_dunits = build_units(pg, n_pages[b], b, choose_decode_units(cfg, batch, inst_tokens + tail_est),
+                                  tail_est, cfg.max_tail_tokens, items, &n_items, dunits, &n_dunits);
+        // prefill: coarse partition (the question rows supply the parallelism)
+        int pu = (int)((inst_tokens + tail_est) / 1024);
+        if (pu < 1) pu = 1;
+        if (pu > kMaxPrefillUnitsPerInstance) pu = kMaxPrefillUnitsPerInstance;
+        in.punit0 = n_punits;
+        in.n_punits = build_units(pg, n_pages[b], b, pu, q_len[b], cfg.max_tail_tokens, items, &n_items,
+                                  punits, &n_punits);
     }
     hdr->batch = batch; hdr->n_items = n_items; hdr->n_dunits = n_dunits; hdr->n_punits = n_punits;
     hdr->total_q = cu; hdr->max_q = max_q;
@@ -577,6 +613,7 @@ static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int
     a.q = q; a.out = out; a.tail_k = tail_k; a.tail_v = tail_v;
     a.table = reinterpret_cast<const char*>(table);
     a.partials = reinterpret_cast<float*>(c->workspace + c->wl.off_partials);
+    a.variant = prefill ? 0 : c->cfg.decode_variant;
     a.counters = reinterpret_cast<int32_t*>(c->workspace + c->wl.off_counters);
     a.layer = layer; a.n_layers = c->cfg.n_layers;
     a.Hq = c->cfg.n_q_heads; a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim;

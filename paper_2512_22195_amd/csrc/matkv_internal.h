@@ -14,10 +14,10 @@ namespace matkv {
 // instance its pages cut into work items, then one item for its tail.  Built on the host by
 // matkv_assemble, read by the attention and tail-materialize kernels.
 
-constexpr int kMaxItemsPerInstance = 256;   // page pieces + tail
+constexpr int kMaxDecodeUnitsPerInstance = 256;
 constexpr int kMaxPrefillUnitsPerInstance = 32;
 
-struct Item {              // 32 bytes
+struct Item {              // 32 bytes: a run of tokens inside one page, or the tail
     uint64_t base;         // device address of the page's blob; 0 = the instance's tail
     int32_t page_tokens;   // tokens of the whole page (stride of a head inside the blob)
     int32_t tok0;          // first token of this piece
@@ -25,11 +25,16 @@ struct Item {              // 32 bytes
     int32_t pad[3];
 };
 
-struct Unit {              // 16 bytes: a run of consecutive items of one instance
+struct Unit {              // 64 bytes: the work of one workgroup = consecutive items of one instance
     int32_t inst;
-    int32_t item0;         // global item index
+    int32_t item0;         // global index of the first item
     int32_t n_items;
     int32_t idx_in_inst;
+    int32_t n_units_inst;  // units of this instance in this partition
+    int32_t unit0_inst;    // global index of the instance's first unit
+    int32_t has_tail;      // the last item is the tail
+    int32_t page_tokens;   // token rows of the unit's page items together
+    Item first;            // copy of items[item0]: one fetch is enough to start streaming
 };
 
 struct InstanceInfo {      // 48 bytes
@@ -60,8 +65,9 @@ struct TableLayout {
 
 inline TableLayout table_layout(const matkv_config& c) {
     TableLayout L;
-    L.max_items = c.max_batch * kMaxItemsPerInstance;
-    L.max_dunits = L.max_items;
+    // every unit boundary and every page boundary starts a new item, in both partitions
+    L.max_items = c.max_batch * (kMaxDecodeUnitsPerInstance + kMaxPrefillUnitsPerInstance + 2 * c.max_pages + 2);
+    L.max_dunits = c.max_batch * kMaxDecodeUnitsPerInstance;
     L.max_punits = c.max_batch * kMaxPrefillUnitsPerInstance;
     size_t o = sizeof(TableHeader);
     L.off_inst = o;   o += sizeof(InstanceInfo) * (size_t)c.max_batch;
@@ -90,8 +96,8 @@ inline WorkspaceLayout workspace_layout(const matkv_config& c) {
     W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)max_q_rows(c);
     o += ((W.n_counters * sizeof(int32_t)) + 255) & ~(size_t)255;
     W.off_partials = o;
-    size_t stride = (size_t)c.n_q_heads * (c.head_dim + 2);
-    size_t dec = (size_t)c.max_batch * kMaxItemsPerInstance * stride;
+    size_t stride = (size_t)c.n_q_heads * (c.head_dim + 4);   // acc[D] + {m, l} (padded)
+    size_t dec = (size_t)c.max_batch * kMaxDecodeUnitsPerInstance * stride;
     size_t pre = (size_t)c.max_batch * kMaxPrefillUnitsPerInstance * (size_t)max_q_rows(c) * stride;
     W.partial_floats = dec > pre ? dec : pre;
     o += W.partial_floats * sizeof(float);
@@ -112,7 +118,7 @@ struct AttnArgs {
     const void* tail_k;
     const void* tail_v;
     const char* table;         // device table
-    float* partials;
+    float* partials;           // [unit][row][Hq][D + 4]: accumulator, running max, sum, pad
     int32_t* counters;
     int32_t layer, n_layers;
     int32_t Hq, Hkv, D;
@@ -121,6 +127,7 @@ struct AttnArgs {
     int32_t n_units;           // grid.x
     int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail
     float scale_log2e;
+    int32_t variant;           // kernel shape to use (0 = default); see attn_rows.hip
     size_t off_inst, off_items, off_units;
 };
 

@@ -32,7 +32,8 @@ class Case:
     rope_base: float = 10000.0
     scale: float = 1.0               # std of the generated values
     q_scale: float | None = None     # std of Q (defaults to scale)
-    split_tokens: int = 0
+    decode_units: int = 0
+    decode_variant: int = 0
     max_tail: int | None = None
     needle: bool = False             # plant one key that dominates the softmax
 
@@ -112,7 +113,8 @@ def make_context(case: Case, device="cuda:0"):
     from paper_2512_22195_amd import binding as mk
     cfg = mk.make_config(case.n_layers, case.Hq, case.Hkv, case.D, case.hidden, case.dtype,
                          case.rope_base, max_batch=case.batch, max_pages=case.max_pages,
-                         max_tail_tokens=case.tail_cap, split_tokens=case.split_tokens)
+                         max_tail_tokens=case.tail_cap, decode_units=case.decode_units,
+                         decode_variant=case.decode_variant)
     return mk.Context(cfg, device=device)
 
 

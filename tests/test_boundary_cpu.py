@@ -52,7 +52,7 @@ def test_config_check_rejects_what_is_not_built(mk):
     assert mk.config_check(mk.make_config(**ok)) == mk.OK
     bad = [dict(head_dim=96), dict(n_q_heads=6, n_kv_heads=4), dict(n_q_heads=32, n_kv_heads=2),
            dict(hidden=100), dict(max_tail_tokens=41), dict(n_layers=0), dict(rope_base=1.0),
-           dict(split_tokens=12), dict(max_batch=0)]
+           dict(decode_units=1000), dict(max_batch=0)]
     for delta in bad:
         cfg = mk.make_config(**{**ok, **delta})
         assert mk.config_check(cfg) in (mk.EINVAL, mk.EUNSUPPORTED), delta
