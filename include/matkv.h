@@ -77,7 +77,7 @@ typedef struct {
     int32_t max_pages;        /* chunks per instance */
     int32_t max_tail_tokens;  /* question + generated tokens per instance, multiple of 8 */
     int32_t decode_units;     /* decode workgroups per (instance, KV head); 0 = chosen per table */
-    int32_t decode_variant;   /* decode kernel shape, waves*100 + loads in flight; 0 = default */
+    int32_t decode_variant;   /* decode kernel shape; 0 = default (see the design doc for the codes) */
 } matkv_config;
 
 /* One loaded chunk: the device slot that holds its blob and its token count (host struct). */

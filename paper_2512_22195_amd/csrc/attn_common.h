@@ -1,0 +1,250 @@
+// Pieces shared by the two attention kernels (plain-ALU rows and matrix-core tiles): the walk
+// over a work unit's token rows, and the merge of partial results across waves and across the
+// units of one (instance, KV head).
+#pragma once
+
+#include "matkv_internal.h"
+
+namespace matkv {
+namespace attn {
+
+constexpr float kNegBig = -1.0e30f;   // "no key seen yet": finite, so that exp2(m - m) = 1
+constexpr int kPartialStride(int D) { return D + 4; }   // floats: accumulator, max, sum, pad
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// exp2 of a non-positive argument: the bare hardware instruction (results below the normal
+// range flush to zero, which is what a softmax weight that small should be).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 16-byte load through the global address space (a pointer rebuilt from an integer would
+// otherwise be treated as generic and loaded with the slower flat instructions).
+__device__ __forceinline__ uint4 ldg16(const void* p) {
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+    const u32x4 r = *(gptr)(uintptr_t)p;
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+// Agent-scope relaxed accesses: coherent across the chip's L2 slices without cache flushes.
+__device__ __forceinline__ void st_agent2(float* p, float x, float y) {
+    const uint64_t v = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float* p) {
+    const uint64_t r = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
+}
+
+// Value of the lane whose index differs in bit log2(off); off in {32, 16, 8}.  Distances 32
+// and 16 are register swaps on this chip; 8 goes through the LDS crossbar.
+__device__ __forceinline__ float lane_xor(float v, int off, int lane) {
+    const unsigned x = __float_as_uint(v);
+    if (off == 32) {
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return __uint_as_float((lane & 32) ? r.x : r.y);
+    }
+    if (off == 16) {
+        const u32x2 r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return __uint_as_float((lane & 16) ? r.x : r.y);
+    }
+    return __shfl_xor(v, off);
+}
+
+struct KernelArgs {
+    const void* __restrict__ q;
+    void* __restrict__ out;
+    const void* __restrict__ tail_k;
+    const void* __restrict__ tail_v;
+    float* __restrict__ partials;
+    int32_t* __restrict__ counters;
+    int32_t layer, Hq, Hkv, max_tail, rows, prefill;
+    float scale_log2e;
+};
+
+inline KernelArgs make_kernel_args(const AttnArgs& a) {
+    KernelArgs k;
+    k.q = a.q; k.out = a.out; k.tail_k = a.tail_k; k.tail_v = a.tail_v;
+    k.partials = a.partials; k.counters = a.counters;
+    k.layer = a.layer; k.Hq = a.Hq; k.Hkv = a.Hkv; k.max_tail = a.max_tail; k.rows = a.rows;
+    k.prefill = a.prefill; k.scale_log2e = a.scale_log2e;
+    return k;
+}
+
+// Where a wave's next block of token rows lives.
+template <typename T>
+struct BlockRef {
+    const T* k;      // row 0 of the item's K stream for this head
+    const T* v;
+    int t0;          // first token row of the block (index inside the page, or inside the tail)
+    int tok_end;     // one past the block's last valid row
+    bool is_tail;
+    bool valid;
+};
+
+// The unit's items, end to end, form one run of token rows (the tail clipped to tail_visible).
+// Each wave takes an equal contiguous share of the run, rounded up to ALIGN rows, and walks it
+// in blocks of at most BLK rows that never straddle two items.  All state is wave-uniform.
+template <typename T, int D, int NW, int BLK, int ALIGN>
+struct Walker {
+    const KernelArgs& a;
+    const Unit& unit;
+    const Item* __restrict__ items;
+    int kvh, tail_visible;
+    Item item;
+    int item_i, item_pos0, pos, pos_end;
+
+    __device__ __forceinline__ Walker(const KernelArgs& a_, const Unit& u_, const Item* items_, int kvh_,
+                                      int tail_visible_, int wave)
+        : a(a_), unit(u_), items(items_), kvh(kvh_), tail_visible(tail_visible_), item(u_.first),
+          item_i(0), item_pos0(0) {
+        int total = unit.page_tokens;
+        if (unit.has_tail) total += min(a.max_tail, tail_visible);
+        const int share = ((total + NW - 1) / NW + ALIGN - 1) / ALIGN * ALIGN;
+        pos = wave * share;
+        pos_end = min(total, pos + share);
+    }
+    __device__ __forceinline__ int rows_of(const Item& it) const {
+        return it.base ? it.ntok : min(it.ntok, tail_visible);
+    }
+    __device__ __forceinline__ BlockRef<T> next() {
+        BlockRef<T> r;
+        r.valid = false; r.is_tail = false; r.k = nullptr; r.v = nullptr; r.t0 = 0; r.tok_end = 0;
+        if (pos >= pos_end) return r;
+        int rows = rows_of(item);
+        while (pos >= item_pos0 + rows) {
+            item_pos0 += rows;
+            if (++item_i >= unit.n_items) return r;
+            item = items[unit.item0 + item_i];
+            rows = rows_of(item);
+        }
+        if (item.base) {
+            const size_t head_elems = (size_t)item.page_tokens * D;
+            const T* blob = reinterpret_cast<const T*>(item.base);
+            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+        } else {
+            const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
+            r.k = reinterpret_cast<const T*>(a.tail_k) + off;
+            r.v = reinterpret_cast<const T*>(a.tail_v) + off;
+            r.is_tail = true;
+        }
+        const int in_item = pos - item_pos0;
+        const int n = min(BLK, min(rows - in_item, pos_end - pos));
+        r.t0 = item.tok0 + in_item;
+        r.tok_end = r.t0 + n;
+        r.valid = true;
+        pos += n;
+        return r;
+    }
+};
+
+// What a local result row of a workgroup stands for.
+struct RowMap {
+    int slot_row;    // row index inside the partial buffer (question row; 0 for decode)
+    int head;        // query head
+    int q_row;       // row of the packed Q / O tensors
+};
+
+// Merge of one workgroup's per-wave states (already in LDS: accumulators sm_acc[w][row][..]
+// with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums sm_l[w][row]) into the
+// unit's partial, followed - in the last workgroup of this (instance, KV head, z index) to
+// arrive - by the merge of all units' partials into the output rows.
+//
+// Partials are written and read with agent-scope accesses: every thread waits for its own
+// stores to complete, the barrier orders them before thread 0's ticket, and the last arrival
+// reads the partials back from memory.  No L2 write-back or invalidate is involved.
+template <typename T, int D, int NW, int ROWS, int ACC_STRIDE, typename MapFn>
+__device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& unit, int kvh, int zidx,
+                                            const float* sm_acc, const float* sm_m, const float* sm_l,
+                                            int* sm_last, int n_valid_rows, MapFn map) {
+    constexpr int NT = NW * 64;
+    constexpr int PSTRIDE = kPartialStride(D);
+    const int tid = threadIdx.x;
+    __syncthreads();
+
+    const int cols_valid = n_valid_rows * (D / 2);            // valid rows are a prefix of the local rows
+    for (int col = tid; col < cols_valid; col += NT) {
+        const int i = col / (D / 2), d = (col % (D / 2)) * 2;
+        const RowMap rm = map(i);
+        float mn = sm_m[i];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) mn = fmaxf(mn, sm_m[w * ROWS + i]);
+        float ax = 0.f, ay = 0.f, lv = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float c = fast_exp2(sm_m[w * ROWS + i] - mn);
+            const float* src = sm_acc + ((size_t)w * ROWS + i) * ACC_STRIDE + d;
+            ax = fmaf(src[0], c, ax);
+            ay = fmaf(src[1], c, ay);
+            lv = fmaf(sm_l[w * ROWS + i], c, lv);
+        }
+        float* prow = a.partials + (((size_t)blockIdx.x * a.rows + rm.slot_row) * a.Hq + rm.head) * PSTRIDE;
+        st_agent2(prow + d, ax, ay);
+        if (d == 0) st_agent2(prow + D, mn, lv);
+    }
+
+    const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + zidx;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) {
+        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *sm_last = (prev == unit.n_units_inst - 1);
+    }
+    __syncthreads();
+    if (!*sm_last) return;
+
+    // One pass, all loads in flight at once: a thread owns one pair of output elements, reads
+    // that pair and the (max, sum) of its row from up to MCH units, then folds them in.
+    constexpr int MCH = 32;
+    const int n_units = unit.n_units_inst;
+    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
+    for (int col = tid; col < cols_valid; col += NT) {
+        const int i = col / (D / 2), d = (col % (D / 2)) * 2;
+        const RowMap rm = map(i);
+        const float* src = a.partials + (((size_t)unit.unit0_inst * a.rows + rm.slot_row) * a.Hq + rm.head) * PSTRIDE;
+        float M = kNegBig, Lsum = 0.f, ox = 0.f, oy = 0.f;
+        for (int u0 = 0; u0 < n_units; u0 += MCH) {
+            float2 av[MCH], ml[MCH];
+#pragma unroll
+            for (int k = 0; k < MCH; ++k) {
+                const size_t uo = (size_t)min(u0 + k, n_units - 1) * ustride;
+                ml[k] = ld_agent2(src + uo + D);
+                av[k] = ld_agent2(src + uo + d);
+            }
+            float mn = M;
+#pragma unroll
+            for (int k = 0; k < MCH; ++k) mn = fmaxf(mn, (u0 + k < n_units) ? ml[k].x : kNegBig);
+            const float cold = fast_exp2(M - mn);
+            Lsum *= cold; ox *= cold; oy *= cold;
+            M = mn;
+#pragma unroll
+            for (int k = 0; k < MCH; ++k) {
+                const float c = (u0 + k < n_units) ? fast_exp2(ml[k].x - mn) : 0.f;
+                Lsum = fmaf(ml[k].y, c, Lsum);
+                ox = fmaf(av[k].x, c, ox);
+                oy = fmaf(av[k].y, c, oy);
+            }
+        }
+        const float inv = 1.0f / Lsum;
+        T* op = reinterpret_cast<T*>(a.out) + ((size_t)rm.q_row * a.Hq + rm.head) * D + d;
+        if constexpr (sizeof(T) == 4) {
+            *reinterpret_cast<float2*>(op) = make_float2(ox * inv, oy * inv);
+        } else {
+            *reinterpret_cast<uint32_t*>(op) =
+                (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
+        }
+    }
+    if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+}
+
+}  // namespace attn
+}  // namespace matkv

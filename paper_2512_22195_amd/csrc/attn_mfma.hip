@@ -1,0 +1,289 @@
+// Matrix-core attention over the assembled cache, bf16, head_dim 128: the question prefill
+// (paper Section V-A "prefill time": rows i of the question over every chunk key and question
+// keys j <= i) and, with a single row per instance, the decode step.
+//
+// The M dimension of the tiles is the flattened (question row, query head of one KV head)
+// index, so the G query heads that share a KV head ride in the same matrix-core operation.
+// Per wave and per block of 32 token rows:
+//   S^T = K Q^T     mfma 16x16x32: A = K rows straight from HBM in operand layout (16 tokens x
+//                   8 consecutive dims per lane), B = Q held in registers for the whole unit
+//   softmax         per lane on its own column (one (row, head)) with a running maximum that
+//                   the four 16-lane groups agree on through register swaps
+//   O^T += V^T P^T  A = V transposed on the fly: V rows land in a private LDS strip as loaded
+//                   (coalesced 16-byte loads) and come back through the transposing LDS read,
+//                   B = P rounded to bf16, already sitting in operand layout
+// Waves of a workgroup split the unit's tokens; workgroups split the cache; merging is the
+// same as in the plain-ALU kernel.
+#include "attn_common.h"
+
+namespace matkv {
+namespace {
+
+using namespace attn;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int D = 128;
+constexpr int BLK = 32;             // token rows per wave step
+constexpr int VSTR = D + 16;        // bf16 elements per LDS row of the V strip (bank spread)
+constexpr int ACCS = D + 4;         // floats per LDS row of the merge buffer
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& r) { return __builtin_bit_cast(bf16x8, r); }
+
+// Transposing LDS read: the 16 lanes of a group each name 8 bytes (4 bf16); lane i of the group
+// receives element i of the group's four 16-element rows.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
+    typedef s16x4 __attribute__((address_space(3))) * lptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)p);
+}
+
+template <int G, int NW, int MS, int PF>
+__global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
+        KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
+        const Unit* __restrict__ units) {
+    constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
+    typedef uint16_t T;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int kvh = blockIdx.y, tile = blockIdx.z;
+    const int m0 = tile * ROWS;
+
+    const Unit unit = units[blockIdx.x];
+
+    int n_m, q_row0, tail_len = 0, tail_visible;
+    if (a.prefill) {
+        const InstanceInfo inst = insts[unit.inst];
+        n_m = inst.q_len * G;
+        if (m0 >= n_m) return;                          // whole workgroup leaves together
+        q_row0 = inst.cu_q;
+        const int r_last = (min(m0 + ROWS, n_m) - 1) / G;
+        tail_visible = r_last + 1;                      // the most any row of this tile may see
+    } else {
+        n_m = G;
+        q_row0 = unit.inst;
+        if (unit.has_tail) tail_len = insts[unit.inst].tail_len;
+        tail_visible = tail_len;
+    }
+
+    // Q in operand layout: lane (c16, g4) holds, for sub-tile j and 32-dim chunk c, the 8 dims
+    // 32c + 8*g4 .. +8 of row m0 + 16j + c16.  Padding rows repeat the last real row.
+    bf16x8 bq[MS][4];
+    int vis[MS];                                        // tail rows this lane's row may see
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        const int m = min(m0 + 16 * j + c16, n_m - 1);
+        const int r = m / G, g = m % G;
+        const int q_row = a.prefill ? q_row0 + r : q_row0;
+        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + 8 * g4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + 32 * c));
+        vis[j] = a.prefill ? r + 1 : tail_len;
+    }
+
+    f32x4 ot[MS][8];                                    // O^T: dims 16s + 4*g4 + i of row 16j + c16
+    float mrow[MS], lrow[MS];
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        mrow[j] = kNegBig; lrow[j] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ot[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // LDS: per-wave V strips during the walk, the merge buffer afterwards (same bytes).
+    constexpr int V_BYTES = NW * BLK * VSTR * 2;
+    constexpr int ACC_BYTES = NW * ROWS * ACCS * 4;
+    __shared__ __attribute__((aligned(16))) char smem[V_BYTES > ACC_BYTES ? V_BYTES : ACC_BYTES];
+    __shared__ float sm_m[NW * ROWS], sm_l[NW * ROWS];
+    __shared__ int sm_last;
+    uint16_t* const vstrip = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * BLK * VSTR;
+
+    Walker<T, D, NW, BLK, 8> walk(a, unit, items, kvh, tail_visible, wave);
+
+    // Rows past the block's end are clamped to its last row and masked in the softmax.
+    auto issue = [&](const BlockRef<T>& r, uint4 (*ak)[4], uint4* vr) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const T* kp = r.k + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 8 * g4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ak[h][c] = ldg16(kp + 32 * c);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            vr[u] = ldg16(r.v + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
+    };
+
+    auto consume = [&](const BlockRef<T>& r, const uint4 (*ak)[4], const uint4* vr) {
+        // V rows into this wave's strip, as loaded
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            *reinterpret_cast<uint4*>(vstrip + (4 * u + g4) * VSTR + 8 * c16) = vr[u];
+
+        bf16x8 pb[MS];
+#pragma unroll
+        for (int j = 0; j < MS; ++j) {
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[0][c]), bq[j][c], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[1][c]), bq[j][c], s1, 0, 0, 0);
+            }
+            // lane holds tokens t0 + 4*g4 + i (s0) and t0 + 16 + 4*g4 + i (s1) of its row
+            const int limit = r.is_tail ? min(r.tok_end, vis[j]) : r.tok_end;
+            const int tb = r.t0 + 4 * g4;
+            float sv[8];
+            bool ok[8];
+            float mx = kNegBig;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ok[i] = tb + i < limit;
+                ok[4 + i] = tb + 16 + i < limit;
+                sv[i] = ok[i] ? s0[i] * a.scale_log2e : kNegBig;
+                sv[4 + i] = ok[4 + i] ? s1[i] * a.scale_log2e : kNegBig;
+                mx = fmaxf(mx, fmaxf(sv[i], sv[4 + i]));
+            }
+            mx = fmaxf(mx, lane_xor(mx, 16, lane));
+            mx = fmaxf(mx, lane_xor(mx, 32, lane));
+            const float mn = fmaxf(mrow[j], mx);
+            const float alpha = fast_exp2(mrow[j] - mn);
+            mrow[j] = mn;
+            float psum = 0.f;
+            float p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = ok[i] ? fast_exp2(sv[i] - mn) : 0.f;
+                psum += p[i];
+            }
+            lrow[j] = lrow[j] * alpha + psum;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)p[i];
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's maximum moved
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    ot[j][s][0] *= alpha; ot[j][s][1] *= alpha; ot[j][s][2] *= alpha; ot[j][s][3] *= alpha;
+                }
+            }
+        }
+
+        __builtin_amdgcn_wave_barrier();                // strip writes stay ahead of the reads below
+        // lane (c16, g4) names 4 dims (4*(c16%4) ..) of token 4*g4 + c16/4 (+16 for the second
+        // half) and receives dim 16s + c16 of tokens 4*g4 .. 4*g4+3: the k order of P above
+        const uint16_t* vp = vstrip + (4 * g4 + (c16 >> 2)) * VSTR + 4 * (c16 & 3);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const s16x4 lo = lds_read_tr(vp + 16 * s);
+            const s16x4 hi = lds_read_tr(vp + 16 * VSTR + 16 * s);
+            const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int j = 0; j < MS; ++j)
+                ot[j][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j], ot[j][s], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();                // and the next block's writes behind them
+    };
+
+    // PF blocks of loads stay in flight: block i + PF is issued right after block i is consumed.
+    {
+        uint4 kb[PF][2][4], vb[PF][8];
+        BlockRef<T> rb[PF];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            rb[i] = walk.next();
+            if (rb[i].valid) issue(rb[i], kb[i], vb[i]);
+        }
+        while (rb[0].valid) {
+#pragma unroll
+            for (int i = 0; i < PF; ++i) {
+                if (rb[i].valid) {
+                    consume(rb[i], kb[i], vb[i]);
+                    rb[i] = walk.next();
+                    if (rb[i].valid) issue(rb[i], kb[i], vb[i]);
+                }
+            }
+        }
+    }
+
+    // ---- per-wave states to LDS (the strips are dead now), then the common merge ----
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        lrow[j] += lane_xor(lrow[j], 16, lane);
+        lrow[j] += lane_xor(lrow[j], 32, lane);
+    }
+    __syncthreads();                                    // every wave is done with its strip
+    float* const sm_acc = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        float* dst = sm_acc + ((size_t)wave * ROWS + 16 * j + c16) * ACCS + 4 * g4;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            *reinterpret_cast<float4*>(dst + 16 * s) = make_float4(ot[j][s][0], ot[j][s][1], ot[j][s][2], ot[j][s][3]);
+        if (g4 == 0) { sm_m[wave * ROWS + 16 * j + c16] = mrow[j]; sm_l[wave * ROWS + 16 * j + c16] = lrow[j]; }
+    }
+    const int prefill = a.prefill;
+    auto map = [&](int i) {
+        RowMap rm;
+        const int m = m0 + i;
+        const int r = m / G, g = m % G;
+        rm.slot_row = prefill ? r : 0;
+        rm.head = kvh * G + g;
+        rm.q_row = prefill ? q_row0 + r : q_row0;
+        return rm;
+    };
+    finish_unit<T, D, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
+}
+
+template <int G, int NW, int MS, int PF>
+hipError_t launch_v(const AttnArgs& a, int tiles, hipStream_t s) {
+    const KernelArgs k = make_kernel_args(a);
+    dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
+    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, MS, PF>), grid, block, 0, s, k,
+                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
+                       reinterpret_cast<const Item*>(a.table + a.off_items),
+                       reinterpret_cast<const Unit*>(a.table + a.off_units));
+    return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
+    if (a.prefill) {
+        constexpr int MS = 2;
+        const int tiles = (a.rows * G + 16 * MS - 1) / (16 * MS);
+        return launch_v<G, 4, MS, 2>(a, tiles, s);
+    }
+    // decode: variant 9000 + 10 * (blocks in flight) + waves
+    switch (a.variant % 100) {
+        case 24: return launch_v<G, 4, 1, 2>(a, 1, s);
+        case 34: return launch_v<G, 4, 1, 3>(a, 1, s);
+        case 28: return launch_v<G, 8, 1, 2>(a, 1, s);
+        case 22: return launch_v<G, 2, 1, 2>(a, 1, s);
+        default: break;
+    }
+    // measured: eight waves pay off once eight query heads share a KV head
+    if (G == 8) return launch_v<G, 8, 1, 2>(a, 1, s);
+    return launch_v<G, 4, 1, 2>(a, 1, s);
+}
+
+}  // namespace
+
+bool attn_mfma_supported(const AttnArgs& a, int dtype) {
+    const int g = a.Hq / a.Hkv;
+    return dtype == MATKV_BF16 && a.D == 128 && (g == 1 || g == 2 || g == 4 || g == 8);
+}
+
+hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
+    if (a.n_units <= 0) return hipSuccess;
+    if (!attn_mfma_supported(a, dtype)) return hipErrorInvalidValue;
+    switch (a.Hq / a.Hkv) {
+        case 1: return launch_g<1>(a, s);
+        case 2: return launch_g<2>(a, s);
+        case 4: return launch_g<4>(a, s);
+        case 8: return launch_g<8>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace matkv

@@ -10,27 +10,19 @@
 // row) are merged by the last workgroup to arrive (atomic ticket), so a layer's attention is
 // one launch; partials travel through agent-scope (cache-bypassing) accesses, which keeps
 // the chip's separate L2 slices coherent without flushing them.
-#include "matkv_internal.h"
+#include "attn_common.h"
 
 namespace matkv {
 namespace {
 
-constexpr float kNegBig = -1.0e30f;   // "no key seen yet": finite, so that exp2(m - m) = 1
+using namespace attn;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct ElemTraits;
 template <> struct ElemTraits<float> { static constexpr int kPerLoad = 4; };
 template <> struct ElemTraits<uint16_t> { static constexpr int kPerLoad = 8; };   // bf16 bits
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v) {
@@ -48,39 +40,6 @@ __device__ __forceinline__ float group_sum(float v) {
     if (LPT >= 16) v = dpp_add<0x140>(v);   // row_mirror: other half of the 16-lane row
     if (LPT >= 32) v += __shfl_xor(v, 16);
     return v;
-}
-
-// Value of the lane whose index differs in bit log2(off); off in {32, 16, 8}.
-__device__ __forceinline__ float lane_xor(float v, int off, int lane) {
-    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-    const unsigned x = __float_as_uint(v);
-    if (off == 32) {
-        const u32x2 r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-        return __uint_as_float((lane & 32) ? r.x : r.y);
-    }
-    if (off == 16) {
-        const u32x2 r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-        return __uint_as_float((lane & 16) ? r.x : r.y);
-    }
-    return __shfl_xor(v, off);
-}
-
-// 16-byte load through the global address space (a pointer rebuilt from an integer would
-// otherwise be treated as generic and loaded with the slower flat instructions).
-__device__ __forceinline__ uint4 ldg16(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x4* gptr;
-    const u32x4 r = *(gptr)(uintptr_t)p;
-    return make_uint4(r.x, r.y, r.z, r.w);
-}
-
-// Agent-scope relaxed accesses: coherent across the chip's L2 slices without cache flushes.
-__device__ __forceinline__ void st_agent2(float* p, float x, float y) {
-    const uint64_t v = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
-    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 ld_agent2(const float* p) {
-    const uint64_t r = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
 }
 
 // ---- per-element-type arithmetic on one 16-byte piece of a K or V row -----------------------
@@ -170,27 +129,6 @@ template <int G, int U> struct PV<uint16_t, G, U> {
     }
 };
 
-struct KernelArgs {
-    const void* __restrict__ q;
-    void* __restrict__ out;
-    const void* __restrict__ tail_k;
-    const void* __restrict__ tail_v;
-    float* __restrict__ partials;
-    int32_t* __restrict__ counters;
-    int32_t layer, Hq, Hkv, max_tail, rows, prefill;
-    float scale_log2e;
-};
-
-// Where a wave's next block of BLK token rows lives.
-template <typename T>
-struct BlockRef {
-    const T* k;      // row 0 of the item's K stream for this head
-    const T* v;
-    int t0;          // first token row of the block
-    int tok_end;     // one past the item's last valid row
-    bool valid;
-};
-
 template <typename T, int D, int G, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
         KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
@@ -238,46 +176,8 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    // The unit's items, end to end, form one run of token rows (the tail clipped to what this
-    // row may see).  Each wave takes an equal contiguous share of it, rounded to whole
-    // wave-loads, and walks it in blocks of up to BLK rows that never straddle two items.
-    int total = unit.page_tokens;
-    if (unit.has_tail) total += min(a.max_tail, tail_visible);
-    const int share = ((total + NW - 1) / NW + TPW - 1) / TPW * TPW;
-    int pos = wave * share;                               // next row of this wave, in run coordinates
-    const int pos_end = min(total, pos + share);
-    Item item = unit.first;
-    int item_i = 0, item_pos0 = 0;                        // run coordinate of the item's first row
-    auto item_rows = [&](const Item& it) { return it.base ? it.ntok : min(it.ntok, tail_visible); };
-    auto next_block = [&]() -> BlockRef<T> {
-        BlockRef<T> r;
-        r.valid = false; r.k = nullptr; r.v = nullptr; r.t0 = 0; r.tok_end = 0;
-        if (pos >= pos_end) return r;
-        int rows = item_rows(item);
-        while (pos >= item_pos0 + rows) {
-            item_pos0 += rows;
-            if (++item_i >= unit.n_items) return r;
-            item = items[unit.item0 + item_i];
-            rows = item_rows(item);
-        }
-        if (item.base) {
-            const size_t head_elems = (size_t)item.page_tokens * D;
-            const T* blob = reinterpret_cast<const T*>(item.base);
-            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
-            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
-        } else {
-            const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
-            r.k = reinterpret_cast<const T*>(a.tail_k) + off;
-            r.v = reinterpret_cast<const T*>(a.tail_v) + off;
-        }
-        const int in_item = pos - item_pos0;
-        const int n = min(BLK, min(rows - in_item, pos_end - pos));
-        r.t0 = item.tok0 + in_item;
-        r.tok_end = r.t0 + n;
-        r.valid = true;
-        pos += n;
-        return r;
-    };
+    Walker<T, D, NW, BLK, TPW> walk(a, unit, items, kvh, tail_visible, wave);
+    auto next_block = [&]() { return walk.next(); };
     // Rows past the end are clamped to the last valid row (a cached re-read, no extra HBM
     // traffic) and masked later, so all 2*U loads issue back to back without branches.
     auto issue = [&](const BlockRef<T>& r, uint4* kraw, uint4* vraw) {
@@ -308,13 +208,13 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
             float mn = m[g];
 #pragma unroll
             for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][g]);
-            const float alpha = exp2f(m[g] - mn);
+            const float alpha = fast_exp2(m[g] - mn);
             m[g] = mn;
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const bool ok = r.t0 + u * TPW + grp < r.tok_end;
-                s[u][g] = ok ? exp2f(s[u][g] - mn) : 0.f;
+                s[u][g] = ok ? fast_exp2(s[u][g] - mn) : 0.f;
                 psum += s[u][g];
             }
             l[g] = l[g] * alpha + psum;
@@ -349,7 +249,7 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
             const float mo = lane_xor(m[g], off, lane);
             const float lo = lane_xor(l[g], off, lane);
             const float mn = fmaxf(m[g], mo);
-            const float ca = exp2f(m[g] - mn), cb = exp2f(mo - mn);
+            const float ca = fast_exp2(m[g] - mn), cb = fast_exp2(mo - mn);
             l[g] = l[g] * ca + lo * cb;
             m[g] = mn;
 #pragma unroll
@@ -360,7 +260,7 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
         }
     }
 
-    // ---- merge the waves of the workgroup through LDS, write the unit's partial ----
+    // ---- per-wave states to LDS, then the common merge ----
     __shared__ float sm_acc[NW][G][D];
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ int sm_last;
@@ -372,92 +272,17 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
             if (sub == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
         }
     }
-    __syncthreads();
-
-    constexpr int COLS = G * D / 2;                                   // pairs of output elements
-    float* const prow = a.partials + (((size_t)blockIdx.x * a.rows + row) * a.Hq + (size_t)kvh * G) * PSTRIDE;
-    for (int col = tid; col < COLS; col += NT) {
-        const int g = col / (D / 2), d = (col % (D / 2)) * 2;
-        float mn = sm_m[0][g];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) mn = fmaxf(mn, sm_m[w][g]);
-        float ax = 0.f, ay = 0.f, lv = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float c = exp2f(sm_m[w][g] - mn);
-            ax = fmaf(sm_acc[w][g][d], c, ax);
-            ay = fmaf(sm_acc[w][g][d + 1], c, ay);
-            lv = fmaf(sm_l[w][g], c, lv);
-        }
-        st_agent2(prow + (size_t)g * PSTRIDE + d, ax, ay);
-        if (d == 0) st_agent2(prow + (size_t)g * PSTRIDE + D, mn, lv);
-    }
-
-    // ---- the last workgroup of this (instance, KV head, row) merges all units ----
-    // Every thread waits for its own partial stores to complete, the barrier orders them
-    // before thread 0's ticket, and the last arrival reads the partials back from memory.
-    const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + row;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) {
-        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_last = (prev == unit.n_units_inst - 1);
-    }
-    __syncthreads();
-    if (!sm_last) return;
-
-    // One pass, all loads in flight at once: a thread owns one pair of output elements, reads
-    // that pair and the (max, sum) of its head from up to MCH units, then folds them in.
-    constexpr int MCH = 32;
-    const int n_units = unit.n_units_inst;
-    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
-    const float* const p0 = a.partials + (((size_t)unit.unit0_inst * a.rows + row) * a.Hq + (size_t)kvh * G) * PSTRIDE;
-    for (int col = tid; col < COLS; col += NT) {
-        const int g = col / (D / 2), d = (col % (D / 2)) * 2;
-        const float* src = p0 + (size_t)g * PSTRIDE;
-        float M = kNegBig, Lsum = 0.f, ox = 0.f, oy = 0.f;
-        for (int u0 = 0; u0 < n_units; u0 += MCH) {
-            float2 av[MCH], ml[MCH];
-#pragma unroll
-            for (int i = 0; i < MCH; ++i) {
-                const size_t uo = (size_t)min(u0 + i, n_units - 1) * ustride;
-                av[i] = ld_agent2(src + uo + d);
-                ml[i] = ld_agent2(src + uo + D);
-            }
-            float mn = M;
-#pragma unroll
-            for (int i = 0; i < MCH; ++i) mn = fmaxf(mn, (u0 + i < n_units) ? ml[i].x : kNegBig);
-            const float cold = exp2f(M - mn);
-            Lsum *= cold; ox *= cold; oy *= cold;
-            M = mn;
-#pragma unroll
-            for (int i = 0; i < MCH; ++i) {
-                const float c = (u0 + i < n_units) ? exp2f(ml[i].x - mn) : 0.f;
-                Lsum = fmaf(ml[i].y, c, Lsum);
-                ox = fmaf(av[i].x, c, ox);
-                oy = fmaf(av[i].y, c, oy);
-            }
-        }
-        const float inv = 1.0f / Lsum;
-        T* op = reinterpret_cast<T*>(a.out) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + d;
-        if constexpr (sizeof(T) == 4) {
-            *reinterpret_cast<float2*>(op) = make_float2(ox * inv, oy * inv);
-        } else {
-            *reinterpret_cast<uint32_t*>(op) =
-                (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
-        }
-    }
-    if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    auto map = [&](int g) {
+        RowMap rm;
+        rm.slot_row = row; rm.head = kvh * G + g; rm.q_row = q_row;
+        return rm;
+    };
+    finish_unit<T, D, NW, G, D>(a, unit, kvh, row, &sm_acc[0][0][0], &sm_m[0][0], &sm_l[0][0], &sm_last, G, map);
 }
 
 template <typename T, int D, int G, int NW, int U>
 hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
-    KernelArgs k;
-    k.q = a.q; k.out = a.out; k.tail_k = a.tail_k; k.tail_v = a.tail_v;
-    k.partials = a.partials; k.counters = a.counters;
-    k.layer = a.layer; k.Hq = a.Hq; k.Hkv = a.Hkv; k.max_tail = a.max_tail; k.rows = a.rows;
-    k.prefill = a.prefill; k.scale_log2e = a.scale_log2e;
+    const KernelArgs k = make_kernel_args(a);
     dim3 grid(a.n_units, a.Hkv, a.rows), block(NW * 64);
     hipLaunchKernelGGL((attn_rows_kernel<T, D, G, NW, U>), grid, block, 0, s, k,
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),

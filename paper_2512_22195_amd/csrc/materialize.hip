@@ -126,6 +126,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_rows_kernel(M
 #pragma unroll
     for (int t = 0; t < TT; ++t) { acc0[t] = 0.f; acc1[t] = 0.f; }
 
+#pragma unroll 8
     for (int c = lane * N; c < a.Hd; c += 64 * N) {
         float f0[N], f1[N];
         Ld<T>::get(w0 + c, f0);
@@ -192,6 +193,7 @@ hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
     const int total_rows = a.n_tokens;
     if (total_rows <= 0) return hipSuccess;
+    if (materialize_mfma_supported(a, dtype, total_rows)) return launch_materialize_mfma(a, total_rows, s);
     if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);
     return launch_rows<uint16_t>(a, total_rows, s);
 }

@@ -1,0 +1,190 @@
+// K/V materialization of one layer as a matrix-core GEMM with the rotary embedding in the
+// epilogue (paper Section III-B steps 2-3, cut to the K/V projection):
+//   [T, Hd] x [2*Hkv*D, Hd]^T  ->  K = RoPE(X Wk^T, pos), V = X Wv^T,   bf16, D = 128.
+// Both operands are contiguous along the contraction (hidden) axis, which is what the
+// matrix-core operand layout wants: a lane's 8 consecutive bf16 of one row.
+//
+// A workgroup owns 128 tokens x one head of K or of V (128 features, so both halves of every
+// rotary pair are in the tile), stepping 64 hidden columns at a time through double-buffered
+// LDS tiles.  Its four waves form a 2 x 2 grid of 64-token x 64-feature sub-tiles; a wave's
+// features are the 16-wide blocks {2w, 2w+1} and their rotary partners {2w+4, 2w+5}, so the
+// rotation is lane-local on the fp32 accumulators.  One rounding to bf16 on store.
+#include "matkv_internal.h"
+
+namespace matkv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128, BM = 128, BK = 64;
+constexpr int LDS_STRIDE = BK + 8;          // bf16 per LDS row: 144 bytes, conflict-free 16-byte reads
+
+__device__ __forceinline__ uint4 ldg16(const void* p) {
+    typedef const __attribute__((address_space(1))) u32x4* gptr;
+    const u32x4 r = *(gptr)(uintptr_t)p;
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+struct RowDest {
+    float pos;          // rotary position (exact in fp32: below 2^24)
+    size_t elem_off;    // element offset of [head 0][row][0] in the destination
+    bool valid;
+};
+
+__device__ __forceinline__ RowDest resolve_row(const MaterializeArgs& a, int r) {
+    RowDest d;
+    d.valid = false; d.pos = 0.f; d.elem_off = 0;
+    if (a.table == nullptr) {
+        if (r < a.n_tokens) { d.valid = true; d.pos = (float)(a.pos0 + r); d.elem_off = (size_t)r * D; }
+        return d;
+    }
+    const InstanceInfo* insts = reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst);
+    int b = -1, j = 0;
+    if (a.rows_per_instance > 0) {
+        if (r < a.batch * a.rows_per_instance) {
+            b = r / a.rows_per_instance;
+            j = insts[b].tail_len - a.rows_per_instance + (r % a.rows_per_instance);
+        }
+    } else {
+        for (int i = 0; i < a.batch; ++i) {
+            const int c0 = insts[i].cu_q;
+            if (r >= c0 && r < c0 + insts[i].q_len) { b = i; j = r - c0; break; }
+        }
+    }
+    if (b < 0 || j < 0 || j >= a.token_stride) return d;
+    d.valid = true;
+    d.pos = (float)(insts[b].pos_base + j);
+    d.elem_off = ((size_t)b * a.Hkv * a.token_stride + (size_t)j) * D;
+    return d;
+}
+
+// cos / sin of pos * theta_j with the angle kept in turns: hi/lo split product, whole turns
+// dropped exactly, then the hardware sine / cosine (which take turns).
+__device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, float& s) {
+    const float t = p * e.turns_hi;
+    const float err = fmaf(p, e.turns_hi, -t);
+    float fr = t - rintf(t);
+    fr += fmaf(p, e.turns_lo, err);
+    c = __builtin_amdgcn_cosf(fr);
+    s = __builtin_amdgcn_sinf(fr);
+}
+
+__global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a, int total_rows) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][D * LDS_STRIDE];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
+    const int row0 = blockIdx.y * BM;
+
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden);
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd;
+
+    // global -> LDS staging: thread t moves 16 bytes of rows t/8 + 32i (i < 4), columns 8*(t%8)
+    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
+    const uint16_t* xg[4];
+    const uint16_t* wg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = min(row0 + ld_row + 32 * i, total_rows - 1);       // rows past the end repeat the last
+        xg[i] = X + (size_t)r * a.Hd + ld_col;
+        wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
+    }
+    uint4 xr[4], wr[4];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { xr[i] = ldg16(xg[i] + k0); wr[i] = ldg16(wg[i] + k0); }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<uint4*>(&As[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = xr[i];
+            *reinterpret_cast<uint4*>(&Bs[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = wr[i];
+        }
+    };
+
+    f32x4 acc[4][4];            // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nk = a.Hd / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int ks = 0; ks < nk; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < nk) load_global((ks + 1) * BK);
+#pragma unroll
+        for (int k2 = 0; k2 < BK / 32; ++k2) {
+            bf16x8 av[4], bv[4];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+                av[mi] = *reinterpret_cast<const bf16x8*>(&As[buf][(64 * wm + 16 * mi + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+                const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
+                bv[ni] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(16 * tn + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (ks + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane holds tokens 64wm + 16mi + 4*g4 + i, features 16*tn + c16
+    uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const RowDest d = resolve_row(a, row0 + 64 * wm + 16 * mi + 4 * g4 + i);
+            if (!d.valid) continue;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int j = 16 * (2 * wn + p) + c16;           // rotary pair index, features j and j + 64
+                float lo = acc[mi][p][i], hi = acc[mi][p + 2][i];
+                if (kv == 0) {
+                    float c, s;
+                    rope_cs(a.rope[j], d.pos, c, s);
+                    const float k0 = lo * c - hi * s;
+                    const float k1 = lo * s + hi * c;
+                    lo = k0; hi = k1;
+                }
+                out[d.elem_off + j] = f32_to_bf16_rne(lo);
+                out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows) {
+    return dtype == MATKV_BF16 && a.D == 128 && (a.Hd % BK) == 0 && total_rows >= 16;
+}
+
+hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    dim3 grid(2 * a.Hkv, (total_rows + BM - 1) / BM), block(256);
+    hipLaunchKernelGGL(materialize_mfma_kernel, grid, block, 0, s, a, total_rows);
+    return hipGetLastError();
+}
+
+}  // namespace matkv

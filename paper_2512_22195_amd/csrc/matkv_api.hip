@@ -624,7 +624,9 @@ static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int
     a.scale_log2e = c->scale_log2e;
     a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
     a.off_units = prefill ? c->tl.off_punits : c->tl.off_dunits;
-    HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
+    const bool want_mfma = prefill || a.variant == 0 || a.variant >= 9000;
+    if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
+    else HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
 }
 

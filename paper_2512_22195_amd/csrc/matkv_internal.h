@@ -127,11 +127,14 @@ struct AttnArgs {
     int32_t n_units;           // grid.x
     int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail
     float scale_log2e;
-    int32_t variant;           // kernel shape to use (0 = default); see attn_rows.hip
+    int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
+                               // waves * 100 + loads in flight = plain-ALU kernel
     size_t off_inst, off_items, off_units;
 };
 
-hipError_t launch_attn_rows(const AttnArgs& a, int dtype, hipStream_t s);
+hipError_t launch_attn_rows(const AttnArgs& a, int dtype, hipStream_t s);     // plain ALU, any dtype
+bool attn_mfma_supported(const AttnArgs& a, int dtype);
+hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s);     // matrix cores, bf16 D=128
 
 struct MaterializeArgs {
     const void* hidden;
@@ -151,6 +154,8 @@ struct MaterializeArgs {
 };
 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s);
+bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows);
+hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s);
 hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s);
 
 }  // namespace matkv

@@ -83,6 +83,17 @@ def test_attention_shapes(dtype, D, Hq, Hkv):
     _attention_parity(case)
 
 
+@pytest.mark.parametrize("variant", [404, 408, 802, 804, 9024, 9034, 9028, 9022])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2)])
+def test_decode_kernel_variants(variant, Hq, Hkv):
+    """Every decode kernel shape that can be selected (plain-ALU: waves*100 + loads in flight;
+    matrix-core: 9000 + 10*blocks in flight + waves) against the oracle, group sizes 4 and 8."""
+    case = Case(f"attn-variant-{Hq}-{Hkv}", n_layers=1, Hq=Hq, Hkv=Hkv, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 300, 1: 77, 2: 1, 3: 129}, retrieved=[[0, 1], [2], [3, 0, 2]],
+                q_lens=[5, 1, 17], steps=3, scale=1.0, q_scale=1.0, decode_units=3, decode_variant=variant)
+    _attention_parity(case)
+
+
 def test_attention_baseline_distribution_auto_units():
     """The stated value distribution (N(0,1)/sqrt(128): near-uniform softmax) with the
     library's own choice of work units."""
