@@ -46,6 +46,33 @@ def test_bf16_chain_ragged_chunks():
     chain.compare_attention(case, gpu["o_pre"], gpu["o_dec"], ref["pre"], ref["dec"])
 
 
+def _chain_parity(case):
+    inp = chain.make_chain_inputs(case)
+    gpu = chain.run_gpu_chain(case, inp)
+    ref = chain.run_oracle_chain(case, inp)
+    for cid in case.chunk_lens:
+        for l in range(case.n_layers):
+            chain.compare_materialized(case, gpu["blobs"][cid][l, 0], ref["blobs"][cid][l][0], f"chunk {cid} K")
+            chain.compare_materialized(case, gpu["blobs"][cid][l, 1], ref["blobs"][cid][l][1], f"chunk {cid} V")
+    for (l, b), (Kt, Vt) in ref["tails"].items():
+        n = Kt.shape[1]
+        chain.compare_materialized(case, gpu["tail"][l, 0, b, :, :n], Kt, "tail K")
+        chain.compare_materialized(case, gpu["tail"][l, 1, b, :, :n], Vt, "tail V")
+    chain.compare_attention(case, gpu["o_pre"], gpu["o_dec"], ref["pre"], ref["dec"])
+
+
+@pytest.mark.parametrize("batch", [1, 2, 5])
+def test_bf16_chain_hidden_4096(batch):
+    """Llama-3-8B hidden size: the chunk and question projections run on the matrix-core GEMM
+    (token counts that are not tile multiples), the decode-token projection on the GEMV form
+    with 1, 2 and 5 rows."""
+    retrieved = [[0], [1, 0], [0, 1], [1], [0]][:batch]
+    case = Case(f"bf16-chain-4096-{batch}", n_layers=1, Hq=8, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 150, 1: 40}, retrieved=retrieved, q_lens=[3, 17, 1, 8, 20][:batch],
+                steps=2, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case)
+
+
 def test_materialize_large_positions_bf16():
     """Question/decode tokens sit at positions ~20 000: rotary angles must stay accurate."""
     case = Case("bf16-farpos", n_layers=1, Hq=4, Hkv=1, D=128, hidden=256, dtype="bf16",
