@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
     ap.add_argument("--decode-only-reps", type=int, default=20)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    ap.add_argument("--stream", type=int, default=8,
+                    help="instances of the pipelined leg (next instance loads while this one decodes); 0 = skip")
     return ap.parse_args()
 
 
@@ -161,6 +165,14 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3)}
 
+    if args.calib_copy:
+        with torch.cuda.stream(cs):
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+            dstc = torch.empty_like(src)
+            dstc.copy_(src)
+            cs.synchronize()
+            del src, dstc
+
     # ---------------------------------------------------------- KV load (never in value) -----
     kv_load = None
     if not args.no_load:
@@ -181,6 +193,63 @@ def main():
         ok = all(torch.equal(d.cpu(), h) for d, h in zip(dst[:1], host[:1]))
         kv_load = {"GBps": round(len(host) * nbytes / best / 1e9, 2), "ms_per_instance": round(best * 1e3, 3),
                    "bytes": len(host) * nbytes, "chunks": len(host), "byte_exact": bool(ok)}
+
+        # ---- pipelined stream (BASELINE config 5 at this shape): the next instance's blobs are
+        # loaded on the side stream into the other slot set while this instance runs its
+        # prefill and decode steps.  Host blobs: a ring of two distinct instance sets.
+        overlap = None
+        if args.stream > 0 and B == 1:
+            n_inst = args.stream
+            host2 = [torch.empty(nbytes, dtype=torch.uint8).pin_memory() for _ in inst_chunks]
+            for h2, h in zip(host2, reversed(host)):
+                h2.copy_(h)
+            host_sets = [host, host2]
+            slot_sets = [dst, [ctx.new_slot(L) for _ in inst_chunks]]
+
+            def enqueue_load(i):
+                return [ctx.load(h, L, d) for h, d in zip(host_sets[i % 2], slot_sets[i % 2])]
+
+            def enqueue_compute(i, tickets):
+                for t in tickets:
+                    ctx.wait(t)
+                ctx.assemble([[(d, L) for d in slot_sets[i % 2]]], q_lens, table)
+                for l in range(nl):
+                    ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
+                    ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+                for _ in range(steps_dec):
+                    ctx.graph_launch(g_step)
+
+            with torch.cuda.stream(cs):
+                torch.cuda.synchronize()
+                # serial: load, wait for it, compute, wait for it
+                t0 = time.perf_counter()
+                for i in range(n_inst):
+                    tk = enqueue_load(i)
+                    ctx.sync(tk[-1])
+                    enqueue_compute(i, tk)
+                    cs.synchronize()
+                t_serial = (time.perf_counter() - t0) / n_inst
+                # pipelined: load of i+1 is enqueued before the compute of i
+                tk = enqueue_load(0)                  # steady state: the first load is already there
+                ctx.sync(tk[-1])
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(n_inst):
+                    tk_next = enqueue_load(i + 1) if i + 1 < n_inst else None
+                    enqueue_compute(i, tk)
+                    tk = tk_next
+                cs.synchronize()
+                torch.cuda.synchronize()
+                t_pipe = (time.perf_counter() - t0) / n_inst
+            t_load = best
+            t_comp = ms_step * 1e-3
+            overlap = {"instances": n_inst, "instances_per_s": round(1.0 / t_pipe, 3),
+                       "ms_per_instance_pipelined": round(t_pipe * 1e3, 3),
+                       "ms_per_instance_serial": round(t_serial * 1e3, 3),
+                       "ms_load": round(t_load * 1e3, 3), "ms_compute": round(t_comp * 1e3, 3),
+                       "overlap_frac": round(max(0.0, min(1.0, (t_serial - t_pipe) / min(t_load, t_comp))), 3)}
+            del host2
+        kv_load["pipelined_stream"] = overlap
         del host, dst
 
     # ------------------------------------------------------------------------ cpu_baseline ---

@@ -261,3 +261,89 @@ def test_assemble_rejects_bad_arguments():
         assert e.value.status == mk.EINVAL
     finally:
         ctx.close()
+
+
+# ------------------------------------------------------------------ load / compute overlap ---
+def test_pipelined_instances_two_slot_sets():
+    """Stream of instances (BASELINE config 5 in small): instance i+1's blobs are loaded on the
+    side stream into the other slot set while instance i runs prefill and decode.  Slots start
+    poisoned with NaN and every instance has different data, so attention that ran before its
+    load finished, or a load that overwrote a slot still being read, cannot match the oracle."""
+    from workload import normal
+    n_inst = 5
+    case = Case("pipe", n_layers=2, Hq=8, Hkv=2, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 300, 1: 180}, retrieved=[[0, 1]], q_lens=[6], steps=3, scale=1.0, decode_units=4)
+    ctx = chain.make_context(case)
+    try:
+        inputs = []
+        for i in range(n_inst):
+            c = Case(f"pipe-{i}", **{k: getattr(case, k) for k in
+                                     ("n_layers", "Hq", "Hkv", "D", "hidden", "dtype", "chunk_lens", "retrieved",
+                                      "q_lens", "steps", "scale", "decode_units")})
+            inputs.append((c, chain.make_attention_inputs(c)))
+        host = [[inp["blobs"][cid].contiguous().view(torch.uint8).reshape(-1).pin_memory() for cid in (0, 1)]
+                for _, inp in inputs]
+        sets = [[ctx.new_slot(case.chunk_lens[cid]) for cid in (0, 1)] for _ in range(2)]
+        for s in sets:
+            for t in s:
+                t.view(torch.bfloat16).fill_(float("nan"))
+        torch.cuda.synchronize()
+        outs = []
+        with torch.cuda.stream(ctx.compute_stream):
+            table = ctx.new_table()
+            tails = [inp["tail"].cuda() for _, inp in inputs]
+            qp = [inp["q_pre"].cuda() for _, inp in inputs]
+            qd = [inp["q_dec"].cuda() for _, inp in inputs]
+            ctx.compute_stream.synchronize()
+
+            def load(i):
+                return [ctx.load(host[i][k], case.chunk_lens[k], sets[i % 2][k]) for k in (0, 1)]
+
+            tk = load(0)
+            for i in range(n_inst):
+                tk_next = load(i + 1) if i + 1 < n_inst else None
+                for t in tk:
+                    ctx.wait(t)
+                ctx.assemble([[(sets[i % 2][k], case.chunk_lens[k]) for k in (0, 1)]], case.q_lens, table)
+                o_pre = torch.full_like(qp[i], float("nan"))
+                o_dec = torch.full_like(qd[i], float("nan"))
+                for l in range(case.n_layers):
+                    ctx.prefill_attn(l, qp[i][l], table, tails[i][l, 0], tails[i][l, 1], o_pre[l])
+                for t in range(case.steps):
+                    ctx.advance(table, 1)
+                    for l in range(case.n_layers):
+                        ctx.decode_attn(l, qd[i][t, l], table, tails[i][l, 0], tails[i][l, 1], o_dec[t, l])
+                outs.append((o_pre, o_dec))
+                tk = tk_next
+            ctx.compute_stream.synchronize()
+        for (c, inp), (o_pre, o_dec) in zip(inputs, outs):
+            pre, dec = chain.run_oracle_attention(c, inp)
+            chain.compare_attention(c, o_pre.cpu(), o_dec.cpu(), pre, dec)
+    finally:
+        ctx.close()
+
+
+def test_assemble_refuses_pages_still_loading():
+    """A page whose load has neither finished nor been waited for is refused (ENOTREADY), not
+    read; after matkv_wait the same call goes through."""
+    from paper_2512_22195_amd import binding as mk
+    case = Case("notready", n_layers=32, Hq=32, Hkv=8, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 1000}, retrieved=[[0]], q_lens=[4], steps=0)
+    ctx = chain.make_context(case)
+    try:
+        n = mk.blob_bytes(ctx.cfg, 1000)                       # 131 MB per blob
+        host = torch.zeros(n, dtype=torch.uint8).pin_memory()
+        slots = [ctx.new_slot(1000) for _ in range(12)]        # 1.5 GB queued on the load stream
+        table = ctx.new_table()
+        torch.cuda.synchronize()
+        tickets = [ctx.load(host, 1000, s) for s in slots]
+        with pytest.raises(mk.MatKVError) as e:
+            ctx.assemble([[(slots[-1], 1000)]], [4], table)
+        assert e.value.status == mk.ENOTREADY
+        assert not ctx.query(tickets[-1]) or True              # may have finished by now; never blocks
+        ctx.wait(tickets[-1])
+        ctx.assemble([[(slots[-1], 1000)]], [4], table)
+        ctx.sync(tickets[-1])
+        assert ctx.query(tickets[-1])
+    finally:
+        ctx.close()
