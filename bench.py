@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
     ap.add_argument("--decode-only-reps", type=int, default=20)
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="only the decode-attention leg, launched eagerly (short run for rocprofv3 --pmc)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--stream", type=int, default=8,
@@ -116,6 +118,9 @@ def main():
             ctx.graph_launch(g_step)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
+    if args.roofline_only:
+        args.steps, args.warmup, args.no_cpu, args.no_load = 0, 0, True, True
+        print("bench: roofline-only run", file=sys.stderr, flush=True)
     with torch.cuda.stream(cs):
         for _ in range(args.warmup):
             one_pass()
@@ -135,9 +140,10 @@ def main():
         cs.synchronize()
         torch.cuda.synchronize()
         t_wall = time.perf_counter() - t_wall0
-    ms_prefill = sum(a.elapsed_time(b) for a, b in zip(e0, e1)) / args.steps
-    ms_decode = sum(b.elapsed_time(c) for b, c in zip(e1, e2)) / args.steps
-    ms_step = t_wall * 1e3 / args.steps
+    n_t = max(args.steps, 1)
+    ms_prefill = sum(a.elapsed_time(b) for a, b in zip(e0, e1)) / n_t
+    ms_decode = sum(b.elapsed_time(c) for b, c in zip(e1, e2)) / n_t
+    ms_step = max(t_wall * 1e3 / n_t, 1e-9)
     tokens_per_s = B * steps_dec / (ms_step * 1e-3)
 
     # ------------------------------------------------- roofline of the dominant kernel (D) ---
@@ -147,22 +153,38 @@ def main():
     with torch.cuda.stream(cs):
         ctx.assemble(pages, q_lens, table)
         ctx.advance(table, steps_dec // 2)
-        for _ in range(3):
-            ctx.graph_launch(g_attn)
+        def attn_all_layers():
+            if args.roofline_only:          # eager launches: one dispatch per layer, no graph
+                for l in range(nl):
+                    ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            else:
+                ctx.graph_launch(g_attn)
+        for _ in range(1 if args.roofline_only else 3):
+            attn_all_layers()
         a, b = ev(), ev()
         a.record(cs)
         for _ in range(args.decode_only_reps):
-            ctx.graph_launch(g_attn)
+            attn_all_layers()
         b.record(cs)
         cs.synchronize()
+        if args.roofline_only:
+            print("bench: decode-attention leg done", file=sys.stderr, flush=True)
     us_per_launch = a.elapsed_time(b) * 1e3 / (args.decode_only_reps * nl)
     kv_tok_bytes = shape.kv_bytes_per_token_layer()
     n_ctx = [sum(L for _ in r) for r in retrieved]
     bytes_per_launch = sum((n + t) * kv_tok_bytes for n, t in zip(n_ctx, mid_tail)) + 2 * B * Hq * D * shape.elem_bytes
     achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "attn_rows_kernel (matkv_decode_attn)",
+    kname = "attn_rows_kernel" if 0 < args.variant < 9000 or shape.dtype != "bf16" or D != 128 else "attn_mfma_kernel"
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same workload
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"decode_attn_config{args.config}_hbm_traffic.txt")
+    if args.units == 0 and args.variant == 0 and os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
+    roofline = {"bound": "hbm", "kernel": f"{kname} (matkv_decode_attn)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3)}
 
     if args.calib_copy:
