@@ -293,7 +293,7 @@ def main():
         qs = {l: to_f64(q_dec[l, b0]) for l in layers}
         reps, t_cpu = 0, 0.0
         t_begin = time.perf_counter()
-        while t_cpu < 10.0 and reps < 50:
+        while t_cpu < 12.0 and reps < 400:
             for l in layers:
                 t0 = time.perf_counter()
                 oracle.materialize(xs[l], wk[l][0], wk[l][1], Hkv, D, float(n_ctx[b0] + n_t - 1), shape.rope_base)

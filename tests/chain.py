@@ -231,7 +231,7 @@ def cu_q(case: Case):
     return cu
 
 
-def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=None):
+def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=None, prefill_rows=None):
     """fp64 oracle over the same generated K/V.  Returns dicts keyed by (layer) / (step, layer)
     of arrays shaped like the GPU outputs restricted to the sampled instances."""
     c = case
@@ -246,8 +246,14 @@ def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=Non
             chunks = [(to_f64(inp["blobs"][cid][l, 0]), to_f64(inp["blobs"][cid][l, 1])) for cid in c.retrieved[b]]
             lq = c.q_lens[b]
             tk, tv = to_f64(tail[l, 0, b]), to_f64(tail[l, 1, b])
-            pre[(l, b)] = oracle.prefill_attn(to_f64(inp["q_pre"][l, cu[b]:cu[b + 1]]), chunks,
-                                              tk[:, :lq], tv[:, :lq])
+            if prefill_rows is None:
+                pre[(l, b)] = oracle.prefill_attn(to_f64(inp["q_pre"][l, cu[b]:cu[b + 1]]), chunks,
+                                                  tk[:, :lq], tv[:, :lq])
+            else:
+                # sampled question rows: row r is a one-row attention that sees tail tokens 0..r
+                K, V, n_ctx = oracle.assemble(chunks, tk[:, :lq], tv[:, :lq])
+                for r in sorted({min(max(r, 0), lq - 1) for r in prefill_rows}):
+                    pre[(l, b, r)] = oracle.attn(to_f64(inp["q_pre"][l, cu[b] + r])[None], K, V, n_ctx, r)
             for t in steps:
                 n = lq + t + 1
                 dec[(t, l, b)] = oracle.decode_attn(to_f64(inp["q_dec"][t, l, b]), chunks, tk[:, :n], tv[:, :n])
@@ -300,8 +306,9 @@ def compare_attention(case: Case, o_pre, o_dec, pre, dec):
     cu = cu_q(case)
     atol, rtol = tolerances(case.dtype)
     worst = 0.0
-    for (l, b), ref in pre.items():
-        got = to_f64(o_pre[l, cu[b]:cu[b + 1]])
+    for key, ref in pre.items():
+        l, b = key[0], key[1]
+        got = to_f64(o_pre[l, cu[b]:cu[b + 1]]) if len(key) == 2 else to_f64(o_pre[l, cu[b] + key[2]])[None]
         assert np.isfinite(got).all(), f"prefill layer {l} instance {b}: non-finite output"
         err = np.abs(got - ref).max()
         rms = np.sqrt((ref ** 2).mean())

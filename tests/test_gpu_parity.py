@@ -203,6 +203,34 @@ def test_config2_full_size_sampled():
     assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
 
 
+def test_config3_batch16_shared_pages_sampled():
+    """Config 3 shape: batch 16, five 1000-token chunks each, drawn from a pool of 200 so that
+    instances share pages, question lengths uniform in 32..128.  Two layers resident; the oracle
+    checks instances {0, 7, 15}: three decode steps (all heads) and four question rows."""
+    case = chain.case_from_config(3, n_layers=2)
+    case.steps = 6
+    assert case.batch == 16 and len({c for r in case.retrieved for c in r}) < 80
+    inp = chain.make_attention_inputs(case)
+    o_pre, o_dec = chain.run_gpu_attention(case, inp)
+    pre, dec = chain.run_oracle_attention(case, inp, layers=[1], steps=[0, 2, 5], instances=[0, 7, 15],
+                                          prefill_rows=[0, 9, 31, 127])
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+    assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
+
+
+def test_config4_70b_shape_sampled():
+    """Config 4 shape: 64 query / 8 KV heads (group 8), 20 chunks x 1000 tokens, batch 4,
+    128-token questions.  Two layers resident; the oracle checks instances {0, 3}."""
+    case = chain.case_from_config(4, n_layers=2)
+    case.steps = 5
+    inp = chain.make_attention_inputs(case)
+    o_pre, o_dec = chain.run_gpu_attention(case, inp)
+    pre, dec = chain.run_oracle_attention(case, inp, layers=[0], steps=[0, 4], instances=[0, 3],
+                                          prefill_rows=[0, 64, 127])
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+    assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
+
+
 # ------------------------------------------------------------------ boundary behaviour ------
 def test_load_is_byte_exact_and_validates():
     from paper_2512_22195_amd import binding as mk
