@@ -187,6 +187,55 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3)}
 
+    # ------------------------------- other kernels: rates against their own rooflines -----------
+    other = None
+    if not args.roofline_only:
+        with torch.cuda.stream(cs):
+            # chunk materialization (ingest time in the paper; here: one chunk, every layer)
+            x_chunk = normal((shape.name, "x_chunk"), (L, Hd), vs, tdt, dev)
+            blob = torch.empty((nl, 2, Hkv, L, D), dtype=tdt, device=dev)
+            for l in range(min(nl, 4)):
+                ctx.materialize(x_chunk, w[l, 0], w[l, 1], L, 0, blob[l, 0], blob[l, 1], L)
+            a, b = ev(), ev()
+            a.record(cs)
+            for l in range(nl):
+                ctx.materialize(x_chunk, w[l, 0], w[l, 1], L, 0, blob[l, 0], blob[l, 1], L)
+            b.record(cs)
+            # question prefill attention alone
+            ctx.assemble(pages, q_lens, table)
+            for l in range(min(nl, 4)):
+                ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+            c, d = ev(), ev()
+            c.record(cs)
+            for l in range(nl):
+                ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+            d.record(cs)
+            # decode-token projection alone
+            for l in range(min(nl, 4)):
+                ctx.materialize_tail(x_dec[l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
+            e, f = ev(), ev()
+            e.record(cs)
+            for l in range(nl):
+                ctx.materialize_tail(x_dec[l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
+            f.record(cs)
+            cs.synchronize()
+        us_mat = a.elapsed_time(b) * 1e3 / nl
+        us_pre = c.elapsed_time(d) * 1e3 / nl
+        us_gemv = e.elapsed_time(f) * 1e3 / nl
+        fl_mat = 2.0 * L * Hd * 2 * Hkv * D
+        fl_pre = sum(4.0 * q * (n + (q + 1) / 2) * D * Hq for q, n in zip(q_lens, n_ctx))
+        by_gemv = 2 * Hkv * D * Hd * shape.elem_bytes + B * Hd * shape.elem_bytes
+        mfma_peak = 2500.0 if shape.dtype == "bf16" else 157.3
+        other = {
+            "materialize_chunk": {"tokens": L, "us_per_layer": round(us_mat, 2), "TFLOPs": round(fl_mat / us_mat / 1e6, 1),
+                                  "frac_of_mfma_peak": round(fl_mat / us_mat / 1e6 / mfma_peak, 4)},
+            "prefill_attn": {"us_per_layer": round(us_pre, 2), "TFLOPs": round(fl_pre / us_pre / 1e6, 1),
+                             "frac_of_mfma_peak": round(fl_pre / us_pre / 1e6 / mfma_peak, 4)},
+            "materialize_decode_token": {"us_per_layer": round(us_gemv, 2), "GBps": round(by_gemv / us_gemv / 1e3, 1),
+                                         "frac_of_hbm_peak": round(by_gemv / us_gemv / 1e3 / HBM_PEAK_GBPS, 4)},
+        }
+        del x_chunk, blob
+
     if args.calib_copy:
         with torch.cuda.stream(cs):
             src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -320,7 +369,7 @@ def main():
                    "batch": B, "cached_tokens": n_ctx if B > 1 else n_ctx[0], "decode_units": args.units, "decode_variant": args.variant},
         "phases_ms": {"assemble+materialize+prefill": round(ms_prefill, 3), "decode": round(ms_decode, 3),
                       "decode_us_per_layer_step": round(ms_decode * 1e3 / (steps_dec * nl), 3)},
-        "roofline": roofline, "kv_load": kv_load, "cpu_baseline": cpu,
+        "roofline": roofline, "other_kernels": other, "kv_load": kv_load, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
     ctx.graph_destroy(g_step)

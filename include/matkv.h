@@ -169,6 +169,14 @@ matkv_status matkv_sync(matkv_ctx* ctx, matkv_ticket t);
 matkv_status matkv_assemble(matkv_ctx* ctx, const matkv_page* pages_host,
                             const int32_t* n_pages_host, const int32_t* q_len_host,
                             const int64_t* pos_base_host, int32_t batch, void* table);
+/* Host-only preview of the decode work partition matkv_assemble builds for one instance of a
+ * batch of `batch` instances like it (no GPU is touched): page_tokens_host[n_pages] are the
+ * chunk lengths, q_len the question length.  Unit u streams unit_tokens_out[u] page tokens and
+ * is made of unit_items_out[u] page pieces; the last unit also owns the tail.  Returns the
+ * number of units (at most cap), or -1 on a bad argument.  Either output may be NULL. */
+int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tokens_host,
+                                int32_t n_pages, int32_t batch, int32_t q_len,
+                                int32_t* unit_tokens_out, int32_t* unit_items_out, int32_t cap);
 /* tail_len[b] += n for every instance of the table (a one-wave kernel; capturable). */
 matkv_status matkv_advance(matkv_ctx* ctx, void* table, int32_t n);
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_graph_begin", "matkv_graph_end",
-    "matkv_graph_launch", "matkv_graph_destroy",
+    "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units",
 ]
 
 
@@ -87,6 +87,9 @@ def _load_library():
     for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
         fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         fn.restype = c_int32
+    lib.matkv_plan_decode_units.argtypes = [cfgp, POINTER(c_int32), c_int32, c_int32, c_int32,
+                                            POINTER(c_int32), POINTER(c_int32), c_int32]
+    lib.matkv_plan_decode_units.restype = c_int32
     lib.matkv_graph_begin.argtypes = [c_void_p]; lib.matkv_graph_begin.restype = c_int32
     lib.matkv_graph_end.argtypes = [c_void_p, POINTER(c_void_p)]; lib.matkv_graph_end.restype = c_int32
     lib.matkv_graph_launch.argtypes = [c_void_p, c_void_p]; lib.matkv_graph_launch.restype = c_int32
@@ -132,6 +135,18 @@ def table_bytes(cfg: Config) -> int:
 
 def config_check(cfg: Config) -> int:
     return int(_lib.matkv_config_check(byref(cfg)))
+
+
+def plan_decode_units(cfg: Config, page_tokens, batch: int, q_len: int):
+    """(tokens, page pieces) of each decode unit matkv_assemble would build for one instance."""
+    n = len(page_tokens)
+    pt = (c_int32 * max(n, 1))(*page_tokens)
+    cap = 512
+    toks, its = (c_int32 * cap)(), (c_int32 * cap)()
+    made = _lib.matkv_plan_decode_units(byref(cfg), pt, n, batch, q_len, toks, its, cap)
+    if made < 0:
+        raise MatKVError(EINVAL, "matkv_plan_decode_units")
+    return list(toks[:made]), list(its[:made])
 
 
 def _ptr(t) -> int:

@@ -4,9 +4,9 @@
 // Both operands are contiguous along the contraction (hidden) axis, which is what the
 // matrix-core operand layout wants: a lane's 8 consecutive bf16 of one row.
 //
-// A workgroup owns 128 tokens x one head of K or of V (128 features, so both halves of every
-// rotary pair are in the tile), stepping 64 hidden columns at a time through double-buffered
-// LDS tiles.  Its four waves form a 2 x 2 grid of 64-token x 64-feature sub-tiles; a wave's
+// A workgroup owns 128 (or 64) tokens x one head of K or of V (128 features, so both halves of
+// every rotary pair are in the tile), stepping 64 hidden columns at a time through double-buffered
+// LDS tiles.  Its four waves form a 2 x 2 grid of sub-tiles 64 features wide; a wave's
 // features are the 16-wide blocks {2w, 2w+1} and their rotary partners {2w+4, 2w+5}, so the
 // rotation is lane-local on the fp32 accumulators.  One rounding to bf16 on store.
 #include "matkv_internal.h"
@@ -18,7 +18,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int D = 128, BM = 128, BK = 64;
+constexpr int D = 128, BK = 64;
 constexpr int LDS_STRIDE = BK + 8;          // bf16 per LDS row: 144 bytes, conflict-free 16-byte reads
 
 __device__ __forceinline__ uint4 ldg16(const void* p) {
@@ -78,7 +78,11 @@ __device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, f
     s = __builtin_amdgcn_sinf(fr);
 }
 
+// BM = token rows per workgroup (128, or 64 when 128-row tiles would leave compute units idle)
+template <int BM>
 __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int MI = BM / 32;              // 16-row token blocks per wave
+    constexpr int LR = BM / 32;              // staging rows per thread for the token tile
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][D * LDS_STRIDE];
 
@@ -94,30 +98,34 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
 
     // global -> LDS staging: thread t moves 16 bytes of rows t/8 + 32i (i < 4), columns 8*(t%8)
     const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
-    const uint16_t* xg[4];
+    const uint16_t* xg[LR];
     const uint16_t* wg[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LR; ++i) {
         const int r = min(row0 + ld_row + 32 * i, total_rows - 1);       // rows past the end repeat the last
         xg[i] = X + (size_t)r * a.Hd + ld_col;
-        wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
     }
-    uint4 xr[4], wr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
+    uint4 xr[LR], wr[4];
     auto load_global = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { xr[i] = ldg16(xg[i] + k0); wr[i] = ldg16(wg[i] + k0); }
+        for (int i = 0; i < LR; ++i) xr[i] = ldg16(xg[i] + k0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wr[i] = ldg16(wg[i] + k0);
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < LR; ++i)
             *reinterpret_cast<uint4*>(&As[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = xr[i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
             *reinterpret_cast<uint4*>(&Bs[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = wr[i];
-        }
     };
 
-    f32x4 acc[4][4];            // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
+    f32x4 acc[MI][4];           // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -130,17 +138,17 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
         if (ks + 1 < nk) load_global((ks + 1) * BK);
 #pragma unroll
         for (int k2 = 0; k2 < BK / 32; ++k2) {
-            bf16x8 av[4], bv[4];
+            bf16x8 av[MI], bv[4];
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-                av[mi] = *reinterpret_cast<const bf16x8*>(&As[buf][(64 * wm + 16 * mi + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
+            for (int mi = 0; mi < MI; ++mi)
+                av[mi] = *reinterpret_cast<const bf16x8*>(&As[buf][(16 * MI * wm + 16 * mi + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni) {
                 const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
                 bv[ni] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(16 * tn + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
             }
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
@@ -149,13 +157,13 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
         __syncthreads();
     }
 
-    // epilogue: lane holds tokens 64wm + 16mi + 4*g4 + i, features 16*tn + c16
+    // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16
     uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const RowDest d = resolve_row(a, row0 + 64 * wm + 16 * mi + 4 * g4 + i);
+            const RowDest d = resolve_row(a, row0 + 16 * MI * wm + 16 * mi + 4 * g4 + i);
             if (!d.valid) continue;
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
@@ -182,8 +190,12 @@ bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_r
 }
 
 hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s) {
-    dim3 grid(2 * a.Hkv, (total_rows + BM - 1) / BM), block(256);
-    hipLaunchKernelGGL(materialize_mfma_kernel, grid, block, 0, s, a, total_rows);
+    const dim3 block(256);
+    if (2 * a.Hkv * ((total_rows + 127) / 128) >= 256) {
+        hipLaunchKernelGGL(materialize_mfma_kernel<128>, dim3(2 * a.Hkv, (total_rows + 127) / 128), block, 0, s, a, total_rows);
+    } else {
+        hipLaunchKernelGGL(materialize_mfma_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), block, 0, s, a, total_rows);
+    }
     return hipGetLastError();
 }
 

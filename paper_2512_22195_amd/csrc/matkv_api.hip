@@ -580,6 +580,36 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     return MATKV_OK;
 }
 
+int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tokens, int32_t n_pages,
+                                int32_t batch, int32_t q_len, int32_t* unit_tokens_out,
+                                int32_t* unit_items_out, int32_t cap) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK) return -1;
+    if (n_pages < 0 || n_pages > cfg->max_pages || (n_pages > 0 && !page_tokens) || batch < 1 ||
+        batch > cfg->max_batch || q_len < 1 || q_len > cfg->max_tail_tokens || cap < 0)
+        return -1;
+    std::vector<matkv_page> pages((size_t)(n_pages > 0 ? n_pages : 1));
+    long inst_tokens = 0;
+    for (int p = 0; p < n_pages; ++p) {
+        if (page_tokens[p] < 1) return -1;
+        pages[p].slot = reinterpret_cast<const void*>((uintptr_t)0x1000);   // never dereferenced
+        pages[p].n_tokens = page_tokens[p];
+        pages[p].reserved = 0;
+        inst_tokens += page_tokens[p];
+    }
+    const int tail_est = q_len + (cfg->max_tail_tokens - q_len) / 2;
+    std::vector<Item> items((size_t)kMaxDecodeUnitsPerInstance + n_pages + 2);
+    std::vector<Unit> units((size_t)kMaxDecodeUnitsPerInstance);
+    int n_items = 0, n_units = 0;
+    const int made = build_units(pages.data(), n_pages, 0, choose_decode_units(*cfg, batch, inst_tokens + tail_est),
+                                 tail_est, cfg->max_tail_tokens, items.data(), &n_items, units.data(), &n_units);
+    for (int u = 0; u < made && u < cap; ++u) {
+        if (unit_tokens_out) unit_tokens_out[u] = units[u].page_tokens;
+        if (unit_items_out) unit_items_out[u] = units[u].n_items - units[u].has_tail;
+    }
+    return made < cap ? made : cap;
+}
+
 matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;

@@ -71,3 +71,30 @@ def test_null_context_is_an_error_not_a_crash(mk):
     assert mk.lib().matkv_destroy(None) == mk.EINVAL
     assert mk.lib().matkv_advance(None, None, 1) == mk.EINVAL
     assert mk.lib().matkv_last_error(None) == b"context is null"
+
+
+def test_decode_partition_covers_every_token_once_and_is_balanced(mk):
+    """Host logic of cache assembly: the units of an instance partition its page tokens
+    (nothing lost, nothing twice), in nearly equal shares, whatever the chunk lengths."""
+    cfg = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, 1, 10, 192)
+    toks, items = mk.plan_decode_units(cfg, [1000] * 10, batch=1, q_len=64)
+    assert sum(toks) == 10000 and len(toks) == 32                  # 8 KV heads x 32 units = 256 workgroups
+    body = toks[:-1]                                               # the last unit also streams the tail
+    assert max(body) - min(body) <= 8 and toks[-1] <= max(body)
+    assert all(1 <= i <= 2 for i in items[:-1])                    # a unit spans at most two 1000-token pages
+    # ragged chunk lengths, including a 1-token chunk; forced unit counts
+    for units in (1, 3, 7, 64):
+        cfg = mk.make_config(2, 8, 2, 128, 512, "bf16", 500000.0, 4, 6, 64, decode_units=units)
+        lens = [300, 77, 1, 129, 1000, 5]
+        toks, items = mk.plan_decode_units(cfg, lens, batch=3, q_len=9)
+        assert sum(toks) == sum(lens) and 1 <= len(toks) <= units
+        assert all(t >= 0 for t in toks) and all(i >= 0 for i in items)
+    # batch 16: one unit per (instance, KV head) pair is already 128 workgroups -> 2 units each
+    cfg = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, 16, 5, 192)
+    toks, _ = mk.plan_decode_units(cfg, [1000] * 5, batch=16, q_len=100)
+    assert len(toks) == 2 and sum(toks) == 5000
+    # no pages at all: a single unit that only owns the tail
+    toks, items = mk.plan_decode_units(cfg, [], batch=1, q_len=10)
+    assert toks == [0] and items == [0]
+    with pytest.raises(mk.MatKVError):
+        mk.plan_decode_units(cfg, [0, 5], batch=1, q_len=10)
