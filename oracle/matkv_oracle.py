@@ -20,13 +20,16 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "matkv_oracle.c")
-_LIB = os.path.join(_HERE, "libmatkv_oracle.so")
+_LIB = os.environ.get("MATKV_ORACLE_LIB") or os.path.join(_HERE, "libmatkv_oracle.so")
 
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (no fast-math: summation order is the source's)."""
+    """Compile the C oracle with gcc (no fast-math: summation order is the source's).
+    MATKV_ORACLE_LIB (used only by the mutation test of the pins) names a prebuilt library."""
+    if os.environ.get("MATKV_ORACLE_LIB"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
