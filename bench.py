@@ -182,10 +182,35 @@ def main():
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
+    # practical ceiling: a plain 16-byte-load read of the same number of bytes per launch, walking
+    # through the same blobs (one launch per layer's worth of bytes), captured and replayed alike
+    read_ceiling = None
+    if not args.roofline_only:
+        with torch.cuda.stream(cs):
+            flat = [slots[cid].view(torch.uint8).reshape(-1) for cid in chunk_ids]
+            per = min(bytes_per_launch, flat[0].numel()) // 16 * 16
+            regions = max(flat[0].numel() // per, 1)            # whole launches' worth per blob
+            ctx.graph_begin()
+            for l in range(nl):
+                f = flat[l % len(flat)]
+                off = ((l // len(flat)) % regions) * per
+                ctx.probe_read(f[off:off + per], per)
+            g_read = ctx.graph_end()
+            ctx.graph_launch(g_read)
+            c, d = ev(), ev()
+            c.record(cs)
+            for _ in range(5):
+                ctx.graph_launch(g_read)
+            d.record(cs)
+            cs.synchronize()
+            ctx.graph_destroy(g_read)
+        us_read = c.elapsed_time(d) * 1e3 / (5 * nl)
+        read_ceiling = {"bytes_per_launch": per, "us_per_launch": round(us_read, 3), "GBps": round(per / us_read / 1e3, 1)}
     roofline = {"bound": "hbm", "kernel": f"{kname} (matkv_decode_attn)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3)}
+                "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3),
+                "plain_read_probe": read_ceiling}
 
     # ------------------------------- other kernels: rates against their own rooflines -----------
     other = None

@@ -192,6 +192,14 @@ matkv_status matkv_prefill_attn(matkv_ctx* ctx, int32_t layer, const void* q, co
 matkv_status matkv_decode_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
                                const void* tail_k, const void* tail_v, void* out);
 
+/* ---- measurement aid ------------------------------------------------------------------------ */
+
+/* Streams `bytes` of device memory at `src` once with 16-byte loads (no output besides a
+ * checksum sink inside the workspace) on the compute stream: the practical ceiling of a read
+ * of that size on this device, to set beside the attention kernels' achieved bandwidth.
+ * src 16-byte aligned, bytes a multiple of 16. */
+matkv_status matkv_probe_read(matkv_ctx* ctx, const void* src, size_t bytes);
+
 /* ---- command capture: replay a fixed sequence of the calls above without host cost ------ */
 
 /* Between begin and end, calls to materialize_tail / advance / prefill_attn / decode_attn

@@ -26,7 +26,7 @@ EXPORTS = [
     "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_graph_begin", "matkv_graph_end",
-    "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units",
+    "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
 ]
 
 
@@ -90,6 +90,7 @@ def _load_library():
     lib.matkv_plan_decode_units.argtypes = [cfgp, POINTER(c_int32), c_int32, c_int32, c_int32,
                                             POINTER(c_int32), POINTER(c_int32), c_int32]
     lib.matkv_plan_decode_units.restype = c_int32
+    lib.matkv_probe_read.argtypes = [c_void_p, c_void_p, c_size_t]; lib.matkv_probe_read.restype = c_int32
     lib.matkv_graph_begin.argtypes = [c_void_p]; lib.matkv_graph_begin.restype = c_int32
     lib.matkv_graph_end.argtypes = [c_void_p, POINTER(c_void_p)]; lib.matkv_graph_end.restype = c_int32
     lib.matkv_graph_launch.argtypes = [c_void_p, c_void_p]; lib.matkv_graph_launch.restype = c_int32
@@ -263,6 +264,9 @@ class Context:
     def decode_attn(self, layer, q, table, tail_k, tail_v, out):
         self._check(_lib.matkv_decode_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
                                            _ptr(out)), "matkv_decode_attn")
+
+    def probe_read(self, src, nbytes):
+        self._check(_lib.matkv_probe_read(self._h, _ptr(src), nbytes), "matkv_probe_read")
 
     def graph_begin(self):
         self._check(_lib.matkv_graph_begin(self._h), "matkv_graph_begin")

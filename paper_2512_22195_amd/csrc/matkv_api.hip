@@ -670,6 +670,16 @@ matkv_status matkv_decode_attn(matkv_ctx* c, int32_t layer, const void* q, const
     return attn_common(c, "decode_attn", 0, layer, q, table, tail_k, tail_v, out);
 }
 
+matkv_status matkv_probe_read(matkv_ctx* c, const void* src, size_t bytes) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!src || !aligned16(src) || bytes == 0 || (bytes % 16)) return fail(c, MATKV_EINVAL, "probe_read: src / bytes");
+    // sink: the last word of the rotary-table page of the workspace (never read by any kernel)
+    unsigned* sink = reinterpret_cast<unsigned*>(c->workspace + c->wl.off_rope + 4096 - 4);
+    HIP_TRY(c, launch_probe_read(src, bytes, sink, c->compute));
+    return MATKV_OK;
+}
+
 // -------------------------------------------------------------------------------- graphs ----
 
 matkv_status matkv_graph_begin(matkv_ctx* c) {
