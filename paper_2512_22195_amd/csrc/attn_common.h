@@ -153,6 +153,72 @@ struct RowMap {
     int q_row;       // row of the packed Q / O tensors
 };
 
+// Last-arrival merge of all units' partials into the output rows (see finish_unit).
+template <typename T, int D, int NT, int CB, typename MapFn>
+__device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& unit, int cols_valid, int n_units, MapFn map) {
+    constexpr int PSTRIDE = kPartialStride(D);
+    constexpr int UPC = 32 / CB;                               // units per column and pass
+    const int tid = threadIdx.x;
+    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
+    for (int c0 = tid; c0 < cols_valid; c0 += NT * CB) {
+        float M[CB], Lsum[CB], ox[CB], oy[CB];
+        const float* src[CB];
+        int dd[CB];
+        RowMap rms[CB];
+        bool live[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            const int col = c0 + cb * NT;
+            live[cb] = col < cols_valid;
+            const int cc = live[cb] ? col : c0;
+            const int i = cc / (D / 2);
+            dd[cb] = (cc % (D / 2)) * 2;
+            rms[cb] = map(i);
+            src[cb] = a.partials + (((size_t)unit.unit0_inst * a.rows + rms[cb].slot_row) * a.Hq + rms[cb].head) * PSTRIDE;
+            M[cb] = kNegBig; Lsum[cb] = 0.f; ox[cb] = 0.f; oy[cb] = 0.f;
+        }
+        for (int u0 = 0; u0 < n_units; u0 += UPC) {
+            float2 av[CB][UPC], ml[CB][UPC];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) {
+                    const size_t uo = (size_t)min(u0 + k, n_units - 1) * ustride;
+                    ml[cb][k] = ld_agent2(src[cb] + uo + D);
+                    av[cb][k] = ld_agent2(src[cb] + uo + dd[cb]);
+                }
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                float mn = M[cb];
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) mn = fmaxf(mn, (u0 + k < n_units) ? ml[cb][k].x : kNegBig);
+                const float cold = fast_exp2(M[cb] - mn);
+                Lsum[cb] *= cold; ox[cb] *= cold; oy[cb] *= cold;
+                M[cb] = mn;
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) {
+                    const float c = (u0 + k < n_units) ? fast_exp2(ml[cb][k].x - mn) : 0.f;
+                    Lsum[cb] = fmaf(ml[cb][k].y, c, Lsum[cb]);
+                    ox[cb] = fmaf(av[cb][k].x, c, ox[cb]);
+                    oy[cb] = fmaf(av[cb][k].y, c, oy[cb]);
+                }
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            if (!live[cb]) continue;
+            const float inv = 1.0f / Lsum[cb];
+            T* op = reinterpret_cast<T*>(a.out) + ((size_t)rms[cb].q_row * a.Hq + rms[cb].head) * D + dd[cb];
+            if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<float2*>(op) = make_float2(ox[cb] * inv, oy[cb] * inv);
+            } else {
+                *reinterpret_cast<uint32_t*>(op) =
+                    (uint32_t)f32_to_bf16_rne(ox[cb] * inv) | ((uint32_t)f32_to_bf16_rne(oy[cb] * inv) << 16);
+            }
+        }
+    }
+}
+
 // Merge of one workgroup's per-wave states (already in LDS: accumulators sm_acc[w][row][..]
 // with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums sm_l[w][row]) into the
 // unit's partial, followed - in the last workgroup of this (instance, KV head, z index) to
@@ -202,47 +268,14 @@ __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& uni
     __syncthreads();
     if (!*sm_last) return;
 
-    // One pass, all loads in flight at once: a thread owns one pair of output elements, reads
-    // that pair and the (max, sum) of its row from up to MCH units, then folds them in.
-    constexpr int MCH = 32;
+    // A thread owns pairs of output elements (columns).  Per pass it takes CB of its columns and
+    // up to 32 / CB units and issues all those loads - the pairs and the (max, sum) of their rows -
+    // at once: one memory round trip per pass.  Few units (prefill) means many columns per pass.
     const int n_units = unit.n_units_inst;
-    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
-    for (int col = tid; col < cols_valid; col += NT) {
-        const int i = col / (D / 2), d = (col % (D / 2)) * 2;
-        const RowMap rm = map(i);
-        const float* src = a.partials + (((size_t)unit.unit0_inst * a.rows + rm.slot_row) * a.Hq + rm.head) * PSTRIDE;
-        float M = kNegBig, Lsum = 0.f, ox = 0.f, oy = 0.f;
-        for (int u0 = 0; u0 < n_units; u0 += MCH) {
-            float2 av[MCH], ml[MCH];
-#pragma unroll
-            for (int k = 0; k < MCH; ++k) {
-                const size_t uo = (size_t)min(u0 + k, n_units - 1) * ustride;
-                ml[k] = ld_agent2(src + uo + D);
-                av[k] = ld_agent2(src + uo + d);
-            }
-            float mn = M;
-#pragma unroll
-            for (int k = 0; k < MCH; ++k) mn = fmaxf(mn, (u0 + k < n_units) ? ml[k].x : kNegBig);
-            const float cold = fast_exp2(M - mn);
-            Lsum *= cold; ox *= cold; oy *= cold;
-            M = mn;
-#pragma unroll
-            for (int k = 0; k < MCH; ++k) {
-                const float c = (u0 + k < n_units) ? fast_exp2(ml[k].x - mn) : 0.f;
-                Lsum = fmaf(ml[k].y, c, Lsum);
-                ox = fmaf(av[k].x, c, ox);
-                oy = fmaf(av[k].y, c, oy);
-            }
-        }
-        const float inv = 1.0f / Lsum;
-        T* op = reinterpret_cast<T*>(a.out) + ((size_t)rm.q_row * a.Hq + rm.head) * D + d;
-        if constexpr (sizeof(T) == 4) {
-            *reinterpret_cast<float2*>(op) = make_float2(ox * inv, oy * inv);
-        } else {
-            *reinterpret_cast<uint32_t*>(op) =
-                (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
-        }
-    }
+    if (n_units <= 4)       merge_units<T, D, NT, 8>(a, unit, cols_valid, n_units, map);
+    else if (n_units <= 8)  merge_units<T, D, NT, 4>(a, unit, cols_valid, n_units, map);
+    else if (n_units <= 16) merge_units<T, D, NT, 2>(a, unit, cols_valid, n_units, map);
+    else                    merge_units<T, D, NT, 1>(a, unit, cols_valid, n_units, map);
     if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 

@@ -250,9 +250,8 @@ hipError_t launch_v(const AttnArgs& a, int tiles, hipStream_t s) {
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
     if (a.prefill) {
-        constexpr int MS = 2;
-        const int tiles = (a.rows * G + 16 * MS - 1) / (16 * MS);
-        return launch_v<G, 4, MS, 2>(a, tiles, s);
+        const int tiles = (a.rows * G + 31) / 32;
+        return launch_v<G, 4, 2, 2>(a, tiles, s);
     }
     // decode: variant 9000 + 10 * (blocks in flight) + waves
     switch (a.variant % 100) {
