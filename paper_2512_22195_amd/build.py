@@ -9,7 +9,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmatkv.so")
 
-SOURCES = ["matkv_api.hip", "attn_rows.hip", "attn_mfma.hip", "materialize.hip",
+SOURCES = ["matkv_api.hip", "attn_rows.hip", "attn_mfma.hip", "attn_prefill.hip", "materialize.hip",
            "materialize_mfma.hip"]
 
 

@@ -219,15 +219,16 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& uni
     }
 }
 
-// Merge of one workgroup's per-wave states (already in LDS: accumulators sm_acc[w][row][..]
-// with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums sm_l[w][row]) into the
+// Merge of one workgroup's NS partial states per row (already in LDS: accumulators
+// sm_acc[w][row][..] with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums
+// sm_l[w][row]; NS = the waves when they split the tokens, 1 when they split the rows) into the
 // unit's partial, followed - in the last workgroup of this (instance, KV head, z index) to
 // arrive - by the merge of all units' partials into the output rows.
 //
 // Partials are written and read with agent-scope accesses: every thread waits for its own
 // stores to complete, the barrier orders them before thread 0's ticket, and the last arrival
 // reads the partials back from memory.  No L2 write-back or invalidate is involved.
-template <typename T, int D, int NW, int ROWS, int ACC_STRIDE, typename MapFn>
+template <typename T, int D, int NW, int NS, int ROWS, int ACC_STRIDE, typename MapFn>
 __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& unit, int kvh, int zidx,
                                             const float* sm_acc, const float* sm_m, const float* sm_l,
                                             int* sm_last, int n_valid_rows, MapFn map) {
@@ -242,10 +243,10 @@ __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& uni
         const RowMap rm = map(i);
         float mn = sm_m[i];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) mn = fmaxf(mn, sm_m[w * ROWS + i]);
+        for (int w = 1; w < NS; ++w) mn = fmaxf(mn, sm_m[w * ROWS + i]);
         float ax = 0.f, ay = 0.f, lv = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
+        for (int w = 0; w < NS; ++w) {
             const float c = fast_exp2(sm_m[w * ROWS + i] - mn);
             const float* src = sm_acc + ((size_t)w * ROWS + i) * ACC_STRIDE + d;
             ax = fmaf(src[0], c, ax);

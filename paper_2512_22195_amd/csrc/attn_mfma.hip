@@ -233,7 +233,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
         rm.q_row = prefill ? q_row0 + r : q_row0;
         return rm;
     };
-    finish_unit<T, D, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
+    finish_unit<T, D, NW, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
 }
 
 template <int G, int NW, int MS, int PF>

@@ -1,0 +1,410 @@
+// Question prefill attention on the matrix cores, bf16, head_dim 128 (paper Section V-A "prefill
+// time": row i of the question attends to every chunk key and to question keys j <= i).
+//
+// The M dimension is the flattened (question row, query head of one KV head) index.  A
+// workgroup owns a tile of 64*MS such rows and one work unit of the cache; its four waves split
+// the ROWS (16*MS each) and walk the unit's tokens TOGETHER, 32 at a time: each K/V block is
+// fetched from HBM once per workgroup with coalesced 16-byte loads into double-buffered LDS
+// tiles and shared by all waves -
+//   S^T = K Q^T     A = K rows from the LDS tile (padded rows, conflict-free 16-byte reads),
+//                   B = Q held in registers
+//   softmax         online, per lane on its own column; the four 16-lane groups agree on the
+//                   running maximum through register swaps
+//   O^T += V^T P^T  A = V through the transposing LDS read, B = P rounded to bf16
+// Blocks are fetched two ahead of the one being used (one in registers, one in LDS), which keeps
+// two blocks per workgroup in flight against the memory latency.
+// A wave owns its rows outright, so nothing is merged between waves.  An instance whose cache
+// is one unit gets its output rows straight from the registers; otherwise every unit leaves an
+// unnormalised partial (accumulator, running maximum, sum) per row and a second, chip-wide
+// launch folds the units of each row together (the last-arrival merge of the decode kernels
+// would leave that work to a handful of compute units here: the partials of a question are
+// megabytes, not kilobytes).
+#include "attn_common.h"
+
+namespace matkv {
+namespace {
+
+using namespace attn;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128;
+constexpr int BLK = 32;             // token rows per step
+constexpr int KSTR = D + 8;         // bf16 per LDS row of the K tile
+constexpr int VSTR = D + 16;        // bf16 per LDS row of the V tile
+constexpr int NW = 4;
+constexpr float kLazyLog2 = 8.0f;     // slack of the running reference exponent, in powers of two
+
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
+    typedef s16x4 __attribute__((address_space(3))) * lptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)p);
+}
+
+template <int G, int MS>
+__global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
+        KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
+        const Unit* __restrict__ units) {
+    constexpr int WR = 16 * MS;                         // rows per wave
+    constexpr int RT = NW * WR;                         // rows per workgroup
+    typedef uint16_t T;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int kvh = blockIdx.y, tile = blockIdx.z;
+    const int m0 = tile * RT;
+
+    const Unit unit = units[blockIdx.x];
+    const InstanceInfo inst = insts[unit.inst];
+    const int n_m = inst.q_len * G;
+    if (m0 >= n_m) return;                              // whole workgroup leaves together
+    const int r_last = (min(m0 + RT, n_m) - 1) / G;
+    const bool wave_live = m0 + WR * wave < n_m;        // this wave has at least one real row
+
+    // Q in operand layout; padding rows repeat the last real row
+    bf16x8 bq[MS][4];
+    int vis[MS];                                        // tail rows this lane's row may see
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        const int m = min(m0 + WR * wave + 16 * j + c16, n_m - 1);
+        const int r = m / G, g = m % G;
+        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)(inst.cu_q + r) * a.Hq + (size_t)kvh * G + g) * D + 8 * g4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bq[j][c] = __builtin_bit_cast(bf16x8, ldg16(qp + 32 * c));
+        vis[j] = r + 1;
+    }
+
+    f32x4 ot[MS][8], ol[MS];          // O^T accumulators; row sums (every element of a lane the same)
+    float mrow[MS];                   // reference score of the lane's row, unscaled
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        mrow[j] = kNegBig;
+        ol[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ot[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    constexpr int TILE_ELEMS = BLK * KSTR + BLK * VSTR;             // one K tile + one V tile
+    __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * TILE_ELEMS];
+
+    // The unit's item list sits in LDS: fetching an item from global memory inside the loop
+    // would put a memory wait there that also drains the block loads in flight.
+    __shared__ __attribute__((aligned(16))) Item sm_items[kMaxPrefillItemsPerUnit];
+    for (int i = tid; i < unit.n_items * 2; i += NW * 64)
+        reinterpret_cast<uint4*>(sm_items)[i] = reinterpret_cast<const uint4*>(items + unit.item0)[i];
+    __syncthreads();
+
+    // Every wave walks the same blocks: the unit's items end to end (the tail clipped to the
+    // rows this tile may see), 32 token rows at a time, never across two items.
+    struct {
+        Item item;
+        int item_i, rows, left;         // current item, its visible rows, rows of it not yet handed out
+    } wk;
+    const int tail_visible = r_last + 1;
+    auto rows_of = [&](const Item& it) { return it.base ? it.ntok : min(min(it.ntok, tail_visible), a.max_tail); };
+    wk.item = unit.first; wk.item_i = 0; wk.rows = rows_of(wk.item); wk.left = wk.rows;
+    // Past the unit's end the previous block comes back marked invalid: still safe to load,
+    // so that the loop below can issue its loads unconditionally.
+    BlockRef<T> last_block;
+    last_block.valid = false; last_block.is_tail = false; last_block.k = nullptr; last_block.v = nullptr;
+    last_block.t0 = 0; last_block.tok_end = 0;
+    auto next_block = [&]() {
+        BlockRef<T> r = last_block;
+        r.valid = false;
+        while (wk.left <= 0) {
+            if (++wk.item_i >= unit.n_items) return r;
+            wk.item = sm_items[wk.item_i];
+            wk.rows = rows_of(wk.item);
+            wk.left = wk.rows;
+        }
+        if (wk.item.base) {
+            const size_t head_elems = (size_t)wk.item.page_tokens * D;
+            const T* blob = reinterpret_cast<const T*>(wk.item.base);
+            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+        } else {
+            const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
+            r.k = reinterpret_cast<const T*>(a.tail_k) + off;
+            r.v = reinterpret_cast<const T*>(a.tail_v) + off;
+            r.is_tail = true;
+        }
+        if (wk.item.base) r.is_tail = false;
+        const int n = min(BLK, wk.left);
+        r.t0 = wk.item.tok0 + (wk.rows - wk.left);
+        r.tok_end = r.t0 + n;
+        r.valid = true;
+        wk.left -= n;
+        last_block = r;
+        return r;
+    };
+
+    // cooperative staging: thread t moves rows t/16 and t/16 + 16, columns 8*(t%16), of K and of V
+    const int st_row = tid >> 4, st_col = (tid & 15) * 8;
+    struct Stage { uint4 k[2], v[2]; };
+    auto load_global = [&](const BlockRef<T>& r, Stage& g) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
+            g.k[i] = ldg16(r.k + off);
+            g.v[i] = ldg16(r.v + off);
+        }
+    };
+    auto store_lds = [&](int buf, const Stage& g) {
+        uint16_t* kt = tiles + buf * TILE_ELEMS;
+        uint16_t* vt = kt + BLK * KSTR;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<uint4*>(kt + (st_row + 16 * i) * KSTR + st_col) = g.k[i];
+            *reinterpret_cast<uint4*>(vt + (st_row + 16 * i) * VSTR + st_col) = g.v[i];
+        }
+    };
+
+    // Scores stay unscaled until the exponent: 2^((s - m) c) is one multiply-add and one
+    // exponential per element, with m the row's reference score (unscaled too).  The row sums
+    // come from the matrix cores as well - P times a block of ones - which sums the weights
+    // exactly as the output uses them (rounded to bf16) and spares the vector ALU the adds.
+    const float sc = a.scale_log2e;
+    const float lazy_raw = kLazyLog2 / sc;
+    bf16x8 ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+
+    // masked: the block is ragged or lies in the tail (per-row causal limit); otherwise all 32
+    // rows are visible to every question row and no element needs a test.
+    auto compute = [&](const BlockRef<T>& r, int buf) {
+        const bool masked = r.is_tail || r.tok_end - r.t0 != BLK;
+        const uint16_t* kt = tiles + buf * TILE_ELEMS;
+        const uint16_t* vt = kt + BLK * KSTR;
+        bf16x8 ak[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                ak[h][c] = *reinterpret_cast<const bf16x8*>(kt + (16 * h + c16) * KSTR + 32 * c + 8 * g4);
+        f32x4 sc0[MS], sc1[MS];
+#pragma unroll
+        for (int j = 0; j < MS; ++j) {
+            sc0[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                sc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][c], bq[j][c], sc0[j], 0, 0, 0);
+                sc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][c], bq[j][c], sc1[j], 0, 0, 0);
+            }
+        }
+        bf16x8 pb[MS];
+#pragma unroll
+        for (int j = 0; j < MS; ++j) {
+            // lane holds tokens t0 + 4*g4 + i (sc0) and t0 + 16 + 4*g4 + i (sc1) of its row
+            float sv[8] = {sc0[j][0], sc0[j][1], sc0[j][2], sc0[j][3], sc1[j][0], sc1[j][1], sc1[j][2], sc1[j][3]};
+            if (masked) {           // wave-uniform
+                const int limit = r.is_tail ? min(r.tok_end, vis[j]) : r.tok_end;
+                const int tb = r.t0 + 4 * g4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    sv[i] = tb + i < limit ? sv[i] : kNegBig;
+                    sv[4 + i] = tb + 16 + i < limit ? sv[4 + i] : kNegBig;
+                }
+            }
+            float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            mx = fmaxf(mx, lane_xor(mx, 16, lane));
+            mx = fmaxf(mx, lane_xor(mx, 32, lane));
+            // The reference score of a row moves only when the block's maximum exceeds it by
+            // more than kLazyLog2 powers of two: weights stay below 2^kLazyLog2, and the
+            // accumulators are rescaled on few blocks instead of on most.
+            const float mn = mx > mrow[j] + lazy_raw ? mx : mrow[j];
+            const float alpha = fast_exp2((mrow[j] - mn) * sc);
+            mrow[j] = mn;
+            // a row that has seen no key yet keeps the floor as its reference; its masked
+            // scores must still come out as weight 0, not 2^0
+            const float nmc = mn > 0.5f * kNegBig ? -mn * sc : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)fast_exp2(fmaf(sv[i], sc, nmc));
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's reference moved
+                ol[j][0] *= alpha;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    ot[j][s][0] *= alpha; ot[j][s][1] *= alpha; ot[j][s][2] *= alpha; ot[j][s][3] *= alpha;
+                }
+            }
+            ol[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j], ol[j], 0, 0, 0);
+        }
+        // lane (c16, g4) names 4 dims (4*(c16%4) ..) of token 4*g4 + c16/4 (+16 for the second
+        // half) and receives dim 16s + c16 of tokens 4*g4 .. 4*g4+3: the k order of P above
+        const uint16_t* vp = vt + (4 * g4 + (c16 >> 2)) * VSTR + 4 * (c16 & 3);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const s16x4 lo = lds_read_tr(vp + 16 * s);
+            const s16x4 hi = lds_read_tr(vp + 16 * VSTR + 16 * s);
+            const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int j = 0; j < MS; ++j)
+                ot[j][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j], ot[j][s], 0, 0, 0);
+        }
+    };
+    // Steady state at the top of the loop: LDS tile 0 holds block r0, stage B holds r1 (its
+    // loads possibly still in flight).  Each half step issues the loads of the block two ahead,
+    // computes, hands the staged block to the other tile and meets the other waves.  Loads and
+    // LDS stores are unconditional (a block past the end repeats the last one): a load under a
+    // branch would leave the compiler no exact count of the loads in flight, and it would then
+    // wait for all of them.
+    BlockRef<T> r0 = next_block();
+    if (r0.valid) {
+        Stage ga, gb;
+        BlockRef<T> r1 = next_block();
+        load_global(r0, ga);
+        load_global(r1, gb);
+        store_lds(0, ga);
+        // Every load so far (Q above all) is waited for here, once: otherwise each first use of
+        // Q inside the loop is guarded with a wait that, loads completing in order, would also
+        // drain the blocks just requested.
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0) only
+        lds_barrier();
+        // one exit, at the bottom: a break half way would, after the compiler has given the loop
+        // its single latch, make stage A look in flight at the top of the loop
+        do {
+            const BlockRef<T> r2 = next_block();
+            load_global(r2, ga);
+            if (wave_live) compute(r0, 0);
+            store_lds(1, gb);
+            lds_barrier();
+            const BlockRef<T> r3 = next_block();
+            load_global(r3, gb);
+            if (wave_live && r1.valid) compute(r1, 1);
+            store_lds(0, ga);
+            lds_barrier();
+            r0 = r2;
+            r1 = r3;
+        } while (r0.valid);
+    }
+    if (!wave_live) return;
+
+    // ---- a wave owns its rows: results leave straight from the registers ----
+    // lane (c16, g4) holds, for row 16j + c16 of the wave, dims 16s + 4*g4 + {0..3}
+    const bool single = unit.n_units_inst == 1;
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        const int m = m0 + WR * wave + 16 * j + c16;
+        if (m >= n_m) continue;
+        const int r = m / G, head = kvh * G + m % G;
+        if (single) {
+            const float inv = 1.0f / ol[j][0];
+            T* op = reinterpret_cast<T*>(a.out) + ((size_t)(inst.cu_q + r) * a.Hq + head) * D + 4 * g4;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                uint2 w;
+                w.x = (uint32_t)f32_to_bf16_rne(ot[j][s][0] * inv) | ((uint32_t)f32_to_bf16_rne(ot[j][s][1] * inv) << 16);
+                w.y = (uint32_t)f32_to_bf16_rne(ot[j][s][2] * inv) | ((uint32_t)f32_to_bf16_rne(ot[j][s][3] * inv) << 16);
+                *reinterpret_cast<uint2*>(op + 16 * s) = w;
+            }
+        } else {
+            float* prow = a.partials + (((size_t)blockIdx.x * a.rows + r) * a.Hq + head) * kPartialStride(D);
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                *reinterpret_cast<float4*>(prow + 16 * s + 4 * g4) = make_float4(ot[j][s][0], ot[j][s][1], ot[j][s][2], ot[j][s][3]);
+            if (g4 == 0) *reinterpret_cast<float2*>(prow + D) = make_float2(mrow[j] * sc, ol[j][0]);
+        }
+    }
+}
+
+// Folds the units' partials of every (question row, query head) of instances cut into several
+// units: out = sum_u 2^(m_u - M) acc_u / sum_u 2^(m_u - M) l_u,  M = max_u m_u.
+// Half a wave owns one row: lane k first fetches (m, l) of unit k, the half wave agrees on M
+// and on every unit's weight, then each lane accumulates its 4 dims over the units.
+__global__ __launch_bounds__(256) void prefill_merge_kernel(
+        KernelArgs a, const InstanceInfo* __restrict__ insts, int batch, int total_pairs) {
+    constexpr int PS = kPartialStride(D);
+    const int lane = threadIdx.x & 63, hl = lane & 31;
+    const int pair = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
+    const bool in_range = pair < total_pairs;
+    const int q_row = in_range ? pair / a.Hq : 0, head = in_range ? pair % a.Hq : 0;
+    int b = 0;
+    for (int i = 1; i < batch; ++i) if (q_row >= insts[i].cu_q) b = i;
+    const InstanceInfo inst = insts[b];
+    const int n_units = (in_range && inst.n_punits > 1) ? inst.n_punits : 0;     // 0: nothing to do
+    const float* base = a.partials + (((size_t)inst.punit0 * a.rows + (q_row - inst.cu_q)) * a.Hq + head) * PS;
+    const size_t ustride = (size_t)a.rows * a.Hq * PS;
+
+    float2 ml = make_float2(kNegBig, 0.f);
+    if (hl < n_units) ml = *reinterpret_cast<const float2*>(base + (size_t)hl * ustride + D);
+    float M = ml.x;
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float w = hl < n_units ? fast_exp2(ml.x - M) : 0.f;
+    float L = w * ml.y;
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) L += __shfl_xor(L, off);
+
+    // both halves of the wave run the same number of steps (shuffles need every lane)
+    const int steps = max(n_units, __shfl_xor(n_units, 32));
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u0 = 0; u0 < steps; u0 += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int u = min(u0 + k, max(n_units, 1) - 1);
+            v[k] = *reinterpret_cast<const float4*>(base + (size_t)u * ustride + 4 * hl);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float c = __shfl(w, (lane & 32) + ((u0 + k) & 31));
+            const float cc = (u0 + k < n_units) ? c : 0.f;
+            acc.x = fmaf(v[k].x, cc, acc.x); acc.y = fmaf(v[k].y, cc, acc.y);
+            acc.z = fmaf(v[k].z, cc, acc.z); acc.w = fmaf(v[k].w, cc, acc.w);
+        }
+    }
+    if (n_units == 0) return;
+    const float inv = 1.0f / L;
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(acc.x * inv) | ((uint32_t)f32_to_bf16_rne(acc.y * inv) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(acc.z * inv) | ((uint32_t)f32_to_bf16_rne(acc.w * inv) << 16);
+    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ((size_t)q_row * a.Hq + head) * D + 4 * hl) = o;
+}
+
+template <int G, int MS>
+hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
+    const KernelArgs k = make_kernel_args(a);
+    const int tiles = (a.rows * G + NW * 16 * MS - 1) / (NW * 16 * MS);
+    dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
+    hipLaunchKernelGGL((attn_prefill_kernel<G, MS>), grid, block, 0, s, k,
+                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
+                       reinterpret_cast<const Item*>(a.table + a.off_items),
+                       reinterpret_cast<const Unit*>(a.table + a.off_units));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.max_units_inst <= 1) return e;
+    const int total_pairs = a.total_q * a.Hq;
+    hipLaunchKernelGGL(prefill_merge_kernel, dim3((total_pairs + 7) / 8), dim3(256), 0, s, k,
+                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst), a.batch, total_pairs);
+    return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
+    if (a.rows * G <= 64) return launch_v<G, 1>(a, s);
+    return launch_v<G, 2>(a, s);
+}
+
+}  // namespace
+
+bool attn_prefill_supported(const AttnArgs& a, int dtype) {
+    const int g = a.Hq / a.Hkv;
+    return a.prefill && dtype == MATKV_BF16 && a.D == 128 && (g == 1 || g == 2 || g == 4 || g == 8) &&
+           a.max_unit_items <= kMaxPrefillItemsPerUnit;
+}
+
+hipError_t launch_attn_prefill(const AttnArgs& a, int dtype, hipStream_t s) {
+    if (a.n_units <= 0) return hipSuccess;
+    if (!attn_prefill_supported(a, dtype)) return hipErrorInvalidValue;
+    switch (a.Hq / a.Hkv) {
+        case 1: return launch_g<1>(a, s);
+        case 2: return launch_g<2>(a, s);
+        case 4: return launch_g<4>(a, s);
+        case 8: return launch_g<8>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace matkv

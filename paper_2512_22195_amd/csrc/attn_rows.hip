@@ -277,7 +277,7 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
         rm.slot_row = row; rm.head = kvh * G + g; rm.q_row = q_row;
         return rm;
     };
-    finish_unit<T, D, NW, G, D>(a, unit, kvh, row, &sm_acc[0][0][0], &sm_m[0][0], &sm_l[0][0], &sm_last, G, map);
+    finish_unit<T, D, NW, NW, G, D>(a, unit, kvh, row, &sm_acc[0][0][0], &sm_m[0][0], &sm_l[0][0], &sm_last, G, map);
 }
 
 template <typename T, int D, int G, int NW, int U>

@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
     const int nk = a.Hd / BK;
     load_global(0);
     store_lds(0);
-    __syncthreads();
+    lds_barrier();
     for (int ks = 0; ks < nk; ++ks) {
         const int buf = ks & 1;
         if (ks + 1 < nk) load_global((ks + 1) * BK);
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
         }
         if (ks + 1 < nk) store_lds(buf ^ 1);
-        __syncthreads();
+        lds_barrier();
     }
 
     // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -34,6 +35,8 @@ struct SlotState {
 
 struct TableHost {
     int batch = 0, n_items = 0, n_dunits = 0, n_punits = 0, total_q = 0, max_q = 0;
+    int max_punits_inst = 0;  // most prefill units of any one instance
+    int max_punit_items = 0;  // most items of any one prefill unit
     int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
     int min_tail_len = 0;
 };
@@ -141,6 +144,25 @@ int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
     if (u < 1) u = 1;
     if (u > kMaxDecodeUnitsPerInstance) u = kMaxDecodeUnitsPerInstance;
     return u;
+}
+
+// Units one instance's cache is cut into for the question prefill.  The matrix-core kernel runs
+// one workgroup per (unit, KV head, 128-row tile); every extra unit costs a partial per question
+// row, so only as many as it takes to give each compute unit its two resident workgroups, and
+// none shorter than 256 tokens.  The other kernels launch a workgroup per question row and want few units.
+int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long tokens) {
+    constexpr long kTargetWorkgroups = 512;      // two resident workgroups per compute unit
+    const int g = cfg.n_q_heads / cfg.n_kv_heads;
+    const bool mfma = cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && (g == 1 || g == 2 || g == 4 || g == 8);
+    long pu;
+    if (mfma) {
+        const long wgs_per_unit = std::max<long>(1, tiles_in_batch * cfg.n_kv_heads);
+        pu = (kTargetWorkgroups + wgs_per_unit - 1) / wgs_per_unit;
+        pu = std::min<long>(pu, tokens / 256);
+    } else {
+        pu = tokens / 1024;
+    }
+    return (int)std::max<long>(1, std::min<long>(pu, kMaxPrefillUnitsPerInstance));
 }
 
 // Cuts one instance's cache (its pages in order, then its tail) into n_units runs of nearly
@@ -532,6 +554,9 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     int n_items = 0, n_dunits = 0, n_punits = 0, cu = 0, max_q = 0;
     TableHost th;
     th.min_tail_len = cfg.max_tail_tokens;
+    long prefill_tiles = 0;            // 128-row tiles of (question row, query head of one KV head) over the batch
+    for (int b = 0; b < batch; ++b)
+        prefill_tiles += ((long)q_len[b] * (cfg.n_q_heads / cfg.n_kv_heads) + 127) / 128;
     for (int b = 0; b < batch; ++b) {
         InstanceInfo& in = insts[b];
         memset(&in, 0, sizeof(in));
@@ -555,13 +580,14 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         in.dunit0 = n_dunits;
         in.n_dunits = build_units(pg, n_pages[b], b, choose_decode_units(cfg, batch, inst_tokens + tail_est),
                                   tail_est, cfg.max_tail_tokens, items, &n_items, dunits, &n_dunits);
-        // prefill: coarse partition (the question rows supply the parallelism)
-        int pu = (int)((inst_tokens + tail_est) / 1024);
-        if (pu < 1) pu = 1;
-        if (pu > kMaxPrefillUnitsPerInstance) pu = kMaxPrefillUnitsPerInstance;
+        // prefill: coarse partition (the question rows supply most of the parallelism)
+        const int pu = choose_prefill_units(cfg, prefill_tiles, inst_tokens + q_len[b]);
         in.punit0 = n_punits;
         in.n_punits = build_units(pg, n_pages[b], b, pu, q_len[b], cfg.max_tail_tokens, items, &n_items,
                                   punits, &n_punits);
+        if (in.n_punits > th.max_punits_inst) th.max_punits_inst = in.n_punits;
+        for (int u = in.punit0; u < n_punits; ++u)
+            if (punits[u].n_items > th.max_punit_items) th.max_punit_items = punits[u].n_items;
     }
     hdr->batch = batch; hdr->n_items = n_items; hdr->n_dunits = n_dunits; hdr->n_punits = n_punits;
     hdr->total_q = cu; hdr->max_q = max_q;
@@ -651,11 +677,15 @@ static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int
     a.prefill = prefill;
     a.rows = prefill ? th->max_q : 1;
     a.n_units = prefill ? th->n_punits : th->n_dunits;
+    a.max_units_inst = prefill ? th->max_punits_inst : 0;
+    a.batch = th->batch; a.total_q = th->total_q;
+    a.max_unit_items = prefill ? th->max_punit_items : 0;
     a.scale_log2e = c->scale_log2e;
     a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
     a.off_units = prefill ? c->tl.off_punits : c->tl.off_dunits;
     const bool want_mfma = prefill || a.variant == 0 || a.variant >= 9000;
-    if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
+    if (attn_prefill_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_prefill(a, c->cfg.dtype, c->compute));
+    else if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
     else HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
 }

@@ -16,6 +16,7 @@ namespace matkv {
 
 constexpr int kMaxDecodeUnitsPerInstance = 256;
 constexpr int kMaxPrefillUnitsPerInstance = 32;
+constexpr int kMaxPrefillItemsPerUnit = 64;      // item list the matrix-core prefill kernel keeps in LDS
 
 struct Item {              // 32 bytes: a run of tokens inside one page, or the tail
     uint64_t base;         // device address of the page's blob; 0 = the instance's tail
@@ -125,6 +126,9 @@ struct AttnArgs {
     int32_t max_tail;
     int32_t rows;              // 1 = decode; > 1 = prefill rows (grid.z)
     int32_t n_units;           // grid.x
+    int32_t max_units_inst;    // most units any one instance is cut into
+    int32_t batch, total_q;    // instances; rows of the packed Q / O tensors (prefill)
+    int32_t max_unit_items;    // most items in any one unit of this launch
     int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail
     float scale_log2e;
     int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
@@ -132,7 +136,18 @@ struct AttnArgs {
     size_t off_inst, off_items, off_units;
 };
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wave (loads and stores share one counter on this chip), which
+// drains a register-staged prefetch at every step; this one leaves those loads in flight.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 hipError_t launch_attn_rows(const AttnArgs& a, int dtype, hipStream_t s);     // plain ALU, any dtype
+bool attn_prefill_supported(const AttnArgs& a, int dtype);
+hipError_t launch_attn_prefill(const AttnArgs& a, int dtype, hipStream_t s);  // matrix cores, rows split over waves
 bool attn_mfma_supported(const AttnArgs& a, int dtype);
 hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s);     // matrix cores, bf16 D=128
 

@@ -297,8 +297,15 @@ def run_oracle_chain(case: Case, inp):
 def tolerances(dtype: str):
     """(max-abs gate, relative-to-rms gate) for attention outputs: the stated bars (1e-5 fp32,
     1e-2 bf16 inputs with fp32 accumulation) plus a relative gate, because with near-uniform
-    softmax the outputs are far smaller than the absolute bar."""
+    softmax the outputs are far smaller than the absolute bar.  For bf16 the relative gate is
+    applied per element with half an ulp of the stored output (2^-8 |ref|) added: an output
+    several times the rms is rounded by more than the rms gate alone allows."""
     return (1e-5, 1e-4) if dtype == "f32" else (1e-2, 2e-2)
+
+
+def store_slack(dtype: str, ref):
+    """Per-element allowance for the one rounding of the output to its storage type."""
+    return 1e-7 if dtype == "f32" else 2.0 ** -8 * np.abs(ref)
 
 
 def compare_attention(case: Case, o_pre, o_dec, pre, dec):
@@ -313,7 +320,7 @@ def compare_attention(case: Case, o_pre, o_dec, pre, dec):
         err = np.abs(got - ref).max()
         rms = np.sqrt((ref ** 2).mean())
         assert err <= atol, f"prefill layer {l} inst {b}: max abs {err:.3e} > {atol}"
-        assert err <= rtol * rms + (1e-7 if case.dtype == "f32" else 0), \
+        assert (np.abs(got - ref) <= rtol * rms + store_slack(case.dtype, ref)).all(), \
             f"prefill layer {l} inst {b}: max abs {err:.3e} vs rms {rms:.3e}"
         worst = max(worst, err)
     for (t, l, b), ref in dec.items():
@@ -322,7 +329,7 @@ def compare_attention(case: Case, o_pre, o_dec, pre, dec):
         err = np.abs(got - ref).max()
         rms = np.sqrt((ref ** 2).mean())
         assert err <= atol, f"decode step {t} layer {l} inst {b}: max abs {err:.3e} > {atol}"
-        assert err <= rtol * rms + (1e-7 if case.dtype == "f32" else 0), \
+        assert (np.abs(got - ref) <= rtol * rms + store_slack(case.dtype, ref)).all(), \
             f"decode step {t} layer {l} inst {b}: max abs {err:.3e} vs rms {rms:.3e}"
         worst = max(worst, err)
     return worst

@@ -146,6 +146,34 @@ def test_attention_peaked_and_needle():
     _attention_parity(case)
 
 
+def test_prefill_mixed_unit_counts_and_row_tiles():
+    """Matrix-core prefill with a batch whose instances are cut differently: a long cache
+    (several units, folded by the second launch), a short one (one unit, output written
+    directly) and one without pages; question lengths that give one partly filled 128-row tile,
+    two tiles, and a single row; chunk lengths that leave ragged 32-token blocks."""
+    case = Case("prefill-mixed", n_layers=2, Hq=8, Hkv=2, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 1203, 1: 997, 2: 85}, retrieved=[[0, 1, 0], [2], []],
+                q_lens=[41, 19, 1], steps=1, scale=0.5)
+    _attention_parity(case)
+
+
+def test_prefill_group8_two_row_tiles():
+    """Group of 8 query heads per KV head: 23 question rows make 184 (row, head) rows, i.e. one
+    full 128-row tile and one ragged one, over a cache cut into several units."""
+    case = Case("prefill-g8", n_layers=1, Hq=16, Hkv=2, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 700, 1: 333}, retrieved=[[0, 1]], q_lens=[23], steps=1, scale=0.5)
+    _attention_parity(case)
+
+
+def test_prefill_many_small_pages_takes_the_other_kernel():
+    """More pages in one unit than the item list of the row-parallel prefill kernel holds
+    (64): the launch falls back to the token-parallel matrix-core kernel."""
+    lens = {i: 3 + (i % 4) for i in range(90)}
+    case = Case("prefill-small-pages", n_layers=1, Hq=8, Hkv=2, D=128, hidden=64, dtype="bf16",
+                chunk_lens=lens, retrieved=[list(range(90))], q_lens=[9], steps=1, scale=0.5)
+    _attention_parity(case)
+
+
 def test_attention_no_pages_and_full_tail():
     """Degenerate caches: an instance that retrieved nothing (plain causal attention over its
     own tokens) and a tail filled to its capacity."""
