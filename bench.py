@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="decode kernel shape (waves*100 + loads in flight); 0 = default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
+    ap.add_argument("--unfused", action="store_true",
+                    help="decode steps as matkv_materialize_tail + matkv_decode_attn instead of matkv_decode_step")
     ap.add_argument("--decode-only-reps", type=int, default=20)
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the decode-attention leg, launched eagerly (short run for rocprofv3 --pmc)")
@@ -98,19 +100,35 @@ def main():
             ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
             ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
 
+    # does matkv_decode_step run as one kernel here?  (bf16, head_dim 128, hidden % 4096, default shape)
+    fused_kernel = (not args.unfused and shape.dtype == "bf16" and D == 128 and Hd % 4096 == 0
+                    and args.variant == 0 and B <= 4 and Hq // Hkv <= 4)
+
     # one decode step of all layers, recorded once, replayed for every step
     with torch.cuda.stream(cs):
         ctx.assemble(pages, q_lens, table)
         ctx.graph_begin()
         ctx.advance(table, 1)
         for l in range(nl):
-            ctx.materialize_tail(x_dec[l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
-            ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            if args.unfused:
+                ctx.materialize_tail(x_dec[l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
+                ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            else:
+                ctx.decode_step(l, x_dec[l], w[l, 0], w[l, 1], q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
         g_step = ctx.graph_end()
+        # the dominant kernel alone, every layer, tail length fixed: the fused step (projection
+        # of the new token + decode attention), or the attention launch when run unfused
+        ctx.graph_begin()
+        for l in range(nl):
+            if fused_kernel:
+                ctx.decode_step(l, x_dec[l], w[l, 0], w[l, 1], q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            else:
+                ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+        g_attn = ctx.graph_end()
         ctx.graph_begin()
         for l in range(nl):
             ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
-        g_attn = ctx.graph_end()
+        g_attn_only = ctx.graph_end()
 
     def one_pass():
         prefill_phase()
@@ -156,7 +174,10 @@ def main():
         def attn_all_layers():
             if args.roofline_only:          # eager launches: one dispatch per layer, no graph
                 for l in range(nl):
-                    ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+                    if fused_kernel:
+                        ctx.decode_step(l, x_dec[l], w[l, 0], w[l, 1], q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+                    else:
+                        ctx.decode_attn(l, q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
             else:
                 ctx.graph_launch(g_attn)
         for _ in range(1 if args.roofline_only else 3):
@@ -172,12 +193,30 @@ def main():
     us_per_launch = a.elapsed_time(b) * 1e3 / (args.decode_only_reps * nl)
     kv_tok_bytes = shape.kv_bytes_per_token_layer()
     n_ctx = [sum(L for _ in r) for r in retrieved]
-    bytes_per_launch = sum((n + t) * kv_tok_bytes for n, t in zip(n_ctx, mid_tail)) + 2 * B * Hq * D * shape.elem_bytes
+    attn_bytes = sum((n + t) * kv_tok_bytes for n, t in zip(n_ctx, mid_tail)) + 2 * B * Hq * D * shape.elem_bytes
+    proj_bytes = (2 * Hkv * D * Hd + B * Hd) * shape.elem_bytes       # W_k, W_v once, the hidden rows
+    bytes_per_launch = attn_bytes + (proj_bytes if fused_kernel else 0)
     achieved = bytes_per_launch / (us_per_launch * 1e-6) / 1e9
     kname = "attn_rows_kernel" if 0 < args.variant < 9000 or shape.dtype != "bf16" or D != 128 else "attn_mfma_kernel"
+    entry = "matkv_decode_step" if fused_kernel else "matkv_decode_attn"
+    # the attention launch on its own, for comparison with the fused step
+    attn_only = None
+    if fused_kernel and not args.roofline_only:
+        with torch.cuda.stream(cs):
+            ctx.graph_launch(g_attn_only)
+            c, d = ev(), ev()
+            c.record(cs)
+            for _ in range(args.decode_only_reps):
+                ctx.graph_launch(g_attn_only)
+            d.record(cs)
+            cs.synchronize()
+        us_attn = c.elapsed_time(d) * 1e3 / (args.decode_only_reps * nl)
+        attn_only = {"us_per_launch": round(us_attn, 3), "bytes_per_launch": attn_bytes,
+                     "GBps": round(attn_bytes / us_attn / 1e3, 1),
+                     "frac_of_hbm_peak": round(attn_bytes / us_attn / 1e3 / HBM_PEAK_GBPS, 4)}
     # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same workload
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"decode_attn_config{args.config}_hbm_traffic.txt")
+    tfile = os.path.join(ROOT, "profiles", f"{'decode_step' if fused_kernel else 'decode_attn'}_config{args.config}_hbm_traffic.txt")
     if args.units == 0 and args.variant == 0 and os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -206,11 +245,11 @@ def main():
             ctx.graph_destroy(g_read)
         us_read = c.elapsed_time(d) * 1e3 / (5 * nl)
         read_ceiling = {"bytes_per_launch": per, "us_per_launch": round(us_read, 3), "GBps": round(per / us_read / 1e3, 1)}
-    roofline = {"bound": "hbm", "kernel": f"{kname} (matkv_decode_attn)",
+    roofline = {"bound": "hbm", "kernel": f"{kname} ({entry})",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "us_per_launch": round(us_per_launch, 3),
-                "plain_read_probe": read_ceiling}
+                "plain_read_probe": read_ceiling, "decode_attn_alone": attn_only}
 
     # ------------------------------- other kernels: rates against their own rooflines -----------
     other = None

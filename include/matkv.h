@@ -12,6 +12,7 @@
  *   matkv_assemble          page table of a batch, no data movement      (IV, put_KV)
  *   matkv_prefill_attn      question rows over [chunks | question]       (V-A "prefill time")
  *   matkv_decode_attn       newest token over [chunks | tail]            (V-A "decode time")
+ *   matkv_decode_step       new token's K/V projection + decode attention, one launch
  *
  * Conventions
  *   - Plain C ABI.  Pointers are DEVICE pointers unless the name or the comment
@@ -191,6 +192,21 @@ matkv_status matkv_prefill_attn(matkv_ctx* ctx, int32_t layer, const void* q, co
  * q/out: [batch][Hq][D]. */
 matkv_status matkv_decode_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
                                const void* tail_k, const void* tail_v, void* out);
+/* One decode step of one layer in a single launch (Section III-B steps 2-3 for the new token,
+ * then Section V-A's decode attention): the same result as
+ *   matkv_materialize_tail(hidden, w_k, w_v, table, 1, tail_k, tail_v) followed by
+ *   matkv_decode_attn(layer, q, table, tail_k, tail_v, out),
+ * i.e. K = RoPE(Wk x_b, pos_base[b] + tail_len[b] - 1) and V = Wv x_b are written (rounded to
+ * the storage type) at tail row tail_len[b] - 1 of every instance, and the new token attends
+ * to all page tokens and tail rows 0..tail_len[b]-1, the row just written included.
+ * hidden: device [batch][hidden]; w_k, w_v: [Hkv*D][hidden]; q/out: [batch][Hq][D].
+ * Call matkv_advance first, as before matkv_materialize_tail.  On bf16, head_dim 128, hidden a
+ * multiple of 4096 and the default decode kernel the projection's weight reads overlap the
+ * cache reads inside one kernel; other configurations run the two launches above.
+ * MATKV_EINVAL if some tail is empty. */
+matkv_status matkv_decode_step(matkv_ctx* ctx, int32_t layer, const void* hidden, const void* w_k,
+                               const void* w_v, const void* q, const void* table, void* tail_k,
+                               void* tail_v, void* out);
 
 /* ---- measurement aid ------------------------------------------------------------------------ */
 
@@ -202,8 +218,8 @@ matkv_status matkv_probe_read(matkv_ctx* ctx, const void* src, size_t bytes);
 
 /* ---- command capture: replay a fixed sequence of the calls above without host cost ------ */
 
-/* Between begin and end, calls to materialize_tail / advance / prefill_attn / decode_attn
- * are recorded from the compute stream instead of executed.  Captured work reads tail
+/* Between begin and end, calls to materialize_tail / advance / prefill_attn / decode_attn /
+ * decode_step are recorded from the compute stream instead of executed.  Captured work reads tail
  * lengths and positions from the table on the device, so one recording of a decode step
  * serves every step. */
 matkv_status matkv_graph_begin(matkv_ctx* ctx);

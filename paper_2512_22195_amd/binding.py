@@ -25,7 +25,7 @@ EXPORTS = [
     "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
     "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
-    "matkv_prefill_attn", "matkv_decode_attn", "matkv_graph_begin", "matkv_graph_end",
+    "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
 ]
 
@@ -87,6 +87,8 @@ def _load_library():
     for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
         fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         fn.restype = c_int32
+    lib.matkv_decode_step.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
+    lib.matkv_decode_step.restype = c_int32
     lib.matkv_plan_decode_units.argtypes = [cfgp, POINTER(c_int32), c_int32, c_int32, c_int32,
                                             POINTER(c_int32), POINTER(c_int32), c_int32]
     lib.matkv_plan_decode_units.restype = c_int32
@@ -264,6 +266,10 @@ class Context:
     def decode_attn(self, layer, q, table, tail_k, tail_v, out):
         self._check(_lib.matkv_decode_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
                                            _ptr(out)), "matkv_decode_attn")
+
+    def decode_step(self, layer, hidden, w_k, w_v, q, table, tail_k, tail_v, out):
+        self._check(_lib.matkv_decode_step(self._h, layer, _ptr(hidden), _ptr(w_k), _ptr(w_v), _ptr(q), _ptr(table),
+                                           _ptr(tail_k), _ptr(tail_v), _ptr(out)), "matkv_decode_step")
 
     def probe_read(self, src, nbytes):
         self._check(_lib.matkv_probe_read(self._h, _ptr(src), nbytes), "matkv_probe_read")

@@ -61,8 +61,8 @@ __device__ __forceinline__ float lane_xor(float v, int off, int lane) {
 struct KernelArgs {
     const void* __restrict__ q;
     void* __restrict__ out;
-    const void* __restrict__ tail_k;
-    const void* __restrict__ tail_v;
+    const void* tail_k;          // a fused decode step also writes the newest row of each instance
+    const void* tail_v;
     float* __restrict__ partials;
     int32_t* __restrict__ counters;
     int32_t layer, Hq, Hkv, max_tail, rows, prefill;
@@ -144,6 +144,28 @@ struct Walker {
         pos += n;
         return r;
     }
+    // next(), except that past the end it hands out a one-row block (the first row of the
+    // unit's first item) marked invalid: a loop can then issue its loads without a branch, and
+    // the loads of such a block all fall on one row.
+    __device__ __forceinline__ BlockRef<T> next_safe() {
+        BlockRef<T> r = next();
+        if (r.valid) return r;
+        const Item& f = unit.first;
+        if (f.base) {
+            const size_t head_elems = (size_t)f.page_tokens * D;
+            const T* blob = reinterpret_cast<const T*>(f.base);
+            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+        } else {
+            const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
+            r.k = reinterpret_cast<const T*>(a.tail_k) + off;
+            r.v = reinterpret_cast<const T*>(a.tail_v) + off;
+        }
+        r.is_tail = f.base == 0;
+        r.t0 = f.tok0;
+        r.tok_end = f.tok0 + 1;
+        return r;
+    }
 };
 
 // What a local result row of a workgroup stands for.
@@ -154,8 +176,12 @@ struct RowMap {
 };
 
 // Last-arrival merge of all units' partials into the output rows (see finish_unit).
+// unit0 = the instance's first unit.  xm / xv, when given, describe one more contribution that
+// never went through memory: per local row its score in the exponent's units (xm[row]), weight
+// 1, and a value vector shared by the rows (xv[D]) - the token a fused decode step projects.
 template <typename T, int D, int NT, int CB, typename MapFn>
-__device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& unit, int cols_valid, int n_units, MapFn map) {
+__device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int cols_valid, int n_units, MapFn map,
+                                            const float* xm, const float* xv) {
     constexpr int PSTRIDE = kPartialStride(D);
     constexpr int UPC = 32 / CB;                               // units per column and pass
     const int tid = threadIdx.x;
@@ -174,7 +200,7 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& uni
             const int i = cc / (D / 2);
             dd[cb] = (cc % (D / 2)) * 2;
             rms[cb] = map(i);
-            src[cb] = a.partials + (((size_t)unit.unit0_inst * a.rows + rms[cb].slot_row) * a.Hq + rms[cb].head) * PSTRIDE;
+            src[cb] = a.partials + (((size_t)unit0 * a.rows + rms[cb].slot_row) * a.Hq + rms[cb].head) * PSTRIDE;
             M[cb] = kNegBig; Lsum[cb] = 0.f; ox[cb] = 0.f; oy[cb] = 0.f;
         }
         for (int u0 = 0; u0 < n_units; u0 += UPC) {
@@ -204,6 +230,18 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& uni
                 }
             }
         }
+        if (xm != nullptr) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const int col = live[cb] ? c0 + cb * NT : c0;
+                const float mx = xm[col / (D / 2)];
+                const float mn = fmaxf(M[cb], mx);
+                const float cold = fast_exp2(M[cb] - mn), cx = fast_exp2(mx - mn);
+                Lsum[cb] = fmaf(Lsum[cb], cold, cx);
+                ox[cb] = fmaf(ox[cb], cold, xv[dd[cb]] * cx);
+                oy[cb] = fmaf(oy[cb], cold, xv[dd[cb] + 1] * cx);
+            }
+        }
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             if (!live[cb]) continue;
@@ -219,20 +257,46 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, const Unit& uni
     }
 }
 
+// A thread owns pairs of output elements (columns).  Per pass it takes CB of its columns and
+// up to 32 / CB units and issues all those loads - the pairs and the (max, sum) of their rows -
+// at once: one memory round trip per pass.  Few units means many columns per pass.
+template <typename T, int D, int NT, typename MapFn>
+__device__ __forceinline__ void merge_dispatch(const KernelArgs& a, int unit0, int n_units, int cols_valid, MapFn map,
+                                               const float* xm, const float* xv) {
+    if (n_units <= 4)       merge_units<T, D, NT, 8>(a, unit0, cols_valid, n_units, map, xm, xv);
+    else if (n_units <= 8)  merge_units<T, D, NT, 4>(a, unit0, cols_valid, n_units, map, xm, xv);
+    else if (n_units <= 16) merge_units<T, D, NT, 2>(a, unit0, cols_valid, n_units, map, xm, xv);
+    else                    merge_units<T, D, NT, 1>(a, unit0, cols_valid, n_units, map, xm, xv);
+}
+
+// One workgroup's arrival at the counter of (instance, KV head, z index): every thread has
+// waited for its own agent-scope stores, the barrier orders them before thread 0's ticket.
+// Returns true in every thread of the workgroup that arrived last of `expected`.
+__device__ __forceinline__ bool arrive(const KernelArgs& a, int cidx, int expected, int* sm_last) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *sm_last = (prev == expected - 1);
+    }
+    __syncthreads();
+    return *sm_last != 0;
+}
+__device__ __forceinline__ void reset_counter(const KernelArgs& a, int cidx) {
+    if (threadIdx.x == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+}
+
 // Merge of one workgroup's NS partial states per row (already in LDS: accumulators
 // sm_acc[w][row][..] with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums
 // sm_l[w][row]; NS = the waves when they split the tokens, 1 when they split the rows) into the
-// unit's partial, followed - in the last workgroup of this (instance, KV head, z index) to
-// arrive - by the merge of all units' partials into the output rows.
-//
-// Partials are written and read with agent-scope accesses: every thread waits for its own
-// stores to complete, the barrier orders them before thread 0's ticket, and the last arrival
-// reads the partials back from memory.  No L2 write-back or invalidate is involved.
-template <typename T, int D, int NW, int NS, int ROWS, int ACC_STRIDE, typename MapFn>
-__device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& unit, int kvh, int zidx,
-                                            const float* sm_acc, const float* sm_m, const float* sm_l,
-                                            int* sm_last, int n_valid_rows, MapFn map) {
-    constexpr int NT = NW * 64;
+// unit's partial, written with agent-scope stores (coherent across the chip's L2 slices; no
+// L2 write-back or invalidate is involved), followed by the workgroup's arrival.  Returns true
+// in the workgroup that arrived last of `expected`: it then folds all partials (merge_dispatch)
+// and resets the counter.
+template <typename T, int D, int NT, int NS, int ROWS, int ACC_STRIDE, typename MapFn>
+__device__ __forceinline__ void publish_partial(const KernelArgs& a, const float* sm_acc, const float* sm_m,
+                                                const float* sm_l, int n_valid_rows, MapFn map) {
     constexpr int PSTRIDE = kPartialStride(D);
     const int tid = threadIdx.x;
     __syncthreads();
@@ -257,27 +321,25 @@ __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& uni
         st_agent2(prow + d, ax, ay);
         if (d == 0) st_agent2(prow + D, mn, lv);
     }
+}
 
+template <typename T, int D, int NW, int NS, int ROWS, int ACC_STRIDE, typename MapFn>
+__device__ __forceinline__ bool publish_unit(const KernelArgs& a, int cidx, int expected,
+                                             const float* sm_acc, const float* sm_m, const float* sm_l,
+                                             int* sm_last, int n_valid_rows, MapFn map) {
+    publish_partial<T, D, NW * 64, NS, ROWS, ACC_STRIDE>(a, sm_acc, sm_m, sm_l, n_valid_rows, map);
+    return arrive(a, cidx, expected, sm_last);
+}
+
+template <typename T, int D, int NW, int NS, int ROWS, int ACC_STRIDE, typename MapFn>
+__device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& unit, int kvh, int zidx,
+                                            const float* sm_acc, const float* sm_m, const float* sm_l,
+                                            int* sm_last, int n_valid_rows, MapFn map) {
     const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + zidx;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) {
-        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *sm_last = (prev == unit.n_units_inst - 1);
-    }
-    __syncthreads();
-    if (!*sm_last) return;
-
-    // A thread owns pairs of output elements (columns).  Per pass it takes CB of its columns and
-    // up to 32 / CB units and issues all those loads - the pairs and the (max, sum) of their rows -
-    // at once: one memory round trip per pass.  Few units (prefill) means many columns per pass.
-    const int n_units = unit.n_units_inst;
-    if (n_units <= 4)       merge_units<T, D, NT, 8>(a, unit, cols_valid, n_units, map);
-    else if (n_units <= 8)  merge_units<T, D, NT, 4>(a, unit, cols_valid, n_units, map);
-    else if (n_units <= 16) merge_units<T, D, NT, 2>(a, unit, cols_valid, n_units, map);
-    else                    merge_units<T, D, NT, 1>(a, unit, cols_valid, n_units, map);
-    if (tid == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    if (!publish_unit<T, D, NW, NS, ROWS, ACC_STRIDE>(a, cidx, unit.n_units_inst, sm_acc, sm_m, sm_l, sm_last, n_valid_rows, map))
+        return;
+    merge_dispatch<T, D, NW * 64>(a, unit.unit0_inst, unit.n_units_inst, n_valid_rows * (D / 2), map, nullptr, nullptr);
+    reset_counter(a, cidx);
 }
 
 }  // namespace attn

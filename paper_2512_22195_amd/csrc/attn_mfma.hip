@@ -15,6 +15,7 @@
 // Waves of a workgroup split the unit's tokens; workgroups split the cache; merging is the
 // same as in the plain-ALU kernel.
 #include "attn_common.h"
+#include "gemv_common.h"
 
 namespace matkv {
 namespace {
@@ -40,13 +41,93 @@ __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)p);
 }
 
-template <int G, int NW, int MS, int PF>
-__global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
-        KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
+// What a fused decode step adds to the attention launch (paper Section III-B steps 2-3 for the
+// newest token of every instance, then Section V-A's decode attention over everything).
+struct StepArgs {
+    const void* hidden;         // [batch][Hd]
+    const void* w_k;            // [Hkv * D][Hd]
+    const void* w_v;
+    const RopeEntry* rope;
+    int32_t Hd, batch;
+};
+
+// The newest token of instance b, KV head kvh, as one more contribution to the merge: its
+// scores against the G query rows (in the exponent's units) and its value vector, read back
+// from the tail cache where the projection workgroups left them (agent-scope stores).
+template <int G, int NW>
+__device__ __forceinline__ void newest_token_terms(const KernelArgs& a, const InstanceInfo& inst, int b, int kvh,
+                                                   float* sm_xm, float* sm_xv) {
+    typedef uint16_t T;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const size_t off = (((size_t)b * a.Hkv + kvh) * (size_t)a.max_tail + (size_t)(inst.tail_len - 1)) * D + 2 * lane;
+    const uint32_t kw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_k) + off),
+                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (wave == 0) {
+        const uint32_t vw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_v) + off),
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_xv[2 * lane] = __uint_as_float(vw << 16);
+        sm_xv[2 * lane + 1] = __uint_as_float(vw & 0xffff0000u);
+    }
+    for (int g = wave; g < G; g += NW) {
+        const uint32_t qw = *reinterpret_cast<const uint32_t*>(
+            reinterpret_cast<const T*>(a.q) + ((size_t)b * a.Hq + (size_t)kvh * G + g) * D + 2 * lane);
+        const float s = gemv::wave_sum(gemv::dot2(qw, kw, 0.f), lane);
+        if (lane == 0) sm_xm[g] = s * a.scale_log2e;
+    }
+    __syncthreads();
+}
+
+// A projection wave of a fused decode step: one task = one rotary pair of K or of V of KV head
+// kvh for a group of FR instances; the pair is stored (bf16, agent scope) at the newest tail
+// row of each instance.  The n_waves projection waves of this KV head share the tasks round-robin.
+template <int FR>
+__device__ __forceinline__ void projection_tasks(const KernelArgs& a, const StepArgs& f, const InstanceInfo* __restrict__ insts,
+                                                 int kvh, int wave_id, int n_waves, int lane) {
+    typedef uint16_t T;
+    const int groups = (f.batch + FR - 1) / FR;
+    for (int task = wave_id; task < groups * D; task += n_waves) {
+        const int b0 = (task / D) * FR;
+        const int kv = (task % D) / (D / 2), j = task % (D / 2);
+        const T* w = reinterpret_cast<const T*>(kv == 0 ? f.w_k : f.w_v);
+        const T* w0 = w + ((size_t)kvh * D + j) * f.Hd;
+        const T* w1 = w0 + (size_t)(D / 2) * f.Hd;
+        const T* x = reinterpret_cast<const T*>(f.hidden) + (size_t)b0 * f.Hd;
+        float acc0[FR], acc1[FR];
+        gemv::pair_dots<FR>(w0, w1, x, (size_t)f.Hd, f.batch - b0, f.Hd, lane, acc0, acc1);
+        if (lane < FR && b0 + lane < f.batch) {
+            float r0 = 0.f, r1 = 0.f;
+#pragma unroll
+            for (int r = 0; r < FR; ++r) if (lane == r) { r0 = acc0[r]; r1 = acc1[r]; }
+            const int b = b0 + lane;
+            const int row = insts[b].tail_len - 1;
+            if (row >= 0 && row < a.max_tail) {
+                if (kv == 0) gemv::rotate_pair(f.rope[j], (float)(insts[b].pos_base + row), r0, r1);
+                T* out = reinterpret_cast<T*>(const_cast<void*>(kv == 0 ? a.tail_k : a.tail_v)) +
+                         (((size_t)b * a.Hkv + kvh) * (size_t)a.max_tail + (size_t)row) * D + j;
+                __hip_atomic_store(out, f32_to_bf16_rne(r0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(out + D / 2, f32_to_bf16_rne(r1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+constexpr int kFusedMaxBatch = 4;
+
+// FR = 0: attention only, NW waves.  FR > 0: fused decode step - the workgroup has NW more
+// waves, which project the newest token's K/V (FR instances per task) while the first NW walk
+// the cache; every compute unit then holds both kinds of work side by side.  In that form each
+// workgroup of a KV head arrives at the counter of EVERY instance of the batch once all its
+// work is out, so the last arrival at an instance's counter knows that instance's partials and
+// its newest K/V row are complete, whichever workgroups produced them.
+template <int G, int NW, int MS, int PF, int FR>
+__global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void attn_mfma_kernel(
+        KernelArgs a, StepArgs f, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
     constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
+    constexpr int NT = (FR > 0 ? 2 : 1) * NW * 64;      // threads of the workgroup
     typedef uint16_t T;
-
+    __shared__ float sm_xm[8], sm_xv[D];
+    __shared__ int sm_last, sm_lastv[FR > 0 ? kFusedMaxBatch : 1];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -67,23 +148,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
     } else {
         n_m = G;
         q_row0 = unit.inst;
-        if (unit.has_tail) tail_len = insts[unit.inst].tail_len;
+        if (unit.has_tail) tail_len = insts[unit.inst].tail_len - (FR > 0 ? 1 : 0);   // fused: the newest row is not in the cache yet
         tail_visible = tail_len;
-    }
-
-    // Q in operand layout: lane (c16, g4) holds, for sub-tile j and 32-dim chunk c, the 8 dims
-    // 32c + 8*g4 .. +8 of row m0 + 16j + c16.  Padding rows repeat the last real row.
-    bf16x8 bq[MS][4];
-    int vis[MS];                                        // tail rows this lane's row may see
-#pragma unroll
-    for (int j = 0; j < MS; ++j) {
-        const int m = min(m0 + 16 * j + c16, n_m - 1);
-        const int r = m / G, g = m % G;
-        const int q_row = a.prefill ? q_row0 + r : q_row0;
-        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + 8 * g4;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + 32 * c));
-        vis[j] = a.prefill ? r + 1 : tail_len;
     }
 
     f32x4 ot[MS][8];                                    // O^T: dims 16s + 4*g4 + i of row 16j + c16
@@ -100,7 +166,26 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
     constexpr int ACC_BYTES = NW * ROWS * ACCS * 4;
     __shared__ __attribute__((aligned(16))) char smem[V_BYTES > ACC_BYTES ? V_BYTES : ACC_BYTES];
     __shared__ float sm_m[NW * ROWS], sm_l[NW * ROWS];
-    __shared__ int sm_last;
+
+    if (FR > 0 && wave >= NW) {
+        if constexpr (FR > 0)
+            projection_tasks<FR>(a, f, insts, kvh, (int)blockIdx.x * NW + (wave - NW), (int)gridDim.x * NW, lane);
+    } else {
+    // Q in operand layout: lane (c16, g4) holds, for sub-tile j and 32-dim chunk c, the 8 dims
+    // 32c + 8*g4 .. +8 of row m0 + 16j + c16.  Padding rows repeat the last real row.
+    bf16x8 bq[MS][4];
+    int vis[MS];                                        // tail rows this lane's row may see
+#pragma unroll
+    for (int j = 0; j < MS; ++j) {
+        const int m = min(m0 + 16 * j + c16, n_m - 1);
+        const int r = m / G, g = m % G;
+        const int q_row = a.prefill ? q_row0 + r : q_row0;
+        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + 8 * g4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + 32 * c));
+        vis[j] = a.prefill ? r + 1 : tail_len;
+    }
+
     uint16_t* const vstrip = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * BLK * VSTR;
 
     Walker<T, D, NW, BLK, 8> walk(a, unit, items, kvh, tail_visible, wave);
@@ -187,41 +272,46 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
     };
 
     // PF blocks of loads stay in flight: block i + PF is issued right after block i is consumed.
+    // The loads are issued without a branch (past the end of the wave's share they all fall on
+    // one row) and the loop has one exit: only then can the compiler count the loads in flight
+    // exactly, instead of waiting for all of them before each block.
     {
         uint4 kb[PF][2][4], vb[PF][8];
         BlockRef<T> rb[PF];
 #pragma unroll
         for (int i = 0; i < PF; ++i) {
-            rb[i] = walk.next();
-            if (rb[i].valid) issue(rb[i], kb[i], vb[i]);
+            rb[i] = walk.next_safe();
+            issue(rb[i], kb[i], vb[i]);
         }
-        while (rb[0].valid) {
+        do {
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                if (rb[i].valid) {
-                    consume(rb[i], kb[i], vb[i]);
-                    rb[i] = walk.next();
-                    if (rb[i].valid) issue(rb[i], kb[i], vb[i]);
-                }
+                if (rb[i].valid) consume(rb[i], kb[i], vb[i]);
+                rb[i] = walk.next_safe();
+                issue(rb[i], kb[i], vb[i]);
             }
-        }
+        } while (rb[0].valid);
     }
 
-    // ---- per-wave states to LDS (the strips are dead now), then the common merge ----
 #pragma unroll
     for (int j = 0; j < MS; ++j) {
         lrow[j] += lane_xor(lrow[j], 16, lane);
         lrow[j] += lane_xor(lrow[j], 32, lane);
     }
+    }   // attention waves
+
+    // ---- per-wave states to LDS (the strips are dead now), then the common merge ----
     __syncthreads();                                    // every wave is done with its strip
     float* const sm_acc = reinterpret_cast<float*>(smem);
+    if (wave < NW) {
 #pragma unroll
-    for (int j = 0; j < MS; ++j) {
-        float* dst = sm_acc + ((size_t)wave * ROWS + 16 * j + c16) * ACCS + 4 * g4;
+        for (int j = 0; j < MS; ++j) {
+            float* dst = sm_acc + ((size_t)wave * ROWS + 16 * j + c16) * ACCS + 4 * g4;
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-            *reinterpret_cast<float4*>(dst + 16 * s) = make_float4(ot[j][s][0], ot[j][s][1], ot[j][s][2], ot[j][s][3]);
-        if (g4 == 0) { sm_m[wave * ROWS + 16 * j + c16] = mrow[j]; sm_l[wave * ROWS + 16 * j + c16] = lrow[j]; }
+            for (int s = 0; s < 8; ++s)
+                *reinterpret_cast<float4*>(dst + 16 * s) = make_float4(ot[j][s][0], ot[j][s][1], ot[j][s][2], ot[j][s][3]);
+            if (g4 == 0) { sm_m[wave * ROWS + 16 * j + c16] = mrow[j]; sm_l[wave * ROWS + 16 * j + c16] = lrow[j]; }
+        }
     }
     const int prefill = a.prefill;
     auto map = [&](int i) {
@@ -233,18 +323,63 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(
         rm.q_row = prefill ? q_row0 + r : q_row0;
         return rm;
     };
-    finish_unit<T, D, NW, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
+    if constexpr (FR == 0) {
+        finish_unit<T, D, NW, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
+    } else {
+        publish_partial<T, D, NT, NW, ROWS, ACCS>(a, sm_acc, sm_m, sm_l, G, map);
+        // arrival at every instance's counter of this KV head
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid < f.batch) {
+            const int prev = __hip_atomic_fetch_add(&a.counters[(tid * a.Hkv + kvh) * a.rows], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sm_lastv[tid] = (prev == (int)gridDim.x - 1);
+        }
+        __syncthreads();
+        for (int b = 0; b < f.batch; ++b) {
+            if (!sm_lastv[b]) continue;                 // uniform
+            const InstanceInfo inst = insts[b];
+            newest_token_terms<G, NT / 64>(a, inst, b, kvh, sm_xm, sm_xv);
+            auto bmap = [&](int i) {
+                RowMap rm;
+                rm.slot_row = 0; rm.head = kvh * G + i; rm.q_row = b;
+                return rm;
+            };
+            merge_dispatch<T, D, NT>(a, inst.dunit0, inst.n_dunits, G * (D / 2), bmap, sm_xm, sm_xv);
+            reset_counter(a, (b * a.Hkv + kvh) * a.rows);
+            __syncthreads();                            // sm_xm / sm_xv are reused
+        }
+    }
 }
 
 template <int G, int NW, int MS, int PF>
 hipError_t launch_v(const AttnArgs& a, int tiles, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
     dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
-    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, MS, PF>), grid, block, 0, s, k,
+    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, MS, PF, 0>), grid, block, 0, s, k, StepArgs{},
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
     return hipGetLastError();
+}
+
+template <int G, int NW, int FR>
+hipError_t launch_step_v(const AttnArgs& a, const MaterializeArgs& m, hipStream_t s) {
+    const KernelArgs k = make_kernel_args(a);
+    StepArgs f;
+    f.hidden = m.hidden; f.w_k = m.w_k; f.w_v = m.w_v; f.rope = m.rope;
+    f.Hd = m.Hd; f.batch = a.batch;
+    dim3 grid(a.n_units, a.Hkv, 1), block(2 * NW * 64);
+    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, 1, 2, FR>), grid, block, 0, s, k, f,
+                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
+                       reinterpret_cast<const Item*>(a.table + a.off_items),
+                       reinterpret_cast<const Unit*>(a.table + a.off_units));
+    return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch_step_g(const AttnArgs& a, const MaterializeArgs& m, hipStream_t s) {
+    return a.batch == 1 ? launch_step_v<G, 4, 1>(a, m, s) : launch_step_v<G, 4, 4>(a, m, s);
 }
 
 template <int G>
@@ -281,6 +416,27 @@ hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
         case 2: return launch_g<2>(a, s);
         case 4: return launch_g<4>(a, s);
         case 8: return launch_g<8>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+
+// Fused decode step: K/V projection of every instance's newest token and the decode attention
+// in one launch (default kernel shape only).
+bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype) {
+    // Measured: the single launch wins while every projection wave has one task (up to four
+    // instances) and four attention waves are the better shape anyway (group size up to 4).
+    return attn_mfma_supported(a, dtype) && !a.prefill && a.variant == 0 && (m.Hd % 4096) == 0 &&
+           a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4;
+}
+
+hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int dtype, hipStream_t s) {
+    if (a.n_units <= 0 || !decode_step_supported(a, m, dtype)) return hipErrorInvalidValue;
+    switch (a.Hq / a.Hkv) {
+        case 1: return launch_step_g<1>(a, m, s);
+        case 2: return launch_step_g<2>(a, m, s);
+        case 4: return launch_step_g<4>(a, m, s);
+        case 8: return launch_step_g<8>(a, m, s);
     }
     return hipErrorInvalidValue;
 }

@@ -5,7 +5,7 @@
 // tokens.  With one token per instance (a decode step) it is a GEMV bound by reading the
 // weights once from HBM; it is also the fp32 path.  The tile-GEMM form for long token
 // runs lives in materialize_mfma.hip.
-#include "matkv_internal.h"
+#include "gemv_common.h"
 
 namespace matkv {
 namespace {
@@ -167,42 +167,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_rows_kernel(M
 }
 
 // ---- bf16 GEMV form: a handful of token rows (a decode step), hidden a multiple of 4096 ------
-// One wave per rotary pair, as above, but shaped for latency: all 16 weight loads of a
-// 4096-column pass are issued before anything is consumed, products use the packed bf16 dot
-// instruction (exact products, fp32 accumulation), the 64-lane sum runs on DPP adds and
-// register swaps, and the rotation takes the hardware sine / cosine on an angle kept in turns.
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2v __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ uint4 ldg16(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x4v* gptr;
-    const u32x4v r = *(gptr)(uintptr_t)p;
-    return make_uint4(r.x, r.y, r.z, r.w);
-}
-__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
-}
-__device__ __forceinline__ float dot8(const uint4& a, const uint4& b, float c) {
-    c = dot2(a.x, b.x, c); c = dot2(a.y, b.y, c); c = dot2(a.z, b.z, c); c = dot2(a.w, b.w, c);
-    return c;
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-    int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
-    return v + __int_as_float(o);
-}
-__device__ __forceinline__ float wave_sum_fast(float v, int lane) {
-    v = dpp_add<0xB1>(v); v = dpp_add<0x4E>(v); v = dpp_add<0x141>(v); v = dpp_add<0x140>(v);   // 16-lane rows
-    const unsigned x = __float_as_uint(v);
-    const u32x2v r16 = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-    v += __uint_as_float((lane & 16) ? r16.x : r16.y);
-    const unsigned y = __float_as_uint(v);
-    const u32x2v r32 = __builtin_amdgcn_permlane32_swap(y, y, false, false);
-    v += __uint_as_float((lane & 32) ? r32.x : r32.y);
-    return v;
-}
-
+// One wave per rotary pair, as above, but shaped for latency (see gemv_common.h).
 template <int R>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(MaterializeArgs a) {
     typedef uint16_t T;
@@ -216,33 +181,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
     const int row0 = blockIdx.y * R;
 
     const T* w = reinterpret_cast<const T*>(kv == 0 ? a.w_k : a.w_v);
-    const T* w0 = w + ((size_t)head * a.D + j) * a.Hd + lane * 8;
+    const T* w0 = w + ((size_t)head * a.D + j) * a.Hd;
     const T* w1 = w0 + (size_t)half * a.Hd;
-    const T* x = reinterpret_cast<const T*>(a.hidden) + lane * 8;
+    const T* x = reinterpret_cast<const T*>(a.hidden) + (size_t)row0 * a.Hd;
 
     float acc0[R], acc1[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
-    for (int c0 = 0; c0 < a.Hd; c0 += 4096) {
-        uint4 wa[8], wb[8], xv[R][8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { wa[i] = ldg16(w0 + c0 + 512 * i); wb[i] = ldg16(w1 + c0 + 512 * i); }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const T* xr = x + (size_t)min(row0 + r, a.n_tokens - 1) * a.Hd + c0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) xv[r][i] = ldg16(xr + 512 * i);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                acc0[r] = dot8(wa[i], xv[r][i], acc0[r]);
-                acc1[r] = dot8(wb[i], xv[r][i], acc1[r]);
-            }
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) { acc0[r] = wave_sum_fast(acc0[r], lane); acc1[r] = wave_sum_fast(acc1[r], lane); }
+    gemv::pair_dots<R>(w0, w1, x, (size_t)a.Hd, a.n_tokens - row0, a.Hd, lane, acc0, acc1);
 
     if (lane < R) {
         float r0 = 0.f, r1 = 0.f;
@@ -250,18 +194,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
         for (int r = 0; r < R; ++r) if (lane == r) { r0 = acc0[r]; r1 = acc1[r]; }
         const RowDest d = resolve_row(a, row0 + lane);
         if (d.valid) {
-            if (kv == 0) {
-                const RopeEntry e = a.rope[j];
-                const float p = (float)d.pos;
-                const float t = p * e.turns_hi;
-                const float err = fmaf(p, e.turns_hi, -t);
-                float fr = t - rintf(t);
-                fr += fmaf(p, e.turns_lo, err);
-                const float c = __builtin_amdgcn_cosf(fr), s = __builtin_amdgcn_sinf(fr);
-                const float k0 = r0 * c - r1 * s;
-                const float k1 = r0 * s + r1 * c;
-                r0 = k0; r1 = k1;
-            }
+            if (kv == 0) gemv::rotate_pair(a.rope[j], (float)d.pos, r0, r1);
             T* out = reinterpret_cast<T*>(kv == 0 ? a.k_out : a.v_out) + d.elem_off +
                      (size_t)head * a.token_stride * a.D + j;
             out[0] = f32_to_bf16_rne(r0);
@@ -269,6 +202,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
         }
     }
 }
+
+constexpr int kGemmMinRows = 64;
 
 bool gemv_supported(const MaterializeArgs& a, int dtype) { return dtype == MATKV_BF16 && (a.Hd % 4096) == 0; }
 
@@ -309,6 +244,9 @@ hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
     const int total_rows = a.n_tokens;
     if (total_rows <= 0) return hipSuccess;
+    // a few dozen rows (a decode step of a batch) make too few GEMM tiles to fill the chip: the
+    // GEMV form re-reads the weights from the caches once per 4 rows and still comes out ahead
+    if (gemv_supported(a, dtype) && total_rows < kGemmMinRows) return launch_gemv(a, total_rows, s);
     if (materialize_mfma_supported(a, dtype, total_rows)) return launch_materialize_mfma(a, total_rows, s);
     if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);
     if (gemv_supported(a, dtype)) return launch_gemv(a, total_rows, s);

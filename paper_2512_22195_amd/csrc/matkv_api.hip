@@ -655,8 +655,8 @@ matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
 
 // -------------------------------------------------------------------------------- P / D ----
 
-static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int32_t layer, const void* q,
-                                const void* table, const void* tail_k, const void* tail_v, void* out) {
+static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32_t layer, const void* q,
+                              const void* table, const void* tail_k, const void* tail_v, void* out, AttnArgs* out_args) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;
     if (!q || !table || !tail_k || !tail_v || !out) return fail(c, MATKV_EINVAL, "%s: null pointer", name);
@@ -683,6 +683,15 @@ static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int
     a.scale_log2e = c->scale_log2e;
     a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
     a.off_units = prefill ? c->tl.off_punits : c->tl.off_dunits;
+    *out_args = a;
+    return MATKV_OK;
+}
+
+static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int32_t layer, const void* q,
+                                const void* table, const void* tail_k, const void* tail_v, void* out) {
+    AttnArgs a;
+    matkv_status st = attn_args(c, name, prefill, layer, q, table, tail_k, tail_v, out, &a);
+    if (st != MATKV_OK) return st;
     const bool want_mfma = prefill || a.variant == 0 || a.variant >= 9000;
     if (attn_prefill_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_prefill(a, c->cfg.dtype, c->compute));
     else if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
@@ -698,6 +707,35 @@ matkv_status matkv_prefill_attn(matkv_ctx* c, int32_t layer, const void* q, cons
 matkv_status matkv_decode_attn(matkv_ctx* c, int32_t layer, const void* q, const void* table,
                                const void* tail_k, const void* tail_v, void* out) {
     return attn_common(c, "decode_attn", 0, layer, q, table, tail_k, tail_v, out);
+}
+
+matkv_status matkv_decode_step(matkv_ctx* c, int32_t layer, const void* hidden, const void* w_k, const void* w_v,
+                               const void* q, const void* table, void* tail_k, void* tail_v, void* out) {
+    if (c && (!hidden || !w_k || !w_v)) return fail(c, MATKV_EINVAL, "decode_step: null pointer");
+    if (c && (!aligned16(hidden) || !aligned16(w_k) || !aligned16(w_v)))
+        return fail(c, MATKV_EINVAL, "decode_step: pointers must be 16-byte aligned");
+    AttnArgs a;
+    matkv_status st = attn_args(c, "decode_step", 0, layer, q, table, tail_k, tail_v, out, &a);
+    if (st != MATKV_OK) return st;
+    TableHost* th = find_table(c, table);
+    if (th->min_tail_len < 1) return fail(c, MATKV_EINVAL, "decode_step: a tail holds no row for the new token");
+    MaterializeArgs m{};
+    m.hidden = hidden; m.w_k = w_k; m.w_v = w_v; m.k_out = tail_k; m.v_out = tail_v;
+    m.rope = reinterpret_cast<const RopeEntry*>(c->workspace + c->wl.off_rope);
+    m.table = reinterpret_cast<const char*>(table); m.off_inst = c->tl.off_inst;
+    m.pos0 = 0; m.token_stride = c->cfg.max_tail_tokens;
+    m.rows_per_instance = 1; m.batch = th->batch; m.n_tokens = th->batch;
+    m.Hkv = c->cfg.n_kv_heads; m.D = c->cfg.head_dim; m.Hd = c->cfg.hidden;
+    if (decode_step_supported(a, m, c->cfg.dtype)) {
+        HIP_TRY(c, launch_decode_step(a, m, c->cfg.dtype, c->compute));
+        return MATKV_OK;
+    }
+    // shapes the fused kernel does not cover: the two launches it stands for
+    HIP_TRY(c, launch_materialize(m, c->cfg.dtype, c->compute));
+    const bool want_mfma = a.variant == 0 || a.variant >= 9000;
+    if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
+    else HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
+    return MATKV_OK;
 }
 
 matkv_status matkv_probe_read(matkv_ctx* c, const void* src, size_t bytes) {

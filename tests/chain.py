@@ -180,8 +180,11 @@ def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=Non
             ctx.close()
 
 
-def run_gpu_chain(case: Case, inp, device="cuda:0"):
-    """Full chain.  Returns dict with materialized blobs/tail (CPU tensors) and outputs."""
+def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False):
+    """Full chain.  Returns dict with materialized blobs/tail (CPU tensors) and outputs.
+    fused: each decode step of a layer is one matkv_decode_step call instead of
+    matkv_materialize_tail + matkv_decode_attn; use_graph (with fused): the step of all layers
+    is recorded once and replayed, with a synchronisation and an eager copy between replays."""
     c = case
     ctx = make_context(c, device)
     try:
@@ -211,11 +214,29 @@ def run_gpu_chain(case: Case, inp, device="cuda:0"):
             for l in range(c.n_layers):                                      # M (question) + P
                 ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
                 ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
-            for t in range(c.steps):                                         # M (token) + D
+            if fused and use_graph and c.steps > 0:
+                x_cur, q_cur, o_cur = torch.empty_like(x_dec[0]), torch.empty_like(q_dec[0]), torch.empty_like(o_dec[0])
+                ctx.graph_begin()
                 ctx.advance(table, 1)
                 for l in range(c.n_layers):
-                    ctx.materialize_tail(x_dec[t, l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
-                    ctx.decode_attn(l, q_dec[t, l], table, tail[l, 0], tail[l, 1], o_dec[t, l])
+                    ctx.decode_step(l, x_cur[l], w[l, 0], w[l, 1], q_cur[l], table, tail[l, 0], tail[l, 1], o_cur[l])
+                g = ctx.graph_end()
+                for t in range(c.steps):
+                    x_cur.copy_(x_dec[t]); q_cur.copy_(q_dec[t])
+                    ctx.graph_launch(g)
+                    o_dec[t].copy_(o_cur)
+                    ctx.compute_stream.synchronize()
+                ctx.graph_destroy(g)
+            else:
+                for t in range(c.steps):                                     # M (token) + D
+                    ctx.advance(table, 1)
+                    for l in range(c.n_layers):
+                        if fused:
+                            ctx.decode_step(l, x_dec[t, l], w[l, 0], w[l, 1], q_dec[t, l], table,
+                                            tail[l, 0], tail[l, 1], o_dec[t, l])
+                        else:
+                            ctx.materialize_tail(x_dec[t, l], w[l, 0], w[l, 1], table, 1, tail[l, 0], tail[l, 1])
+                            ctx.decode_attn(l, q_dec[t, l], table, tail[l, 0], tail[l, 1], o_dec[t, l])
             ctx.compute_stream.synchronize()
             return dict(blobs=host_blobs, tail=tail.cpu(), o_pre=o_pre.cpu(),
                         o_dec=o_dec.cpu() if c.steps > 0 else o_dec[:0].cpu())

@@ -46,9 +46,9 @@ def test_bf16_chain_ragged_chunks():
     chain.compare_attention(case, gpu["o_pre"], gpu["o_dec"], ref["pre"], ref["dec"])
 
 
-def _chain_parity(case):
+def _chain_parity(case, fused=False, use_graph=False):
     inp = chain.make_chain_inputs(case)
-    gpu = chain.run_gpu_chain(case, inp)
+    gpu = chain.run_gpu_chain(case, inp, fused=fused, use_graph=use_graph)
     ref = chain.run_oracle_chain(case, inp)
     for cid in case.chunk_lens:
         for l in range(case.n_layers):
@@ -71,6 +71,31 @@ def test_bf16_chain_hidden_4096(batch):
                 chunk_lens={0: 150, 1: 40}, retrieved=retrieved, q_lens=[3, 17, 1, 8, 20][:batch],
                 steps=2, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
     _chain_parity(case)
+
+
+@pytest.mark.parametrize("batch,Hq,use_graph", [(1, 8, False), (2, 8, False), (4, 8, True), (5, 8, False),
+                                                (1, 16, False), (6, 16, False)])
+def test_fused_decode_step_chain(batch, Hq, use_graph):
+    """matkv_decode_step, full chain against the oracle (bf16, head_dim 128, hidden 4096): the
+    new token's K/V land in the tail cache and the attention includes them.  Batches 1, 2 and 4
+    at group size 4 take the single-launch form (one row per projection task; a partly and a
+    fully used group of four rows; once recorded and replayed); batch 5 and group size 8 take
+    the two launches it stands for."""
+    retrieved = [[0], [1, 0], [0, 1], [1], [0], [1, 1]][:batch]
+    case = Case(f"fused-step-{batch}-{Hq}", n_layers=2, Hq=Hq, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 150, 1: 40}, retrieved=retrieved, q_lens=[3, 17, 1, 8, 20, 2][:batch],
+                steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case, fused=True, use_graph=use_graph)
+
+
+def test_decode_step_other_shapes_run_two_launches():
+    """Same entry point where the single-launch form does not apply (hidden 512; fp32)."""
+    case = Case("step-fallback-bf16", n_layers=1, Hq=8, Hkv=2, D=128, hidden=512, dtype="bf16",
+                chunk_lens={0: 90}, retrieved=[[0], [0]], q_lens=[4, 2], steps=2, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case, fused=True)
+    case = Case("step-fallback-f32", n_layers=1, Hq=4, Hkv=2, D=64, hidden=256, dtype="f32",
+                chunk_lens={0: 70}, retrieved=[[0]], q_lens=[5], steps=2, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case, fused=True)
 
 
 def test_materialize_large_positions_bf16():
