@@ -176,12 +176,9 @@ struct RowMap {
 };
 
 // Last-arrival merge of all units' partials into the output rows (see finish_unit).
-// unit0 = the instance's first unit.  xm / xv, when given, describe one more contribution that
-// never went through memory: per local row its score in the exponent's units (xm[row]), weight
-// 1, and a value vector shared by the rows (xv[D]) - the token a fused decode step projects.
+// unit0 = the instance's first unit.
 template <typename T, int D, int NT, int CB, typename MapFn>
-__device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int cols_valid, int n_units, MapFn map,
-                                            const float* xm, const float* xv) {
+__device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int cols_valid, int n_units, MapFn map) {
     constexpr int PSTRIDE = kPartialStride(D);
     constexpr int UPC = 32 / CB;                               // units per column and pass
     const int tid = threadIdx.x;
@@ -230,18 +227,6 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int 
                 }
             }
         }
-        if (xm != nullptr) {
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const int col = live[cb] ? c0 + cb * NT : c0;
-                const float mx = xm[col / (D / 2)];
-                const float mn = fmaxf(M[cb], mx);
-                const float cold = fast_exp2(M[cb] - mn), cx = fast_exp2(mx - mn);
-                Lsum[cb] = fmaf(Lsum[cb], cold, cx);
-                ox[cb] = fmaf(ox[cb], cold, xv[dd[cb]] * cx);
-                oy[cb] = fmaf(oy[cb], cold, xv[dd[cb] + 1] * cx);
-            }
-        }
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             if (!live[cb]) continue;
@@ -261,12 +246,11 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int 
 // up to 32 / CB units and issues all those loads - the pairs and the (max, sum) of their rows -
 // at once: one memory round trip per pass.  Few units means many columns per pass.
 template <typename T, int D, int NT, typename MapFn>
-__device__ __forceinline__ void merge_dispatch(const KernelArgs& a, int unit0, int n_units, int cols_valid, MapFn map,
-                                               const float* xm, const float* xv) {
-    if (n_units <= 4)       merge_units<T, D, NT, 8>(a, unit0, cols_valid, n_units, map, xm, xv);
-    else if (n_units <= 8)  merge_units<T, D, NT, 4>(a, unit0, cols_valid, n_units, map, xm, xv);
-    else if (n_units <= 16) merge_units<T, D, NT, 2>(a, unit0, cols_valid, n_units, map, xm, xv);
-    else                    merge_units<T, D, NT, 1>(a, unit0, cols_valid, n_units, map, xm, xv);
+__device__ __forceinline__ void merge_dispatch(const KernelArgs& a, int unit0, int n_units, int cols_valid, MapFn map) {
+    if (n_units <= 4)       merge_units<T, D, NT, 8>(a, unit0, cols_valid, n_units, map);
+    else if (n_units <= 8)  merge_units<T, D, NT, 4>(a, unit0, cols_valid, n_units, map);
+    else if (n_units <= 16) merge_units<T, D, NT, 2>(a, unit0, cols_valid, n_units, map);
+    else                    merge_units<T, D, NT, 1>(a, unit0, cols_valid, n_units, map);
 }
 
 // One workgroup's arrival at the counter of (instance, KV head, z index): every thread has
@@ -338,7 +322,7 @@ __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& uni
     const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + zidx;
     if (!publish_unit<T, D, NW, NS, ROWS, ACC_STRIDE>(a, cidx, unit.n_units_inst, sm_acc, sm_m, sm_l, sm_last, n_valid_rows, map))
         return;
-    merge_dispatch<T, D, NW * 64>(a, unit.unit0_inst, unit.n_units_inst, n_valid_rows * (D / 2), map, nullptr, nullptr);
+    merge_dispatch<T, D, NW * 64>(a, unit.unit0_inst, unit.n_units_inst, n_valid_rows * (D / 2), map);
     reset_counter(a, cidx);
 }
 

@@ -51,30 +51,64 @@ struct StepArgs {
     int32_t Hd, batch;
 };
 
-// The newest token of instance b, KV head kvh, as one more contribution to the merge: its
-// scores against the G query rows (in the exponent's units) and its value vector, read back
-// from the tail cache where the projection workgroups left them (agent-scope stores).
-template <int G, int NW>
-__device__ __forceinline__ void newest_token_terms(const KernelArgs& a, const InstanceInfo& inst, int b, int kvh,
-                                                   float* sm_xm, float* sm_xv) {
+// Last arrival of a fused decode step at instance b, KV head kvh: folds the units' partials and
+// the newest token into the G output rows.  Wave w owns row w (query head kvh*G + w), lane l
+// the dims 2l, 2l+1.  The newest token's K/V row is read back from the tail cache, where the
+// projection waves left it with agent-scope stores; its loads and the partials' loads are all
+// issued before anything is consumed (one memory round trip), its score is a 64-lane dot
+// product, and it enters as one more contribution of weight 1.  No barrier: waves past G leave.
+template <int G, int NT>
+__device__ __forceinline__ void merge_decode_step(const KernelArgs& a, const InstanceInfo& inst, int b, int kvh) {
     typedef uint16_t T;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const size_t off = (((size_t)b * a.Hkv + kvh) * (size_t)a.max_tail + (size_t)(inst.tail_len - 1)) * D + 2 * lane;
-    const uint32_t kw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_k) + off),
+    constexpr int PSTRIDE = kPartialStride(D);
+    constexpr int UPC = 16;                             // units per pass
+    static_assert(NT / 64 >= G, "one wave per output row");
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (w >= G) return;
+    const int head = kvh * G + w, d = 2 * lane;
+
+    const size_t toff = (((size_t)b * a.Hkv + kvh) * (size_t)a.max_tail + (size_t)(inst.tail_len - 1)) * D + d;
+    const uint32_t kw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_k) + toff),
                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (wave == 0) {
-        const uint32_t vw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_v) + off),
-                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_xv[2 * lane] = __uint_as_float(vw << 16);
-        sm_xv[2 * lane + 1] = __uint_as_float(vw & 0xffff0000u);
+    const uint32_t vw = __hip_atomic_load(reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.tail_v) + toff),
+                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t qw = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const T*>(a.q) + ((size_t)b * a.Hq + head) * D + d);
+
+    const int n_units = inst.n_dunits;
+    const float* src = a.partials + ((size_t)inst.dunit0 * a.rows * a.Hq + head) * PSTRIDE;
+    const size_t ustride = (size_t)a.rows * a.Hq * PSTRIDE;
+    float M = kNegBig, L = 0.f, ox = 0.f, oy = 0.f;
+    for (int u0 = 0; u0 < n_units; u0 += UPC) {
+        float2 av[UPC], ml[UPC];
+#pragma unroll
+        for (int k = 0; k < UPC; ++k) {
+            const size_t uo = (size_t)min(u0 + k, n_units - 1) * ustride;
+            ml[k] = ld_agent2(src + uo + D);
+            av[k] = ld_agent2(src + uo + d);
+        }
+        float mn = M;
+#pragma unroll
+        for (int k = 0; k < UPC; ++k) mn = fmaxf(mn, (u0 + k < n_units) ? ml[k].x : kNegBig);
+        const float cold = fast_exp2(M - mn);
+        L *= cold; ox *= cold; oy *= cold;
+        M = mn;
+#pragma unroll
+        for (int k = 0; k < UPC; ++k) {
+            const float c = (u0 + k < n_units) ? fast_exp2(ml[k].x - mn) : 0.f;
+            L = fmaf(ml[k].y, c, L);
+            ox = fmaf(av[k].x, c, ox);
+            oy = fmaf(av[k].y, c, oy);
+        }
     }
-    for (int g = wave; g < G; g += NW) {
-        const uint32_t qw = *reinterpret_cast<const uint32_t*>(
-            reinterpret_cast<const T*>(a.q) + ((size_t)b * a.Hq + (size_t)kvh * G + g) * D + 2 * lane);
-        const float s = gemv::wave_sum(gemv::dot2(qw, kw, 0.f), lane);
-        if (lane == 0) sm_xm[g] = s * a.scale_log2e;
-    }
-    __syncthreads();
+    const float sx = gemv::wave_sum(gemv::dot2(qw, kw, 0.f), lane) * a.scale_log2e;
+    const float mn = fmaxf(M, sx);
+    const float cold = fast_exp2(M - mn), cx = fast_exp2(sx - mn);
+    L = fmaf(L, cold, cx);
+    ox = fmaf(ox, cold, __uint_as_float(vw << 16) * cx);
+    oy = fmaf(oy, cold, __uint_as_float(vw & 0xffff0000u) * cx);
+    const float inv = 1.0f / L;
+    *reinterpret_cast<uint32_t*>(reinterpret_cast<T*>(a.out) + ((size_t)b * a.Hq + head) * D + d) =
+        (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
 }
 
 // A projection wave of a fused decode step: one task = one rotary pair of K or of V of KV head
@@ -126,7 +160,6 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
     constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
     constexpr int NT = (FR > 0 ? 2 : 1) * NW * 64;      // threads of the workgroup
     typedef uint16_t T;
-    __shared__ float sm_xm[8], sm_xv[D];
     __shared__ int sm_last, sm_lastv[FR > 0 ? kFusedMaxBatch : 1];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -338,16 +371,8 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
         __syncthreads();
         for (int b = 0; b < f.batch; ++b) {
             if (!sm_lastv[b]) continue;                 // uniform
-            const InstanceInfo inst = insts[b];
-            newest_token_terms<G, NT / 64>(a, inst, b, kvh, sm_xm, sm_xv);
-            auto bmap = [&](int i) {
-                RowMap rm;
-                rm.slot_row = 0; rm.head = kvh * G + i; rm.q_row = b;
-                return rm;
-            };
-            merge_dispatch<T, D, NT>(a, inst.dunit0, inst.n_dunits, G * (D / 2), bmap, sm_xm, sm_xv);
+            merge_decode_step<G, NT>(a, insts[b], b, kvh);
             reset_counter(a, (b * a.Hkv + kvh) * a.rows);
-            __syncthreads();                            // sm_xm / sm_xv are reused
         }
     }
 }
