@@ -328,8 +328,19 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     const float* base = a.partials + (((size_t)inst.punit0 * a.rows + (q_row - inst.cu_q)) * a.Hq + head) * PS;
     const size_t ustride = (size_t)a.rows * a.Hq * PS;
 
+    // the first 16 units' accumulators are requested together with the (m, l) pairs, before
+    // anything is consumed: one memory round trip for up to 16 units, two for up to 32
+    auto load16 = [&](int u0, float4 (&v)[16]) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int u = min(u0 + k, max(n_units, 1) - 1);
+            v[k] = *reinterpret_cast<const float4*>(base + (size_t)u * ustride + 4 * hl);
+        }
+    };
     float2 ml = make_float2(kNegBig, 0.f);
     if (hl < n_units) ml = *reinterpret_cast<const float2*>(base + (size_t)hl * ustride + D);
+    float4 v[16];
+    load16(0, v);
     float M = ml.x;
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
@@ -341,15 +352,10 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     // both halves of the wave run the same number of steps (shuffles need every lane)
     const int steps = max(n_units, __shfl_xor(n_units, 32));
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int u0 = 0; u0 < steps; u0 += 8) {
-        float4 v[8];
+    for (int u0 = 0; u0 < steps; u0 += 16) {
+        if (u0 > 0) load16(u0, v);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int u = min(u0 + k, max(n_units, 1) - 1);
-            v[k] = *reinterpret_cast<const float4*>(base + (size_t)u * ustride + 4 * hl);
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 16; ++k) {
             const float c = __shfl(w, (lane & 32) + ((u0 + k) & 31));
             const float cc = (u0 + k < n_units) ? c : 0.f;
             acc.x = fmaf(v[k].x, cc, acc.x); acc.y = fmaf(v[k].y, cc, acc.y);

@@ -6,9 +6,12 @@
 //
 // A workgroup owns 128 (or 64) tokens x one head of K or of V (128 features, so both halves of
 // every rotary pair are in the tile), stepping 64 hidden columns at a time through double-buffered
-// LDS tiles.  Its four waves form a 2 x 2 grid of sub-tiles 64 features wide; a wave's
-// features are the 16-wide blocks {2w, 2w+1} and their rotary partners {2w+4, 2w+5}, so the
-// rotation is lane-local on the fp32 accumulators.  One rounding to bf16 on store.
+// LDS tiles fed from four rotating register stages (two steps' loads stay in flight).  Its four
+// waves form a 2 x 2 grid of sub-tiles 64 features wide; a wave's features are the 16-wide
+// blocks {2w, 2w+1} and their rotary partners {2w+4, 2w+5}, so the rotation is lane-local on
+// the fp32 accumulators.  One rounding to bf16 on store.
+#include <type_traits>
+
 #include "matkv_internal.h"
 
 namespace matkv {
@@ -107,20 +110,30 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
-    uint4 xr[LR], wr[4];
-    auto load_global = [&](int k0) {
+    // NS register stages rotate through the hidden axis: while block k is multiplied out of one
+    // LDS tile, block k+1 moves from its stage into the other tile and blocks k+2 .. k+NS-1 are
+    // in flight - a step of 64 columns is far shorter than a trip to the L2, so several steps'
+    // worth of loads have to be outstanding.  Loads and LDS stores carry no branch (past the end
+    // they repeat the last block) and the loop has one exit, so that the compiler can count the
+    // loads in flight instead of draining them at every step.
+    constexpr int NS = 4;                       // measured: 6 stages gain nothing over 4
+    struct Stage { uint4 x[LR], w[4]; };
+    Stage st[NS];
+    const int nk = a.Hd / BK;
+    auto load_global = [&](Stage& g, int ks) {
+        const int k0 = min(ks, nk - 1) * BK;
 #pragma unroll
-        for (int i = 0; i < LR; ++i) xr[i] = ldg16(xg[i] + k0);
+        for (int i = 0; i < LR; ++i) g.x[i] = ldg16(xg[i] + k0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wr[i] = ldg16(wg[i] + k0);
+        for (int i = 0; i < 4; ++i) g.w[i] = ldg16(wg[i] + k0);
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf, const Stage& g) {
 #pragma unroll
         for (int i = 0; i < LR; ++i)
-            *reinterpret_cast<uint4*>(&As[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = xr[i];
+            *reinterpret_cast<uint4*>(&As[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = g.x[i];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4*>(&Bs[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = wr[i];
+            *reinterpret_cast<uint4*>(&Bs[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = g.w[i];
     };
 
     f32x4 acc[MI][4];           // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
@@ -129,13 +142,7 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = a.Hd / BK;
-    load_global(0);
-    store_lds(0);
-    lds_barrier();
-    for (int ks = 0; ks < nk; ++ks) {
-        const int buf = ks & 1;
-        if (ks + 1 < nk) load_global((ks + 1) * BK);
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int k2 = 0; k2 < BK / 32; ++k2) {
             bf16x8 av[MI], bv[4];
@@ -153,9 +160,28 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
                 for (int ni = 0; ni < 4; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
         }
-        if (ks + 1 < nk) store_lds(buf ^ 1);
+    };
+
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) load_global(st[i], i);
+    store_lds(0, st[0]);
+    lds_barrier();
+    int ks = 0;
+    // block ks sits in LDS tile ks & 1; its stage index S = ks % NS is a compile-time constant
+    auto step = [&](auto stage_tag) {
+        constexpr int S = decltype(stage_tag)::value;
+        load_global(st[(S + NS - 1) % NS], ks + NS - 1);
+        if (ks < nk) compute(ks & 1);
+        store_lds((ks + 1) & 1, st[(S + 1) % NS]);
         lds_barrier();
-    }
+        ++ks;
+    };
+    do {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+    } while (ks < nk);
 
     // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16
     uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
