@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="decode kernel shape (waves*100 + loads in flight); 0 = default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
+    ap.add_argument("--with-others", action="store_true",
+                    help="with --roofline-only: also run the other kernels' leg (few eager launches each)")
     ap.add_argument("--unfused", action="store_true",
                     help="decode steps as matkv_materialize_tail + matkv_decode_attn instead of matkv_decode_step")
     ap.add_argument("--decode-only-reps", type=int, default=20)
@@ -253,7 +255,7 @@ def main():
 
     # ------------------------------- other kernels: rates against their own rooflines -----------
     other = None
-    if not args.roofline_only:
+    if not args.roofline_only or args.with_others:
         with torch.cuda.stream(cs):
             # chunk materialization (ingest time in the paper; here: one chunk, every layer)
             x_chunk = normal((shape.name, "x_chunk"), (L, Hd), vs, tdt, dev)

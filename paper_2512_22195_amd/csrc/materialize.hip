@@ -244,9 +244,11 @@ hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
     const int total_rows = a.n_tokens;
     if (total_rows <= 0) return hipSuccess;
-    // a few dozen rows (a decode step of a batch) make too few GEMM tiles to fill the chip: the
-    // GEMV form re-reads the weights from the caches once per 4 rows and still comes out ahead
-    if (gemv_supported(a, dtype) && total_rows < kGemmMinRows) return launch_gemv(a, total_rows, s);
+    // up to 15 rows (a decode step of a small batch): the GEMV form, which reads the weights once
+    // per 4 rows; from 16 rows on the matrix cores take over (skinny form, then the tiled GEMM)
+    if (gemv_supported(a, dtype) && total_rows < kGemmMinRows &&
+        !(total_rows >= 16 && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))
+        return launch_gemv(a, total_rows, s);
     if (materialize_mfma_supported(a, dtype, total_rows)) return launch_materialize_mfma(a, total_rows, s);
     if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);
     if (gemv_supported(a, dtype)) return launch_gemv(a, total_rows, s);

@@ -209,13 +209,139 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
     }
 }
 
+// ---- skinny form: 16 .. 255 token rows (a question, a decode step of a large batch) ----------
+// Too few rows for the tiled GEMM to fill the chip (64 rows make 16 tiles).  Here a workgroup owns
+// up to 64 rows x 16 rotary pairs (features 16g .. 16g+15 and their partners 64 further) of one
+// head of K or of V, and its eight waves split the HIDDEN axis: each wave multiplies its slice
+// with operands loaded straight from global memory in matrix-core layout (tokens as A rows,
+// weight rows as B columns; 16 bytes per lane, no LDS staging: the weights are read once, the
+// few token rows come from the caches), the eight partial tiles meet in LDS, and the rotation
+// and the single rounding to bf16 follow.  Grid: 64 x row tiles workgroups of 8 waves.
+template <int MI>
+__global__ __launch_bounds__(512) void materialize_skinny_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int NWV = 8, CH = 2;                      // waves; matrix-core steps per staged chunk (fixed by the lane layout below)
+    constexpr int TM = 16 * MI;
+    __shared__ float red[NWV][TM][33];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int pg = blockIdx.x & 3, head = (blockIdx.x >> 2) % a.Hkv, kv = (blockIdx.x >> 2) / a.Hkv;
+    const int row0 = blockIdx.y * TM;
+    const int kslice = a.Hd / NWV;                      // a multiple of 32 * CH (checked by the launcher)
+    const int n_chunks = kslice / (32 * CH);
+
+    // Columns: a chunk is 64 columns per wave; lane (c16, g4) takes the 16 consecutive columns
+    // 16 g4 .. 16 g4 + 15 of its row as two adjacent 16-byte loads, the first for one matrix-core
+    // step and the second for the next (the contraction order is free as long as tokens and
+    // weights agree), so that the four lanes of a row consume one whole 128-byte line at once
+    // instead of half of it now and half a step later.  The eight waves take adjacent 64-column
+    // pieces: together they read 1 KB of every row per chunk.
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) +
+                        ((size_t)head * D + 16 * pg + c16) * a.Hd + 64 * wave + 16 * g4;
+    const uint16_t* Whi = W + (size_t)(D / 2) * a.Hd;
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden) + 64 * wave + 16 * g4;
+    const uint16_t* xr[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) xr[mi] = X + (size_t)min(row0 + 16 * mi + c16, total_rows - 1) * a.Hd;
+
+    // a thread's output column in the epilogue is fixed (16 pg + tid % 16): its rotary entry is
+    // requested now, not after the reduction
+    const RopeEntry rope_e = a.rope[16 * pg + (tid & 15)];
+
+    struct Chunk { uint4 x[MI][CH], wl[CH], wh[CH]; };
+    auto load = [&](Chunk& c, int ci) {
+        const int off = min(ci, n_chunks - 1) * (32 * CH * NWV);
+#pragma unroll
+        for (int s = 0; s < CH; ++s) {
+            c.wl[s] = ldg16(W + off + 8 * s);
+            c.wh[s] = ldg16(Whi + off + 8 * s);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) c.x[mi][s] = ldg16(xr[mi] + off + 8 * s);
+        }
+    };
+    f32x4 acc[MI][2];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) { acc[mi][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[mi][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    auto mma = [&](const Chunk& c) {
+#pragma unroll
+        for (int s = 0; s < CH; ++s)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const bf16x8 xa = __builtin_bit_cast(bf16x8, c.x[mi][s]);
+                acc[mi][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, __builtin_bit_cast(bf16x8, c.wl[s]), acc[mi][0], 0, 0, 0);
+                acc[mi][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, __builtin_bit_cast(bf16x8, c.wh[s]), acc[mi][1], 0, 0, 0);
+            }
+    };
+    // NCH chunks in flight; loads carry no branch (past the end they repeat the last chunk) and
+    // the loop has one exit, so the compiler counts the loads in flight exactly
+    {
+        constexpr int NCH = MI == 1 ? 4 : 2;
+        Chunk c[NCH];
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) load(c[i], i);
+        int ci = 0;
+        do {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                if (ci + i < n_chunks) mma(c[i]);
+                load(c[i], ci + i + NCH);
+            }
+            ci += NCH;
+        } while (ci < n_chunks);
+    }
+
+    // lane holds tokens 16mi + 4*g4 + i, feature c16 of the low (h = 0) or high (h = 1) half
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][16 * mi + 4 * g4 + i][16 * h + c16] = acc[mi][h][i];
+    __syncthreads();
+
+    uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+    for (int idx = tid; idx < TM * 16; idx += NWV * 64) {
+        const int t = idx >> 4, p = idx & 15;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) { lo += red[w][t][p]; hi += red[w][t][16 + p]; }
+        const RowDest d = resolve_row(a, row0 + t);
+        if (!d.valid) continue;
+        const int j = 16 * pg + p;
+        if (kv == 0) {
+            float c, s;
+            rope_cs(rope_e, d.pos, c, s);
+            const float k0 = lo * c - hi * s;
+            const float k1 = lo * s + hi * c;
+            lo = k0; hi = k1;
+        }
+        out[d.elem_off + j] = f32_to_bf16_rne(lo);
+        out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
+    }
+}
+
 }  // namespace
 
 bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows) {
     return dtype == MATKV_BF16 && a.D == 128 && (a.Hd % BK) == 0 && total_rows >= 16;
 }
 
+// Skinny form: measured ahead of the tiled GEMM below a few hundred rows, where the GEMM's grid
+// leaves most compute units idle.
+constexpr int kSkinnyMaxRows = 256;
+
 hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    if (total_rows < kSkinnyMaxRows && (a.Hd % 512) == 0) {
+        const dim3 block(512);
+        const int gx = 2 * a.Hkv * 4;
+        // 16-row tiles keep every compute unit busy from 64 rows on (64 x 4 workgroups) and leave
+        // registers for four chunks of loads in flight; from 512 workgroups on, 32-row tiles halve
+        // the re-reading of the weights
+        if (total_rows <= 128) hipLaunchKernelGGL(materialize_skinny_kernel<1>, dim3(gx, (total_rows + 15) / 16), block, 0, s, a, total_rows);
+        else                   hipLaunchKernelGGL(materialize_skinny_kernel<2>, dim3(gx, (total_rows + 31) / 32), block, 0, s, a, total_rows);
+        return hipGetLastError();
+    }
     const dim3 block(256);
     if (2 * a.Hkv * ((total_rows + 127) / 128) >= 256) {
         hipLaunchKernelGGL(materialize_mfma_kernel<128>, dim3(2 * a.Hkv, (total_rows + 127) / 128), block, 0, s, a, total_rows);

@@ -98,6 +98,43 @@ def test_decode_step_other_shapes_run_two_launches():
     _chain_parity(case, fused=True)
 
 
+@pytest.mark.parametrize("T", [16, 37, 64, 150, 255, 300, 2100])
+def test_materialize_row_count_forms_bf16(T):
+    """The bf16 projection picks its kernel by row count: skinny split-hidden form (16..255 rows;
+    one, two and four 16-row blocks, several row tiles, ragged ends), tiled GEMM with 64-row
+    tiles (300) and with 128-row tiles (2100, where they fill the chip).  Each against the
+    oracle, K with rotary positions starting at 1000."""
+    case = Case("bf16-rows", n_layers=1, Hq=16, Hkv=8, D=128, hidden=512, dtype="bf16",
+                chunk_lens={0: 8}, retrieved=[[0]], q_lens=[1], steps=0, rope_base=500000.0, scale=1.0 / 4.0)
+    from workload import normal, to_f64
+    import oracle
+    ctx = chain.make_context(case)
+    try:
+        with torch.cuda.stream(ctx.compute_stream):
+            w = normal(("rows", "w"), (2, 8 * 128, 512), 0.25, torch.bfloat16).cuda()
+            x = normal(("rows", "x", T), (T, 512), 0.25, torch.bfloat16).cuda()
+            k = torch.zeros((8, T, 128), dtype=torch.bfloat16, device="cuda")
+            v = torch.zeros_like(k)
+            ctx.materialize(x, w[0], w[1], T, 1000, k, v, T)
+            ctx.compute_stream.synchronize()
+        K, V = oracle.materialize(to_f64(x), to_f64(w[0]), to_f64(w[1]), 8, 128, 1000.0, 500000.0)
+        chain.compare_materialized(case, k.cpu(), K, f"K, {T} rows")
+        chain.compare_materialized(case, v.cpu(), V, f"V, {T} rows")
+    finally:
+        ctx.close()
+
+
+def test_bf16_chain_batch17_decode_rows_on_matrix_cores():
+    """Seventeen instances: the decode-token projection has 17 rows (skinny form, ragged second
+    16-row block), the question projection 17 ragged groups of rows."""
+    B = 17
+    case = Case("bf16-chain-b17", n_layers=1, Hq=8, Hkv=2, D=128, hidden=512, dtype="bf16",
+                chunk_lens={0: 33, 1: 20}, retrieved=[[i % 2] for i in range(B)],
+                q_lens=[1 + (i % 3) for i in range(B)], steps=2, rope_base=500000.0,
+                scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case)
+
+
 def test_materialize_large_positions_bf16():
     """Question/decode tokens sit at positions ~20 000: rotary angles must stay accurate."""
     case = Case("bf16-farpos", n_layers=1, Hq=4, Hkv=1, D=128, hidden=256, dtype="bf16",
