@@ -9,6 +9,7 @@
  *
  *   matkv_materialize       K = RoPE(X Wk^T), V = X Wv^T of one layer   (III-B steps 1-3)
  *   matkv_load              pinned-host KV blob -> HBM slot, side stream (IV, load_KV)
+ *   matkv_load_file         the same from a file, through pinned bounce buffers (IV, load_KV)
  *   matkv_assemble          page table of a batch, no data movement      (IV, put_KV)
  *   matkv_prefill_attn      question rows over [chunks | question]       (V-A "prefill time")
  *   matkv_decode_attn       newest token over [chunks | tail]            (V-A "decode time")
@@ -60,7 +61,8 @@ typedef enum {
     MATKV_ENOTREADY = 3,     /* a page's load has neither completed nor been waited for */
     MATKV_EBUSY = 4,         /* resource in use (capture already open, ticket ring full) */
     MATKV_EHIP = 5,          /* a HIP call failed; sticky until the context is destroyed */
-    MATKV_ENOMEM = 6         /* host allocation failed or caller's buffer too small */
+    MATKV_ENOMEM = 6,        /* host allocation failed or caller's buffer too small */
+    MATKV_EIO = 7            /* reading a file failed or it ended early */
 } matkv_status;
 
 typedef enum { MATKV_F32 = 0, MATKV_BF16 = 1 } matkv_dtype;
@@ -145,12 +147,28 @@ matkv_status matkv_materialize_tail(matkv_ctx* ctx, const void* hidden, const vo
 
 /* Asynchronous byte-exact copy of one blob, pinned host memory -> device slot, on the load
  * stream.  host_blob must be pinned (hipHostMalloc) and stay valid until the ticket
- * completes; bytes must equal matkv_blob_bytes(cfg, n_tokens) and fit slot_bytes.  If the
- * slot was referenced by an earlier matkv_assemble, the copy is ordered after all compute
- * work enqueued so far.  Errors: EINVAL (null, size mismatch, not pinned, slot too small),
+ * completes; bytes must equal matkv_blob_bytes(cfg, n_tokens) and fit slot_bytes.  If a cache
+ * table still points into the slot, the copy is ordered after all compute work enqueued so
+ * far; if that table has since been re-assembled onto other slots, only after the work that
+ * was enqueued up to that re-assembly (so the next instance's load runs beside the current
+ * instance's kernels whichever of the two is enqueued first).  Errors: EINVAL (null, size mismatch, not pinned, slot too small),
  * EBUSY (more than 4096 tickets outstanding), EHIP. */
 matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int32_t n_tokens,
                         void* device_slot, size_t slot_bytes, matkv_ticket* out);
+/* The storage half of load_KV (Section IV: materialized KVs live as raw bytes on flash storage):
+ * the blob is `bytes` bytes at `offset` of the open file descriptor fd.  The call reads the
+ * file in pieces into pinned bounce buffers owned by the context (4 x 8 MiB, allocated on the
+ * first call) and enqueues each piece's copy on the load stream, reading the next piece while
+ * the earlier copies are in flight.  It returns once the LAST piece is enqueued, i.e. it blocks
+ * the calling thread for about the file-read time while work already enqueued on the compute
+ * stream keeps running; the ticket then behaves as matkv_load's.  A descriptor opened with
+ * O_DIRECT needs offset and bytes to be multiples of the device's block size (4096 is safe; a
+ * blob of a multiple of 8 tokens is a multiple of 4096 at head_dim 128); where the system cannot
+ * do direct I/O into pinned GPU-visible memory the pieces pass through one more host copy.  On MATKV_EIO (read
+ * error, file shorter than the blob) no ticket is issued and part of the slot may have been
+ * overwritten.  Other errors as matkv_load. */
+matkv_status matkv_load_file(matkv_ctx* ctx, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
+                             void* device_slot, size_t slot_bytes, matkv_ticket* out);
 /* Makes the compute stream wait for the ticket's copy (does not block the host). */
 matkv_status matkv_wait(matkv_ctx* ctx, matkv_ticket t);
 /* MATKV_OK if the copy has finished, MATKV_ENOTREADY if not; never blocks. */

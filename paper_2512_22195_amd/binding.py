@@ -17,13 +17,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmatkv.so")
 
-OK, EINVAL, EUNSUPPORTED, ENOTREADY, EBUSY, EHIP, ENOMEM = range(7)
+OK, EINVAL, EUNSUPPORTED, ENOTREADY, EBUSY, EHIP, ENOMEM, EIO = range(8)
 F32, BF16 = 0, 1
 
 EXPORTS = [
     "matkv_blob_bytes", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
     "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
-    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load",
+    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load", "matkv_load_file",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
@@ -78,6 +78,8 @@ def _load_library():
     lib.matkv_materialize_tail.restype = c_int32
     lib.matkv_load.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p, c_size_t, POINTER(Ticket)]
     lib.matkv_load.restype = c_int32
+    lib.matkv_load_file.argtypes = [c_void_p, c_int32, c_uint64, c_size_t, c_int32, c_void_p, c_size_t, POINTER(Ticket)]
+    lib.matkv_load_file.restype = c_int32
     for fn in (lib.matkv_wait, lib.matkv_query, lib.matkv_sync):
         fn.argtypes = [c_void_p, Ticket]; fn.restype = c_int32
     lib.matkv_assemble.argtypes = [c_void_p, POINTER(Page), POINTER(c_int32), POINTER(c_int32),
@@ -228,6 +230,13 @@ class Context:
         sb = device_slot.numel() * device_slot.element_size() if slot_bytes is None else slot_bytes
         self._check(_lib.matkv_load(self._h, _ptr(host_blob), nb, n_tokens, _ptr(device_slot), sb, byref(t)),
                     "matkv_load")
+        return t
+
+    def load_file(self, fd: int, offset: int, nbytes: int, n_tokens: int, device_slot, slot_bytes=None) -> Ticket:
+        t = Ticket()
+        sb = device_slot.numel() * device_slot.element_size() if slot_bytes is None else slot_bytes
+        self._check(_lib.matkv_load_file(self._h, fd, offset, nbytes, n_tokens, _ptr(device_slot), sb, byref(t)),
+                    "matkv_load_file")
         return t
 
     def wait(self, ticket: Ticket):

@@ -204,6 +204,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
 }
 
 constexpr int kGemmMinRows = 64;
+constexpr int kSkinnyMinRows = 32;
 
 bool gemv_supported(const MaterializeArgs& a, int dtype) { return dtype == MATKV_BF16 && (a.Hd % 4096) == 0; }
 
@@ -244,10 +245,11 @@ hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
     const int total_rows = a.n_tokens;
     if (total_rows <= 0) return hipSuccess;
-    // up to 15 rows (a decode step of a small batch): the GEMV form, which reads the weights once
-    // per 4 rows; from 16 rows on the matrix cores take over (skinny form, then the tiled GEMM)
+    // a decode step of a batch: the GEMV form, which reads the weights once per 4 rows, is ahead
+    // up to about 24 rows (16 rows: 11.7 us against the skinny form's flat 16 us); from 32 rows on
+    // the matrix cores take over (skinny form, then the tiled GEMM)
     if (gemv_supported(a, dtype) && total_rows < kGemmMinRows &&
-        !(total_rows >= 16 && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))
+        !(total_rows >= kSkinnyMinRows && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))
         return launch_gemv(a, total_rows, s);
     if (materialize_mfma_supported(a, dtype, total_rows)) return launch_materialize_mfma(a, total_rows, s);
     if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);

@@ -4,7 +4,10 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
+#include <errno.h>
+#include <unistd.h>
 
 #include <algorithm>
 #include <new>
@@ -19,6 +22,9 @@ namespace {
 
 constexpr int kTicketRing = 4096;
 constexpr int kStagingRing = 4;
+constexpr int kReleaseRing = 8;                // events marking "work on a table's old contents is enqueued"
+constexpr int kBounceRing = 4;                 // pinned pieces between a file and the load stream
+constexpr size_t kBounceBytes = 8u << 20;
 
 struct Ticket {
     hipEvent_t ev = nullptr;
@@ -30,7 +36,8 @@ struct Ticket {
 struct SlotState {
     uint64_t pending = 0;     // ticket id of the last load into the slot (0 = none)
     bool waited = true;       // compute stream has been ordered after that load
-    bool referenced = false;  // some assembled table points into it
+    int refs = 0;             // live cache tables that point into it
+    hipEvent_t release = nullptr;   // recorded on the compute stream when its last table let go of it
 };
 
 struct TableHost {
@@ -39,6 +46,7 @@ struct TableHost {
     int max_punit_items = 0;  // most items of any one prefill unit
     int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
     int min_tail_len = 0;
+    std::vector<const void*> slots;   // distinct slots its pages point into
 };
 
 struct Staging {
@@ -71,7 +79,13 @@ struct matkv_ctx {
     std::unordered_map<const void*, TableHost> tables;
     Staging staging[kStagingRing];
     int staging_next = 0;
+    Staging bounce[kBounceRing];              // allocated at the first matkv_load_file
+    int bounce_next = 0;
+    char* plain_buf = nullptr;                // see matkv_load_file: direct reads that cannot target pinned memory
+    bool read_via_plain = false;
     hipEvent_t fence_ev = nullptr;
+    hipEvent_t release_ev[kReleaseRing] = {};
+    int release_next = 0;
     bool capturing = false;
     matkv_graph* cap = nullptr;
     std::vector<matkv_graph*> graphs;
@@ -247,6 +261,7 @@ const char* matkv_status_string(matkv_status s) {
         case MATKV_EBUSY: return "MATKV_EBUSY";
         case MATKV_EHIP: return "MATKV_EHIP";
         case MATKV_ENOMEM: return "MATKV_ENOMEM";
+        case MATKV_EIO: return "MATKV_EIO";
     }
     return "MATKV_?";
 }
@@ -346,6 +361,13 @@ matkv_status matkv_destroy(matkv_ctx* c) {
         if (c->staging[i].ev) (void)hipEventDestroy(c->staging[i].ev);
         if (c->staging[i].host) (void)hipHostFree(c->staging[i].host);
     }
+    for (int i = 0; i < kBounceRing; ++i) {
+        if (c->bounce[i].ev) (void)hipEventDestroy(c->bounce[i].ev);
+        if (c->bounce[i].host) (void)hipHostFree(c->bounce[i].host);
+    }
+    free(c->plain_buf);
+    for (int i = 0; i < kReleaseRing; ++i)
+        if (c->release_ev[i]) (void)hipEventDestroy(c->release_ev[i]);
     if (c->fence_ev) (void)hipEventDestroy(c->fence_ev);
     (void)hipGetLastError();
     delete c;
@@ -409,51 +431,122 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
 
 // ------------------------------------------------------------------------------------ L ----
 
+// Checks shared by both load entry points; on success *t_out is the ticket record to fill and
+// the load stream has been ordered after compute work that may still read the slot.
+static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, int32_t n_tokens,
+                                 void* device_slot, size_t slot_bytes, Ticket** t_out) {
+    if (n_tokens < 1) return fail(c, MATKV_EINVAL, "%s: n_tokens=%d", name, n_tokens);
+    const size_t want = matkv_blob_bytes(&c->cfg, n_tokens);
+    if (bytes != want) return fail(c, MATKV_EINVAL, "%s: %zu bytes given, a %d-token blob has %zu", name, bytes, n_tokens, want);
+    if (slot_bytes < bytes) return fail(c, MATKV_EINVAL, "%s: slot of %zu bytes cannot hold %zu", name, slot_bytes, bytes);
+    if (!aligned16(device_slot)) return fail(c, MATKV_EINVAL, "%s: pointers must be 16-byte aligned", name);
+    hipPointerAttribute_t attr;
+    hipError_t pe = hipPointerGetAttributes(&attr, device_slot);
+    if (pe != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(c, MATKV_EINVAL, "%s: slot is not device memory", name);
+    }
+    Ticket& t = c->tickets[c->next_ticket % kTicketRing];
+    if (t.id != 0 && !t.done) {
+        hipError_t q = hipEventQuery(t.ev);
+        if (q == hipErrorNotReady) { (void)hipGetLastError(); return fail(c, MATKV_EBUSY, "%s: %d tickets outstanding", name, kTicketRing); }
+        if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
+        t.done = true;
+    }
+    if (!t.ev) HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
+    SlotState& s = c->slots[device_slot];
+    if (s.refs > 0) {
+        // a live table still points into the slot: order the copy after all compute work so far
+        HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
+        HIP_TRY(c, hipStreamWaitEvent(c->load, c->fence_ev, 0));
+    } else if (s.release) {
+        // its last table was re-assembled onto other slots: the copy waits for the work that was
+        // enqueued up to that moment, not for what has been enqueued since
+        HIP_TRY(c, hipStreamWaitEvent(c->load, s.release, 0));
+    }
+    s.release = nullptr;
+    *t_out = &t;
+    return MATKV_OK;
+}
+
+// The copies of a load are on the load stream: record the ticket's event behind them.
+static matkv_status load_finish(matkv_ctx* c, Ticket* t, void* device_slot, matkv_ticket* out) {
+    HIP_TRY(c, hipEventRecord(t->ev, c->load));
+    t->id = c->next_ticket++;
+    t->slot = device_slot;
+    t->done = false;
+    SlotState& s = c->slots[device_slot];
+    s.pending = t->id;
+    s.waited = false;
+    out->id = t->id;
+    return MATKV_OK;
+}
+
 matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32_t n_tokens,
                         void* device_slot, size_t slot_bytes, matkv_ticket* out) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;
     if (!host_blob || !device_slot || !out) return fail(c, MATKV_EINVAL, "load: null pointer");
-    if (n_tokens < 1) return fail(c, MATKV_EINVAL, "load: n_tokens=%d", n_tokens);
-    const size_t want = matkv_blob_bytes(&c->cfg, n_tokens);
-    if (bytes != want) return fail(c, MATKV_EINVAL, "load: %zu bytes given, a %d-token blob has %zu", bytes, n_tokens, want);
-    if (slot_bytes < bytes) return fail(c, MATKV_EINVAL, "load: slot of %zu bytes cannot hold %zu", slot_bytes, bytes);
-    if (!aligned16(device_slot) || !aligned16(host_blob)) return fail(c, MATKV_EINVAL, "load: pointers must be 16-byte aligned");
+    if (!aligned16(host_blob)) return fail(c, MATKV_EINVAL, "load: pointers must be 16-byte aligned");
     hipPointerAttribute_t attr;
     hipError_t pe = hipPointerGetAttributes(&attr, host_blob);
     if (pe != hipSuccess) { (void)hipGetLastError(); return fail(c, MATKV_EINVAL, "load: host blob is not pinned memory"); }
     if (attr.type != hipMemoryTypeHost) return fail(c, MATKV_EINVAL, "load: host blob is not pinned host memory");
-    pe = hipPointerGetAttributes(&attr, device_slot);
-    if (pe != hipSuccess || attr.type != hipMemoryTypeDevice) {
-        (void)hipGetLastError();
-        return fail(c, MATKV_EINVAL, "load: slot is not device memory");
-    }
-
-    Ticket& t = c->tickets[c->next_ticket % kTicketRing];
-    if (t.id != 0 && !t.done) {
-        hipError_t q = hipEventQuery(t.ev);
-        if (q == hipErrorNotReady) { (void)hipGetLastError(); return fail(c, MATKV_EBUSY, "load: %d tickets outstanding", kTicketRing); }
-        if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
-        t.done = true;
-    }
-    if (!t.ev) HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
-
-    SlotState& s = c->slots[device_slot];
-    if (s.referenced) {
-        // the slot may still be read by compute work enqueued so far: order the copy after it
-        HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
-        HIP_TRY(c, hipStreamWaitEvent(c->load, c->fence_ev, 0));
-        s.referenced = false;
-    }
+    Ticket* t;
+    st = load_prepare(c, "load", bytes, n_tokens, device_slot, slot_bytes, &t);
+    if (st != MATKV_OK) return st;
     HIP_TRY(c, hipMemcpyAsync(device_slot, host_blob, bytes, hipMemcpyHostToDevice, c->load));
-    HIP_TRY(c, hipEventRecord(t.ev, c->load));
-    t.id = c->next_ticket++;
-    t.slot = device_slot;
-    t.done = false;
-    s.pending = t.id;
-    s.waited = false;
-    out->id = t.id;
-    return MATKV_OK;
+    return load_finish(c, t, device_slot, out);
+}
+
+matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
+                             void* device_slot, size_t slot_bytes, matkv_ticket* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (fd < 0 || !device_slot || !out) return fail(c, MATKV_EINVAL, "load_file: bad descriptor or null pointer");
+    if (c->capturing) return fail(c, MATKV_EBUSY, "load_file: not allowed while a graph is being captured");
+    Ticket* t;
+    st = load_prepare(c, "load_file", bytes, n_tokens, device_slot, slot_bytes, &t);
+    if (st != MATKV_OK) return st;
+    for (int i = 0; i < kBounceRing; ++i) {
+        if (c->bounce[i].host) continue;
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
+    }
+    // piece k+1 is read from the file while the copies of the pieces before it are in flight
+    size_t done = 0;
+    while (done < bytes) {
+        Staging& b = c->bounce[c->bounce_next];
+        c->bounce_next = (c->bounce_next + 1) % kBounceRing;
+        if (b.used) HIP_TRY(c, hipEventSynchronize(b.ev));
+        const size_t piece = std::min(kBounceBytes, bytes - done);
+        size_t got = 0;
+        while (got < piece) {
+            char* dest = c->read_via_plain ? c->plain_buf : b.host;
+            ssize_t r = pread(fd, dest + got, piece - got, (off_t)(offset + done + got));
+            if (r < 0 && errno == EINTR) continue;
+            if (r < 0 && errno == EFAULT && !c->read_via_plain) {
+                // direct I/O cannot pin the device-mapped bounce buffer on this system: from now
+                // on read into plain page-aligned memory and copy into the bounce buffer
+                if (!c->plain_buf && posix_memalign(reinterpret_cast<void**>(&c->plain_buf), 4096, kBounceBytes) != 0) {
+                    c->plain_buf = nullptr;
+                    return fail(c, MATKV_ENOMEM, "load_file: out of host memory");
+                }
+                c->read_via_plain = true;
+                if (got) memcpy(c->plain_buf, b.host, got);
+                continue;
+            }
+            if (r < 0) return fail(c, MATKV_EIO, "load_file: pread at %llu: %s", (unsigned long long)(offset + done + got), strerror(errno));
+            if (r == 0) return fail(c, MATKV_EIO, "load_file: file ends %zu bytes short of the blob", bytes - done - got);
+            got += (size_t)r;
+        }
+        if (c->read_via_plain) memcpy(b.host, c->plain_buf, piece);
+        HIP_TRY(c, hipMemcpyAsync(static_cast<char*>(device_slot) + done, b.host, piece, hipMemcpyHostToDevice, c->load));
+        HIP_TRY(c, hipEventRecord(b.ev, c->load));
+        b.used = true;
+        done += piece;
+    }
+    return load_finish(c, t, device_slot, out);
 }
 
 static matkv_status ticket_lookup(matkv_ctx* c, matkv_ticket tk, Ticket** out) {
@@ -564,7 +657,6 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         long inst_tokens = 0;
         for (int p = 0; p < n_pages[b]; ++p) {
             inst_tokens += pg[p].n_tokens;
-            c->slots[pg[p].slot].referenced = true;
         }
         in.pos_base = pos_base ? pos_base[b] : inst_tokens;
         if (in.pos_base + cfg.max_tail_tokens > (1ll << 24)) return fail(c, MATKV_EINVAL, "assemble: positions beyond 2^24");
@@ -602,6 +694,26 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
 
     th.batch = batch; th.n_items = n_items; th.n_dunits = n_dunits; th.n_punits = n_punits;
     th.total_q = cu; th.max_q = max_q;
+    // Slot bookkeeping: the table's old contents are dead from here on in stream order, so the
+    // slots only they pointed into may be overwritten once the work enqueued so far is done.
+    for (int b = 0; b < batch; ++b) {
+        const matkv_page* pg = pages ? pages + (size_t)b * cfg.max_pages : nullptr;
+        for (int p = 0; p < n_pages[b]; ++p)
+            if (std::find(th.slots.begin(), th.slots.end(), pg[p].slot) == th.slots.end()) th.slots.push_back(pg[p].slot);
+    }
+    auto old = c->tables.find(table);
+    if (old != c->tables.end() && !old->second.slots.empty()) {
+        hipEvent_t& ev = c->release_ev[c->release_next];
+        c->release_next = (c->release_next + 1) % kReleaseRing;
+        if (!ev) HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        HIP_TRY(c, hipEventRecord(ev, c->compute));
+        for (const void* sl : old->second.slots) {
+            SlotState& ss = c->slots[sl];
+            if (ss.refs > 0) --ss.refs;
+            if (ss.refs == 0) ss.release = ev;
+        }
+    }
+    for (const void* sl : th.slots) ++c->slots[sl].refs;
     c->tables[table] = th;
     return MATKV_OK;
 }

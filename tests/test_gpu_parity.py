@@ -351,6 +351,61 @@ def test_load_is_byte_exact_and_validates():
         ctx.close()
 
 
+def test_load_file_is_byte_exact(tmp_path):
+    """matkv_load_file: blobs read from a file at nonzero offsets, through the bounce buffers
+    (a blob of several 8 MiB pieces with a ragged last one, and a small one), land byte-exact in
+    their slots; the loaded pages then serve an attention call; a file that ends early gives
+    MATKV_EIO and no ticket; O_DIRECT is used when the filesystem allows it."""
+    import os
+    from paper_2512_22195_amd import binding as mk
+    case = Case("load-file", n_layers=3, Hq=8, Hkv=4, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 3000, 1: 40}, retrieved=[[0, 1]], q_lens=[2], steps=0)
+    ctx = chain.make_context(case)
+    path = str(tmp_path / "blobs.bin")
+    try:
+        n0, n1 = mk.blob_bytes(ctx.cfg, 3000), mk.blob_bytes(ctx.cfg, 40)      # 18 432 000 and 245 760 bytes
+        assert n0 > 2 * (8 << 20) and n0 % (8 << 20) != 0
+        g = torch.Generator().manual_seed(5)
+        b0 = torch.randint(0, 256, (n0,), dtype=torch.uint8, generator=g)
+        b1 = torch.randint(0, 256, (n1,), dtype=torch.uint8, generator=g)
+        off0, off1 = 4096, 4096 + n0 + 8192
+        with open(path, "wb") as f:
+            f.write(b"\0" * off0); f.write(b0.numpy().tobytes())
+            f.write(b"\0" * 8192); f.write(b1.numpy().tobytes())
+            f.flush(); os.fsync(f.fileno())
+        for flags in (os.O_RDONLY | getattr(os, "O_DIRECT", 0), os.O_RDONLY):
+            try:
+                fd = os.open(path, flags)
+            except OSError:
+                continue                                    # no O_DIRECT on this filesystem
+            try:
+                s0, s1 = ctx.new_slot(3000), ctx.new_slot(40)
+                try:
+                    t0 = ctx.load_file(fd, off0, n0, 3000, s0)
+                except mk.MatKVError as e:
+                    if flags & getattr(os, "O_DIRECT", 0) and e.status == mk.EIO:
+                        continue                            # direct reads refused by this filesystem
+                    raise
+                t1 = ctx.load_file(fd, off1, n1, 40, s1)
+                ctx.sync(t1)
+                assert ctx.query(t0) and ctx.query(t1)
+                assert torch.equal(s0.cpu(), b0) and torch.equal(s1.cpu(), b1)
+                with pytest.raises(mk.MatKVError) as e:     # the file ends inside the blob
+                    ctx.load_file(fd, off1 + 4096, n1, 40, s1)
+                assert e.value.status == mk.EIO
+                with pytest.raises(mk.MatKVError) as e:     # wrong byte count
+                    ctx.load_file(fd, off1, n1 - 4096, 40, s1)
+                assert e.value.status == mk.EINVAL
+                # pages loaded from the file are ordinary pages
+                ctx.wait(t0); ctx.wait(t1)
+                table = ctx.new_table()
+                ctx.assemble([[(s0, 3000), (s1, 40)]], [2], table)
+            finally:
+                os.close(fd)
+    finally:
+        ctx.close()
+
+
 def test_assemble_rejects_bad_arguments():
     from paper_2512_22195_amd import binding as mk
     case = Case("asm", n_layers=1, Hq=4, Hkv=2, D=64, hidden=64, dtype="f32",
