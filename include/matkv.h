@@ -10,6 +10,7 @@
  *   matkv_materialize       K = RoPE(X Wk^T), V = X Wv^T of one layer   (III-B steps 1-3)
  *   matkv_load              pinned-host KV blob -> HBM slot, side stream (IV, load_KV)
  *   matkv_load_file         the same from a file, through pinned bounce buffers (IV, load_KV)
+ *   matkv_store_file        device blob -> file, through the same buffers       (IV, store_KV)
  *   matkv_assemble          page table of a batch, no data movement      (IV, put_KV)
  *   matkv_prefill_attn      question rows over [chunks | question]       (V-A "prefill time")
  *   matkv_decode_attn       newest token over [chunks | tail]            (V-A "decode time")
@@ -169,6 +170,12 @@ matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int
  * overwritten.  Other errors as matkv_load. */
 matkv_status matkv_load_file(matkv_ctx* ctx, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
                              void* device_slot, size_t slot_bytes, matkv_ticket* out);
+/* The storage half of store_KV (Section IV): writes `bytes` of device memory (a materialized blob
+ * or any part of one) to the open file descriptor at `offset`, through the same pinned bounce
+ * buffers, after all work enqueued on the compute stream so far.  Synchronous: returns when the
+ * last byte has been handed to pwrite (no fsync).  O_DIRECT descriptors: as for matkv_load_file.
+ * Errors: EINVAL, EIO, EHIP, ENOMEM. */
+matkv_status matkv_store_file(matkv_ctx* ctx, int fd, uint64_t offset, const void* device_blob, size_t bytes);
 /* Makes the compute stream wait for the ticket's copy (does not block the host). */
 matkv_status matkv_wait(matkv_ctx* ctx, matkv_ticket t);
 /* MATKV_OK if the copy has finished, MATKV_ENOTREADY if not; never blocks. */

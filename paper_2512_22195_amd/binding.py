@@ -23,7 +23,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "matkv_blob_bytes", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
     "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
-    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load", "matkv_load_file",
+    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load", "matkv_load_file", "matkv_store_file",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
@@ -80,6 +80,8 @@ def _load_library():
     lib.matkv_load.restype = c_int32
     lib.matkv_load_file.argtypes = [c_void_p, c_int32, c_uint64, c_size_t, c_int32, c_void_p, c_size_t, POINTER(Ticket)]
     lib.matkv_load_file.restype = c_int32
+    lib.matkv_store_file.argtypes = [c_void_p, c_int32, c_uint64, c_void_p, c_size_t]
+    lib.matkv_store_file.restype = c_int32
     for fn in (lib.matkv_wait, lib.matkv_query, lib.matkv_sync):
         fn.argtypes = [c_void_p, Ticket]; fn.restype = c_int32
     lib.matkv_assemble.argtypes = [c_void_p, POINTER(Page), POINTER(c_int32), POINTER(c_int32),
@@ -238,6 +240,10 @@ class Context:
         self._check(_lib.matkv_load_file(self._h, fd, offset, nbytes, n_tokens, _ptr(device_slot), sb, byref(t)),
                     "matkv_load_file")
         return t
+
+    def store_file(self, fd: int, offset: int, device_blob, nbytes=None):
+        nb = device_blob.numel() * device_blob.element_size() if nbytes is None else nbytes
+        self._check(_lib.matkv_store_file(self._h, fd, offset, _ptr(device_blob), nb), "matkv_store_file")
 
     def wait(self, ticket: Ticket):
         self._check(_lib.matkv_wait(self._h, ticket), "matkv_wait")

@@ -549,6 +549,68 @@ matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes
     return load_finish(c, t, device_slot, out);
 }
 
+matkv_status matkv_store_file(matkv_ctx* c, int fd, uint64_t offset, const void* device_blob, size_t bytes) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (fd < 0 || !device_blob || bytes == 0) return fail(c, MATKV_EINVAL, "store_file: bad descriptor, null pointer or no bytes");
+    if (c->capturing) return fail(c, MATKV_EBUSY, "store_file: not allowed while a graph is being captured");
+    hipPointerAttribute_t attr;
+    hipError_t pe = hipPointerGetAttributes(&attr, device_blob);
+    if (pe != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(c, MATKV_EINVAL, "store_file: blob is not device memory");
+    }
+    for (int i = 0; i < kBounceRing; ++i) {
+        if (c->bounce[i].host) continue;
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
+    }
+    // the blob was produced on the compute stream: the copies out follow what is enqueued there
+    HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
+    HIP_TRY(c, hipStreamWaitEvent(c->load, c->fence_ev, 0));
+    // piece k is written to the file while the copy of piece k+1 is in flight
+    const size_t n_pieces = (bytes + kBounceBytes - 1) / kBounceBytes;
+    auto piece_bytes = [&](size_t k) { return std::min(kBounceBytes, bytes - k * kBounceBytes); };
+    auto enqueue = [&](size_t k) -> hipError_t {
+        Staging& b = c->bounce[k % kBounceRing];
+        if (b.used) { hipError_t e = hipEventSynchronize(b.ev); if (e != hipSuccess) return e; }
+        hipError_t e = hipMemcpyAsync(b.host, static_cast<const char*>(device_blob) + k * kBounceBytes, piece_bytes(k),
+                                      hipMemcpyDeviceToHost, c->load);
+        if (e == hipSuccess) e = hipEventRecord(b.ev, c->load);
+        b.used = true;
+        return e;
+    };
+    HIP_TRY(c, enqueue(0));
+    for (size_t k = 0; k < n_pieces; ++k) {
+        if (k + 1 < n_pieces) HIP_TRY(c, enqueue(k + 1));
+        Staging& b = c->bounce[k % kBounceRing];
+        HIP_TRY(c, hipEventSynchronize(b.ev));
+        const char* src = b.host;
+        const size_t piece = piece_bytes(k);
+        if (c->read_via_plain) { memcpy(c->plain_buf, b.host, piece); src = c->plain_buf; }
+        size_t put = 0;
+        while (put < piece) {
+            ssize_t r = pwrite(fd, src + put, piece - put, (off_t)(offset + k * kBounceBytes + put));
+            if (r < 0 && errno == EINTR) continue;
+            if (r < 0 && errno == EFAULT && !c->read_via_plain) {
+                // direct I/O cannot pin the device-mapped bounce buffer on this system (see load_file)
+                if (!c->plain_buf && posix_memalign(reinterpret_cast<void**>(&c->plain_buf), 4096, kBounceBytes) != 0) {
+                    c->plain_buf = nullptr;
+                    return fail(c, MATKV_ENOMEM, "store_file: out of host memory");
+                }
+                c->read_via_plain = true;
+                memcpy(c->plain_buf, b.host, piece);
+                src = c->plain_buf;
+                continue;
+            }
+            if (r <= 0) return fail(c, MATKV_EIO, "store_file: pwrite at %llu: %s", (unsigned long long)(offset + k * kBounceBytes + put),
+                                    r < 0 ? strerror(errno) : "no progress");
+            put += (size_t)r;
+        }
+    }
+    return MATKV_OK;
+}
+
 static matkv_status ticket_lookup(matkv_ctx* c, matkv_ticket tk, Ticket** out) {
     if (tk.id == 0 || tk.id >= c->next_ticket) return fail(c, MATKV_EINVAL, "ticket %llu was never issued", (unsigned long long)tk.id);
     Ticket& t = c->tickets[tk.id % kTicketRing];

@@ -180,11 +180,13 @@ def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=Non
             ctx.close()
 
 
-def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False):
+def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False, blob_dir=None):
     """Full chain.  Returns dict with materialized blobs/tail (CPU tensors) and outputs.
     fused: each decode step of a layer is one matkv_decode_step call instead of
     matkv_materialize_tail + matkv_decode_attn; use_graph (with fused): the step of all layers
-    is recorded once and replayed, with a synchronisation and an eager copy between replays."""
+    is recorded once and replayed, with a synchronisation and an eager copy between replays.
+    blob_dir: materialized chunks go to one file there (matkv_store_file) and come back into the
+    slots from it (matkv_load_file) instead of through pinned host tensors."""
     c = case
     ctx = make_context(c, device)
     try:
@@ -200,8 +202,33 @@ def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False
                 dev_blobs[cid] = blob
             ctx.compute_stream.synchronize()
             host_blobs = {cid: b.cpu() for cid, b in dev_blobs.items()}     # store_KV stand-in
+        if blob_dir is not None:
+            import os
+            path = os.path.join(blob_dir, f"{c.name}.kv")
+            fd = os.open(path, os.O_RDWR | os.O_CREAT | os.O_TRUNC, 0o600)
+            try:
+                offs, off = {}, 0
+                for cid, b in dev_blobs.items():                             # store_KV
+                    offs[cid] = off
+                    ctx.store_file(fd, off, b)
+                    off += (b.numel() * b.element_size() + 4095) // 4096 * 4096
+                os.fsync(fd)
+                slots = {}
+                for cid, n in c.chunk_lens.items():                          # load_KV
+                    slots[cid] = ctx.new_slot(n)
+                    nb = dev_blobs[cid].numel() * dev_blobs[cid].element_size()
+                    ctx.wait(ctx.load_file(fd, offs[cid], nb, n, slots[cid]))
+                with open(path, "rb") as f:                                  # the file holds the blobs' bytes
+                    for cid, b in host_blobs.items():
+                        f.seek(offs[cid])
+                        raw = f.read(b.numel() * b.element_size())
+                        assert raw == b.contiguous().view(torch.uint8).numpy().tobytes(), f"file bytes of chunk {cid}"
+            finally:
+                os.close(fd)
+            keep = None
         del dev_blobs
-        slots, keep = load_blobs(ctx, c, host_blobs)                         # L
+        if blob_dir is None:
+            slots, keep = load_blobs(ctx, c, host_blobs)                     # L
         with torch.cuda.stream(ctx.compute_stream):
             tail = ctx.new_tail()
             table = ctx.new_table()

@@ -351,6 +351,23 @@ def test_load_is_byte_exact_and_validates():
         ctx.close()
 
 
+def test_chain_through_files(tmp_path):
+    """The paper's round trip (Section IV): chunks are materialized on the device, written to a file
+    (matkv_store_file), read back into slots (matkv_load_file), and the question and the decode
+    steps attend over them; file bytes equal the device blobs, outputs match the oracle."""
+    case = Case("chain-files", n_layers=2, Hq=8, Hkv=2, D=128, hidden=512, dtype="bf16",
+                chunk_lens={0: 200, 1: 137, 2: 64}, retrieved=[[0, 1], [2, 0, 1]], q_lens=[9, 21],
+                steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
+    inp = chain.make_chain_inputs(case)
+    gpu = chain.run_gpu_chain(case, inp, blob_dir=str(tmp_path))
+    ref = chain.run_oracle_chain(case, inp)
+    for cid in case.chunk_lens:
+        for l in range(case.n_layers):
+            chain.compare_materialized(case, gpu["blobs"][cid][l, 0], ref["blobs"][cid][l][0], f"chunk {cid} K")
+            chain.compare_materialized(case, gpu["blobs"][cid][l, 1], ref["blobs"][cid][l][1], f"chunk {cid} V")
+    chain.compare_attention(case, gpu["o_pre"], gpu["o_dec"], ref["pre"], ref["dec"])
+
+
 def test_load_file_is_byte_exact(tmp_path):
     """matkv_load_file: blobs read from a file at nonzero offsets, through the bounce buffers
     (a blob of several 8 MiB pieces with a ragged last one, and a small one), land byte-exact in
