@@ -421,8 +421,8 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
         case 22: return launch_v<G, 2, 1, 2>(a, 1, s);
         default: break;
     }
-    // measured: eight waves pay off once eight query heads share a KV head
-    if (G == 8) return launch_v<G, 8, 1, 2>(a, 1, s);
+    // measured: four waves are ahead for every group size (config 4, G = 8: 62.7 us against
+    // 65.1 us with eight)
     return launch_v<G, 4, 1, 2>(a, 1, s);
 }
 
@@ -450,7 +450,8 @@ hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
 // in one launch (default kernel shape only).
 bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype) {
     // Measured: the single launch wins while every projection wave has one task (up to four
-    // instances) and four attention waves are the better shape anyway (group size up to 4).
+    // instances) at the 8B shape; at group size 8 with hidden 8192 (config 4) it is 3 % behind
+    // the two launches (76.6 against 74.3 us per layer and step), so it stops at group size 4.
     return attn_mfma_supported(a, dtype) && !a.prefill && a.variant == 0 && (m.Hd % 4096) == 0 &&
            a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4;
 }
