@@ -3,7 +3,7 @@
 //
 // The M dimension is the flattened (question row, query head of one KV head) index.  A
 // workgroup owns a tile of 64*MS such rows and one work unit of the cache; its four waves split
-// the ROWS (16*MS each) and walk the unit's tokens TOGETHER, 32 at a time: each K/V block is
+// the ROWS (16*MS each) and walk the unit's tokens TOGETHER, 64 at a time: each K/V block is
 // fetched from HBM once per workgroup with coalesced 16-byte loads into double-buffered LDS
 // tiles and shared by all waves -
 //   S^T = K Q^T     A = K rows from the LDS tile (padded rows, conflict-free 16-byte reads),
@@ -11,8 +11,8 @@
 //   softmax         online, per lane on its own column; the four 16-lane groups agree on the
 //                   running maximum through register swaps
 //   O^T += V^T P^T  A = V through the transposing LDS read, B = P rounded to bf16
-// Blocks are fetched two ahead of the one being used (one in registers, one in LDS), which keeps
-// two blocks per workgroup in flight against the memory latency.
+// The next block's loads are in flight (in registers) while the current one is computed out of
+// LDS; two workgroups share a compute unit.
 // A wave owns its rows outright, so nothing is merged between waves.  An instance whose cache
 // is one unit gets its output rows straight from the registers; otherwise every unit leaves an
 // unnormalised partial (accumulator, running maximum, sum) per row and a second, chip-wide
@@ -31,7 +31,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
-constexpr int BLK = 32;             // token rows per step
 constexpr int KSTR = D + 8;         // bf16 per LDS row of the K tile
 constexpr int VSTR = D + 16;        // bf16 per LDS row of the V tile
 constexpr int NW = 4;
@@ -42,12 +41,16 @@ __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)p);
 }
 
-template <int G, int MS>
+// TB = token rows per step (a multiple of 32).  64 against 32 halves the per-step costs that do
+// not depend on the number of tokens (walking the items, addresses, barrier, reference update)
+// and measured 5-12 % ahead.
+template <int G, int MS, int TB>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
     constexpr int WR = 16 * MS;                         // rows per wave
     constexpr int RT = NW * WR;                         // rows per workgroup
+    constexpr int NH = TB / 32;                         // 32-token halves of a step
     typedef uint16_t T;
 
     const int tid = threadIdx.x;
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         for (int s = 0; s < 8; ++s) ot[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    constexpr int TILE_ELEMS = BLK * KSTR + BLK * VSTR;             // one K tile + one V tile
+    constexpr int TILE_ELEMS = TB * KSTR + TB * VSTR;               // one K tile + one V tile
     __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * TILE_ELEMS];
 
     // The unit's item list sits in LDS: fetching an item from global memory inside the loop
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     __syncthreads();
 
     // Every wave walks the same blocks: the unit's items end to end (the tail clipped to the
-    // rows this tile may see), 32 token rows at a time, never across two items.
+    // rows this tile may see), TB token rows at a time, never across two items.
     struct {
         Item item;
         int item_i, rows, left;         // current item, its visible rows, rows of it not yet handed out
@@ -132,7 +135,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             r.is_tail = true;
         }
         if (wk.item.base) r.is_tail = false;
-        const int n = min(BLK, wk.left);
+        const int n = min(TB, wk.left);
         r.t0 = wk.item.tok0 + (wk.rows - wk.left);
         r.tok_end = r.t0 + n;
         r.valid = true;
@@ -141,12 +144,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         return r;
     };
 
-    // cooperative staging: thread t moves rows t/16 and t/16 + 16, columns 8*(t%16), of K and of V
+    // cooperative staging: thread t moves rows t/16 + 16i (i < TB/16), columns 8*(t%16), of K and of V
     const int st_row = tid >> 4, st_col = (tid & 15) * 8;
-    struct Stage { uint4 k[2], v[2]; };
+    constexpr int SR = TB / 16;
+    struct Stage { uint4 k[SR], v[SR]; };
     auto load_global = [&](const BlockRef<T>& r, Stage& g) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < SR; ++i) {
             const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
             g.k[i] = ldg16(r.k + off);
             g.v[i] = ldg16(r.v + off);
@@ -154,9 +158,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     };
     auto store_lds = [&](int buf, const Stage& g) {
         uint16_t* kt = tiles + buf * TILE_ELEMS;
-        uint16_t* vt = kt + BLK * KSTR;
+        uint16_t* vt = kt + TB * KSTR;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < SR; ++i) {
             *reinterpret_cast<uint4*>(kt + (st_row + 16 * i) * KSTR + st_col) = g.k[i];
             *reinterpret_cast<uint4*>(vt + (st_row + 16 * i) * VSTR + st_col) = g.v[i];
         }
@@ -172,44 +176,53 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
 
-    // masked: the block is ragged or lies in the tail (per-row causal limit); otherwise all 32
+    // masked: the block is ragged or lies in the tail (per-row causal limit); otherwise all TB
     // rows are visible to every question row and no element needs a test.
     auto compute = [&](const BlockRef<T>& r, int buf) {
-        const bool masked = r.is_tail || r.tok_end - r.t0 != BLK;
+        const bool masked = r.is_tail || r.tok_end - r.t0 != TB;
         const uint16_t* kt = tiles + buf * TILE_ELEMS;
-        const uint16_t* vt = kt + BLK * KSTR;
-        bf16x8 ak[2][4];
+        const uint16_t* vt = kt + TB * KSTR;
+        // S^T in 16-token quarters q: lane holds tokens t0 + 16q + 4*g4 + i of its row
+        f32x4 st[MS][2 * NH];
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NH; ++h) {
+            bf16x8 ak[2][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                ak[h][c] = *reinterpret_cast<const bf16x8*>(kt + (16 * h + c16) * KSTR + 32 * c + 8 * g4);
-        f32x4 sc0[MS], sc1[MS];
+            for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-        for (int j = 0; j < MS; ++j) {
-            sc0[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < 4; ++c)
+                    ak[hh][c] = *reinterpret_cast<const bf16x8*>(kt + (32 * h + 16 * hh + c16) * KSTR + 32 * c + 8 * g4);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                sc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][c], bq[j][c], sc0[j], 0, 0, 0);
-                sc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][c], bq[j][c], sc1[j], 0, 0, 0);
+            for (int j = 0; j < MS; ++j) {
+                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][c], bq[j][c], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][c], bq[j][c], s1, 0, 0, 0);
+                }
+                st[j][2 * h] = s0;
+                st[j][2 * h + 1] = s1;
             }
         }
-        bf16x8 pb[MS];
+        bf16x8 pb[MS][NH];
 #pragma unroll
         for (int j = 0; j < MS; ++j) {
-            // lane holds tokens t0 + 4*g4 + i (sc0) and t0 + 16 + 4*g4 + i (sc1) of its row
-            float sv[8] = {sc0[j][0], sc0[j][1], sc0[j][2], sc0[j][3], sc1[j][0], sc1[j][1], sc1[j][2], sc1[j][3]};
+            float sv[8 * NH];
+#pragma unroll
+            for (int q = 0; q < 2 * NH; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sv[4 * q + i] = st[j][q][i];
             if (masked) {           // wave-uniform
                 const int limit = r.is_tail ? min(r.tok_end, vis[j]) : r.tok_end;
                 const int tb = r.t0 + 4 * g4;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    sv[i] = tb + i < limit ? sv[i] : kNegBig;
-                    sv[4 + i] = tb + 16 + i < limit ? sv[4 + i] : kNegBig;
-                }
+                for (int q = 0; q < 2 * NH; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) sv[4 * q + i] = tb + 16 * q + i < limit ? sv[4 * q + i] : kNegBig;
             }
-            float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            float mx = sv[0];
+#pragma unroll
+            for (int i = 1; i < 8 * NH; ++i) mx = fmaxf(mx, sv[i]);
             mx = fmaxf(mx, lane_xor(mx, 16, lane));
             mx = fmaxf(mx, lane_xor(mx, 32, lane));
             // The reference score of a row moves only when the block's maximum exceeds it by
@@ -222,7 +235,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             // scores must still come out as weight 0, not 2^0
             const float nmc = mn > 0.5f * kNegBig ? -mn * sc : 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)fast_exp2(fmaf(sv[i], sc, nmc));
+            for (int h = 0; h < NH; ++h)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pb[j][h][i] = (__bf16)fast_exp2(fmaf(sv[8 * h + i], sc, nmc));
             if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's reference moved
                 ol[j][0] *= alpha;
 #pragma unroll
@@ -230,54 +245,50 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
                     ot[j][s][0] *= alpha; ot[j][s][1] *= alpha; ot[j][s][2] *= alpha; ot[j][s][3] *= alpha;
                 }
             }
-            ol[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j], ol[j], 0, 0, 0);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) ol[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j][h], ol[j], 0, 0, 0);
         }
         // lane (c16, g4) names 4 dims (4*(c16%4) ..) of token 4*g4 + c16/4 (+16 for the second
-        // half) and receives dim 16s + c16 of tokens 4*g4 .. 4*g4+3: the k order of P above
-        const uint16_t* vp = vt + (4 * g4 + (c16 >> 2)) * VSTR + 4 * (c16 & 3);
+        // quarter) of a half and receives dim 16s + c16 of tokens 4*g4 .. 4*g4+3: the k order of P
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const s16x4 lo = lds_read_tr(vp + 16 * s);
-            const s16x4 hi = lds_read_tr(vp + 16 * VSTR + 16 * s);
-            const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        for (int h = 0; h < NH; ++h) {
+            const uint16_t* vp = vt + (32 * h + 4 * g4 + (c16 >> 2)) * VSTR + 4 * (c16 & 3);
 #pragma unroll
-            for (int j = 0; j < MS; ++j)
-                ot[j][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j], ot[j][s], 0, 0, 0);
+            for (int s = 0; s < 8; ++s) {
+                const s16x4 lo = lds_read_tr(vp + 16 * s);
+                const s16x4 hi = lds_read_tr(vp + 16 * VSTR + 16 * s);
+                const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int j = 0; j < MS; ++j)
+                    ot[j][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[j][h], ot[j][s], 0, 0, 0);
+            }
         }
     };
-    // Steady state at the top of the loop: LDS tile 0 holds block r0, stage B holds r1 (its
-    // loads possibly still in flight).  Each half step issues the loads of the block two ahead,
-    // computes, hands the staged block to the other tile and meets the other waves.  Loads and
-    // LDS stores are unconditional (a block past the end repeats the last one): a load under a
-    // branch would leave the compiler no exact count of the loads in flight, and it would then
-    // wait for all of them.
+
+    // Loads and LDS stores are unconditional (a block past the end repeats the last one) and the
+    // loops have one exit at the bottom: a load under a branch, or a break half way, would leave
+    // the compiler no exact count of the loads in flight, and it would then wait for all of them.
+    // Every load before the loop (Q above all) is waited for once, ahead of it: otherwise each
+    // first use of Q inside the loop is guarded with a wait that, loads completing in order, would
+    // also drain the block just requested.
     BlockRef<T> r0 = next_block();
     if (r0.valid) {
-        Stage ga, gb;
-        BlockRef<T> r1 = next_block();
-        load_global(r0, ga);
-        load_global(r1, gb);
-        store_lds(0, ga);
-        // Every load so far (Q above all) is waited for here, once: otherwise each first use of
-        // Q inside the loop is guarded with a wait that, loads completing in order, would also
-        // drain the blocks just requested.
+        // one register stage: the next block's loads are in flight while this one is computed,
+        // then move into the other LDS tile
+        Stage g;
+        load_global(r0, g);
+        store_lds(0, g);
         __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0) only
         lds_barrier();
-        // one exit, at the bottom: a break half way would, after the compiler has given the loop
-        // its single latch, make stage A look in flight at the top of the loop
+        int buf = 0;
         do {
-            const BlockRef<T> r2 = next_block();
-            load_global(r2, ga);
-            if (wave_live) compute(r0, 0);
-            store_lds(1, gb);
+            const BlockRef<T> r1 = next_block();
+            load_global(r1, g);
+            if (wave_live) compute(r0, buf);
+            store_lds(buf ^ 1, g);
             lds_barrier();
-            const BlockRef<T> r3 = next_block();
-            load_global(r3, gb);
-            if (wave_live && r1.valid) compute(r1, 1);
-            store_lds(0, ga);
-            lds_barrier();
-            r0 = r2;
-            r1 = r3;
+            r0 = r1;
+            buf ^= 1;
         } while (r0.valid);
     }
     if (!wave_live) return;
@@ -370,12 +381,12 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ((size_t)q_row * a.Hq + head) * D + 4 * hl) = o;
 }
 
-template <int G, int MS>
+template <int G, int MS, int TB>
 hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
     const int tiles = (a.rows * G + NW * 16 * MS - 1) / (NW * 16 * MS);
     dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
-    hipLaunchKernelGGL((attn_prefill_kernel<G, MS>), grid, block, 0, s, k,
+    hipLaunchKernelGGL((attn_prefill_kernel<G, MS, TB>), grid, block, 0, s, k,
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
@@ -389,8 +400,8 @@ hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
 
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
-    if (a.rows * G <= 64) return launch_v<G, 1>(a, s);
-    return launch_v<G, 2>(a, s);
+    if (a.rows * G <= 64) return launch_v<G, 1, 64>(a, s);
+    return launch_v<G, 2, 64>(a, s);
 }
 
 }  // namespace

@@ -256,10 +256,14 @@ def test_chunk_order_invariance_on_gpu():
     a_pre, a_dec = chain.run_gpu_attention(c1, inp)
     b_pre, b_dec = chain.run_gpu_attention(c2, inp)
     # two summation orders, each output rounded once to bf16: one ulp (2^-7 relative) apart at
-    # most, on top of the accumulation-order noise
+    # most, on top of the noise of the bf16-rounded weights, which differ between the two orders
+    # (each run alone is held to 2e-2 rms of the oracle; the two are held to that of each other)
     for a, b in ((a_pre.float(), b_pre.float()), (a_dec.float(), b_dec.float())):
-        bound = 2.0 ** -7 * a.abs() + 1e-2 * a.pow(2).mean().sqrt()
+        bound = 2.0 ** -7 * a.abs() + 2e-2 * a.pow(2).mean().sqrt()
         assert ((a - b).abs() <= bound).all()
+    pre, dec = chain.run_oracle_attention(c1, inp)
+    chain.compare_attention(c1, a_pre, a_dec, pre, dec)
+    chain.compare_attention(c1, b_pre, b_dec, pre, dec)
 
 
 def test_graph_replay_matches_eager():
