@@ -61,7 +61,7 @@ template <int G, int NT>
 __device__ __forceinline__ void merge_decode_step(const KernelArgs& a, const InstanceInfo& inst, int b, int kvh) {
     typedef uint16_t T;
     constexpr int PSTRIDE = kPartialStride(D);
-    constexpr int UPC = 16;                             // units per pass
+    constexpr int UPC = 32;                             // units per pass: the default partition (up to 32 units) folds in one
     static_assert(NT / 64 >= G, "one wave per output row");
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (w >= G) return;
