@@ -194,15 +194,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
                     ak[hh][c] = *reinterpret_cast<const bf16x8*>(kt + (32 * h + 16 * hh + c16) * KSTR + 32 * c + 8 * g4);
 #pragma unroll
             for (int j = 0; j < MS; ++j) {
-                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][c], bq[j][c], s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][c], bq[j][c], s1, 0, 0, 0);
-                }
-                st[j][2 * h] = s0;
-                st[j][2 * h + 1] = s1;
+                st[j][2 * h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                st[j][2 * h + 1] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
+            // dim chunk outermost: 2 * MS independent accumulation chains are interleaved, so no
+            // matrix instruction waits for the result of the one just before it
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int j = 0; j < MS; ++j) {
+                    st[j][2 * h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[0][c], bq[j][c], st[j][2 * h], 0, 0, 0);
+                    st[j][2 * h + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[1][c], bq[j][c], st[j][2 * h + 1], 0, 0, 0);
+                }
         }
         bf16x8 pb[MS][NH];
 #pragma unroll
