@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="decode kernel shape (waves*100 + loads in flight); 0 = default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
+    ap.add_argument("--no-batch16", action="store_true", help="skip the batch-16 decode-attention leg")
     ap.add_argument("--with-others", action="store_true",
                     help="with --roofline-only: also run the other kernels' leg (few eager launches each)")
     ap.add_argument("--unfused", action="store_true",
@@ -85,6 +86,57 @@ def file_load_leg(ctx, host, dst, L, nbytes, with_fd=None):
     finally:
         if os.path.exists(path):
             os.remove(path)
+
+
+def batch16_decode_leg(reps=10, nl=8):
+    """Decode attention at BASELINE config 3's shape (batch 16, five 1000-token chunks each from a
+    pool of 200, question lengths 32..128, tails at mid-run), nl layers resident: the launch size
+    at which the kernel is bandwidth-bound rather than bound by its fixed cost per launch."""
+    import torch
+    from paper_2512_22195_amd import binding as mk
+    from workload import CONFIGS, normal, question_lengths, retrieved_chunks
+    shape = CONFIGS[3]
+    dev = torch.device("cuda:0")
+    B, Hq, Hkv, D, Hd, L = shape.batch, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.hidden, shape.chunk_tokens
+    q_lens, retrieved = question_lengths(shape), retrieved_chunks(shape)
+    chunk_ids = sorted({c for r in retrieved for c in r})
+    max_tail = (max(q_lens) + shape.decode_steps + 7) // 8 * 8
+    cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B, max_pages=shape.n_chunks,
+                         max_tail_tokens=max_tail)
+    ctx = mk.Context(cfg, device=dev)
+    cs = ctx.compute_stream
+    try:
+        with torch.cuda.stream(cs):
+            slots = {cid: normal((shape.name, "blob", cid), (nl, 2, Hkv, L, D), shape.value_scale, shape.torch_dtype, dev)
+                     for cid in chunk_ids}
+            q = normal((shape.name, "q_dec"), (nl, B, Hq, D), shape.value_scale, shape.torch_dtype, dev)
+            o = torch.empty_like(q)
+            tail = normal((shape.name, "tail"), (nl, 2, B, Hkv, max_tail, D), shape.value_scale, shape.torch_dtype, dev)
+            table = ctx.new_table()
+            ctx.assemble([[(slots[cid], L) for cid in r] for r in retrieved], q_lens, table)
+            ctx.advance(table, shape.decode_steps // 2)
+            ctx.graph_begin()
+            for l in range(nl):
+                ctx.decode_attn(l, q[l], table, tail[l, 0], tail[l, 1], o[l])
+            g = ctx.graph_end()
+            for _ in range(3):
+                ctx.graph_launch(g)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(cs)
+            for _ in range(reps):
+                ctx.graph_launch(g)
+            b.record(cs)
+            cs.synchronize()
+            ctx.graph_destroy(g)
+        us = a.elapsed_time(b) * 1e3 / (reps * nl)
+        nbytes = sum((L * len(r) + ql + shape.decode_steps // 2) * shape.kv_bytes_per_token_layer()
+                     for r, ql in zip(retrieved, q_lens)) + 2 * B * Hq * D * shape.elem_bytes
+        return {"workload": f"BASELINE config 3 shape: batch {B}, {shape.n_chunks} x {L} tokens each, {nl} layers resident "
+                            f"({len(chunk_ids)} distinct chunks)",
+                "bytes_per_launch": nbytes, "us_per_launch": round(us, 3), "GBps": round(nbytes / us / 1e3, 1),
+                "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+    finally:
+        ctx.close()
 
 
 def main():
@@ -454,6 +506,13 @@ def main():
             kv_load["from_file"] = file_load_leg(ctx, host, dst, L, nbytes)
         kv_load["pipelined_stream"] = overlap
         del host, dst
+
+    # ----------------------------------- decode attention at a bandwidth-bound launch size ---
+    if not args.roofline_only and not args.no_batch16 and shape.dtype == "bf16":
+        try:
+            roofline["decode_attn_batch16"] = batch16_decode_leg()
+        except torch.cuda.OutOfMemoryError:
+            roofline["decode_attn_batch16"] = None
 
     # ------------------------------------------------------------------------ cpu_baseline ---
     cpu = None
