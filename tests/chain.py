@@ -131,7 +131,7 @@ def load_blobs(ctx, case: Case, blobs: dict):
     return slots, keep
 
 
-def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=None):
+def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=None, proj=None):
     """Returns (prefill O [n_layers, total_q, Hq, D], decode O [steps, n_layers, B, Hq, D]) as CPU tensors."""
     c = case
     own = ctx is None
@@ -149,7 +149,24 @@ def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=Non
             o_dec = torch.full_like(q_dec, float("nan"))
             for l in range(c.n_layers):
                 ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
-            if use_graph and c.steps > 0:
+            if proj is not None and c.steps > 0:
+                # decode steps through matkv_decode_step, recorded once and replayed (the launch
+                # configuration bench.py times): the new token's K/V come from proj["x_dec"][t]
+                w, x_dec = proj["w"].to(device), proj["x_dec"].to(device)
+                q_stage, o_stage, x_stage = torch.empty_like(q_dec[0]), torch.empty_like(o_dec[0]), torch.empty_like(x_dec[0])
+                ctx.graph_begin()
+                ctx.advance(table, 1)
+                for l in range(c.n_layers):
+                    ctx.decode_step(l, x_stage[l], w[l, 0], w[l, 1], q_stage[l], table, tail[l, 0], tail[l, 1], o_stage[l])
+                g = ctx.graph_end()
+                for t in range(c.steps):
+                    q_stage.copy_(q_dec[t]); x_stage.copy_(x_dec[t])
+                    ctx.graph_launch(g)
+                    o_dec[t].copy_(o_stage)
+                    if t % 2 == 1:
+                        ctx.compute_stream.synchronize()
+                ctx.graph_destroy(g)
+            elif use_graph and c.steps > 0:
                 # one recording of a decode step (all layers), replayed for every step; q and
                 # out live in fixed staging buffers that are refreshed between replays
                 q_stage = torch.empty_like(q_dec[0])
@@ -279,9 +296,11 @@ def cu_q(case: Case):
     return cu
 
 
-def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=None, prefill_rows=None):
+def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=None, prefill_rows=None, proj=None):
     """fp64 oracle over the same generated K/V.  Returns dicts keyed by (layer) / (step, layer)
-    of arrays shaped like the GPU outputs restricted to the sampled instances."""
+    of arrays shaped like the GPU outputs restricted to the sampled instances.
+    proj: the tail rows of the decode steps are not the generated ones but the projection of
+    proj["x_dec"][t] at position (chunk tokens + question length + t), rounded to the storage type."""
     c = case
     layers = range(c.n_layers) if layers is None else layers
     steps = range(c.steps) if steps is None else steps
@@ -302,6 +321,15 @@ def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=Non
                 K, V, n_ctx = oracle.assemble(chunks, tk[:, :lq], tv[:, :lq])
                 for r in sorted({min(max(r, 0), lq - 1) for r in prefill_rows}):
                     pre[(l, b, r)] = oracle.attn(to_f64(inp["q_pre"][l, cu[b] + r])[None], K, V, n_ctx, r)
+            if proj is not None and len(list(steps)) > 0:
+                tk, tv = tk.copy(), tv.copy()
+                p0 = float(sum(c.chunk_lens[cid] for cid in c.retrieved[b]))
+                wk, wv = to_f64(proj["w"][l, 0]), to_f64(proj["w"][l, 1])
+                for t in range(max(steps) + 1):
+                    Kt, Vt = oracle.materialize(to_f64(proj["x_dec"][t, l, b])[None], wk, wv, c.Hkv, c.D,
+                                                p0 + lq + t, c.rope_base)
+                    tk[:, lq + t] = store_round(Kt, c.dtype)[:, 0]
+                    tv[:, lq + t] = store_round(Vt, c.dtype)[:, 0]
             for t in steps:
                 n = lq + t + 1
                 dec[(t, l, b)] = oracle.decode_attn(to_f64(inp["q_dec"][t, l, b]), chunks, tk[:, :n], tv[:, :n])

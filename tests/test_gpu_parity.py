@@ -297,6 +297,23 @@ def test_config2_full_size_sampled():
     assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
 
 
+def test_config2_full_size_fused_step_sampled():
+    """The launch configuration bench.py times: Llama-3-8B layer shape, 10 x 1000 cached tokens,
+    all 32 layers resident, decode steps through matkv_decode_step recorded once and replayed;
+    the new token's K/V are projected from hidden states of size 4096 inside the same launch.
+    The oracle checks layers {0, 31} at decode steps {0, 5} (all heads)."""
+    from workload import normal
+    case = chain.case_from_config(2)
+    case.steps = 6
+    inp = chain.make_attention_inputs(case)
+    proj = dict(w=normal((case.name, "w"), (case.n_layers, 2, case.Hkv * case.D, case.hidden), case.scale, case.tdtype),
+                x_dec=normal((case.name, "x_dec"), (case.steps, case.n_layers, case.batch, case.hidden), 1.0, case.tdtype))
+    o_pre, o_dec = chain.run_gpu_attention(case, inp, proj=proj)
+    pre, dec = chain.run_oracle_attention(case, inp, layers=[0, 31], steps=[0, 5], proj=proj)
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+    assert torch.isfinite(o_dec.float()).all()
+
+
 def test_config3_batch16_shared_pages_sampled():
     """Config 3 shape: batch 16, five 1000-token chunks each, drawn from a pool of 200 so that
     instances share pages, question lengths uniform in 32..128.  Two layers resident; the oracle
