@@ -1,6 +1,9 @@
-// Matrix-core attention over the assembled cache, bf16, head_dim 128: the question prefill
-// (paper Section V-A "prefill time": rows i of the question over every chunk key and question
-// keys j <= i) and, with a single row per instance, the decode step.
+// Matrix-core attention over the assembled cache with the unit's TOKENS split over the waves,
+// bf16, head_dim 128: the decode step (paper Section V-A "decode time": the newest token of
+// each instance over every chunk key and the whole tail), alone or fused with the projection of
+// that token's K/V (Section III-B steps 2-3), and - as the fallback of the row-parallel kernel in
+// attn_prefill.hip - the question prefill (rows i of the question over every chunk key and
+// question keys j <= i).
 //
 // The M dimension of the tiles is the flattened (question row, query head of one KV head)
 // index, so the G query heads that share a KV head ride in the same matrix-core operation.
