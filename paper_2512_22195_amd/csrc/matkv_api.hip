@@ -162,17 +162,22 @@ int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
 
 // Units one instance's cache is cut into for the question prefill.  The matrix-core kernel runs
 // one workgroup per (unit, KV head, 128-row tile); every extra unit costs a partial per question
-// row, so only as many as it takes to give each compute unit its two resident workgroups, and
-// none shorter than 256 tokens.  The other kernels launch a workgroup per question row and want few units.
+// row and a share of the fold launch.  So: as many units as it takes to give every compute unit
+// a workgroup (none shorter than 256 tokens), and twice that - two resident workgroups per
+// compute unit overlap each other's matrix and vector phases - only while a unit keeps at least
+// 4096 tokens to amortise its partial over.  Measured per layer: config 2 (16 workgroups
+// uncut) 33 us at 16 or 32 units; config 3 (320 uncut) 217 us uncut against 233 us in two
+// units; config 4 (256 uncut, 20 128 tokens) 569 us uncut against 432 us in two.
+// The other kernels launch a workgroup per question row and want few units.
 int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long tokens) {
-    constexpr long kTargetWorkgroups = 512;      // two resident workgroups per compute unit
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
     const bool mfma = cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && (g == 1 || g == 2 || g == 4 || g == 8);
     long pu;
     if (mfma) {
         const long wgs_per_unit = std::max<long>(1, tiles_in_batch * cfg.n_kv_heads);
-        pu = (kTargetWorkgroups + wgs_per_unit - 1) / wgs_per_unit;
-        pu = std::min<long>(pu, tokens / 256);
+        pu = (256 + wgs_per_unit - 1) / wgs_per_unit;
+        pu = std::max<long>(1, std::min<long>(pu, tokens / 256));
+        if (wgs_per_unit * pu < 512 && tokens / (2 * pu) >= 4096) pu *= 2;
     } else {
         pu = tokens / 1024;
     }
