@@ -88,6 +88,49 @@ def test_fused_decode_step_chain(batch, Hq, use_graph):
     _chain_parity(case, fused=True, use_graph=use_graph)
 
 
+def test_fused_decode_step_degenerate_caches():
+    """Single-launch decode step on degenerate caches: an instance without pages (its first
+    decode token sees only the question and itself), a one-token question, a tail that ends
+    exactly at its capacity on the last step, and a three-instance batch (a partly used group
+    of four rows per projection task)."""
+    case = Case("fused-degenerate", n_layers=1, Hq=8, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 70, 1: 9}, retrieved=[[], [0, 1], [1]], q_lens=[1, 5, 3],
+                steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0, max_tail=8)
+    assert case.tail_cap == 8 and max(case.q_lens) + case.steps == 8
+    _chain_parity(case, fused=True)
+
+
+def test_decode_step_rejects_bad_arguments():
+    from paper_2512_22195_amd import binding as mk
+    case = Case("step-args", n_layers=1, Hq=8, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 32}, retrieved=[[0]], q_lens=[4], steps=2)
+    ctx = chain.make_context(case)
+    try:
+        slot = ctx.new_slot(32)
+        table, tail = ctx.new_table(), ctx.new_tail()
+        x = torch.zeros((1, 4096), dtype=torch.bfloat16, device="cuda")
+        w = torch.zeros((2 * 128, 4096), dtype=torch.bfloat16, device="cuda")
+        q = torch.zeros((1, 8, 128), dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(mk.MatKVError) as e:      # table never assembled
+            ctx.decode_step(0, x, w, w, q, table, tail[0, 0], tail[0, 1], q)
+        assert e.value.status == mk.EINVAL
+        host = torch.zeros(mk.blob_bytes(ctx.cfg, 32), dtype=torch.uint8).pin_memory()
+        ctx.wait(ctx.load(host, 32, slot))
+        ctx.assemble([[(slot, 32)]], [4], table)
+        with pytest.raises(mk.MatKVError) as e:      # layer out of range
+            ctx.decode_step(3, x, w, w, q, table, tail[0, 0], tail[0, 1], q)
+        assert e.value.status == mk.EINVAL
+        with pytest.raises(mk.MatKVError) as e:      # misaligned hidden pointer
+            ctx.decode_step(0, x.view(-1)[1:], w, w, q, table, tail[0, 0], tail[0, 1], q)
+        assert e.value.status == mk.EINVAL
+        ctx.advance(table, 1)
+        ctx.decode_step(0, x, w, w, q, table, tail[0, 0], tail[0, 1], q)   # still works afterwards
+        ctx.compute_stream.synchronize()
+        assert torch.isfinite(q.float()).all()
+    finally:
+        ctx.close()
+
+
 def test_decode_step_other_shapes_run_two_launches():
     """Same entry point where the single-launch form does not apply (hidden 512; fp32)."""
     case = Case("step-fallback-bf16", n_layers=1, Hq=8, Hkv=2, D=128, hidden=512, dtype="bf16",
