@@ -160,6 +160,15 @@ def prefill_attn(Q, chunks, tail_k, tail_v, scale=None):
     return attn(Q, K, V, n_ctx, 0, scale)
 
 
+def chunk_attn(Q, K, V, scale=None):
+    """Self-attention of one chunk during its materialization (Section III-B, steps
+    2-3: the chunk runs through the model's prefill alone, from the first input
+    position): token i attends to the chunk's own tokens j <= i and to nothing else.
+    Q [L, Hq, D]; K, V [Hkv, L, D], all at positions 0..L-1.  Returns O [L, Hq, D]."""
+    assert np.asarray(Q).shape[0] == np.asarray(K).shape[1]
+    return attn(Q, K, V, 0, 0, scale)
+
+
 def decode_attn(q, chunks, tail_k, tail_v, scale=None):
     """One decode step: the newest token (last tail row) attends to every chunk
     token and to the whole tail including itself.  q [Hq, D] -> o [Hq, D]."""

@@ -197,6 +197,27 @@ def test_single_chunk_equals_full_causal_computation():
     np.testing.assert_allclose(O_mat, Ob[L:], atol=1e-12)
 
 
+def test_chunk_attn_is_library_causal_attention():
+    """A chunk's own prefill attention is ordinary causal attention: equal to the
+    library routine (torch CPU, fp64, KV heads repeated for the groups), its first
+    row is V[0], and a chunk's prefix gives the same rows as the whole chunk."""
+    import torch
+    import torch.nn.functional as F
+    L, Hq, Hkv, D = 13, 6, 2, 16
+    Q, K, V = rand(L, Hq, D), rand(Hkv, L, D), rand(Hkv, L, D)
+    scale = 0.21
+    O = oracle.chunk_attn(Q, K, V, scale)
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]                       # [1, Hq, L, D]
+    k = torch.from_numpy(K).repeat_interleave(Hq // Hkv, dim=0)[None]
+    v = torch.from_numpy(V).repeat_interleave(Hq // Hkv, dim=0)[None]
+    ref = F.scaled_dot_product_attention(q, k, v, is_causal=True, scale=scale)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+    for h in range(Hq):
+        np.testing.assert_allclose(O[0, h], V[h // (Hq // Hkv), 0], atol=1e-14)
+    O7 = oracle.chunk_attn(Q[:7], K[:, :7], V[:, :7], scale)
+    np.testing.assert_allclose(O7, O[:7], rtol=0, atol=1e-13)
+
+
 def test_two_chunks_differ_from_concatenated_prefill():
     """With two chunks the MatKV cache is NOT the vanilla one: the second chunk
     restarts at position 0 (Section III-B), so keys differ from the concatenation."""
