@@ -356,6 +356,16 @@ def main():
             for l in range(nl):
                 ctx.materialize(x_chunk, w[l, 0], w[l, 1], L, 0, blob[l, 0], blob[l, 1], L)
             b.record(cs)
+            # the chunk's own causal attention over the K/V just materialized (ingest time too)
+            q_chunk = normal((shape.name, "q_chunk"), (L, Hq, D), vs, tdt, dev)
+            o_chunk = torch.empty_like(q_chunk)
+            for l in range(min(nl, 4)):
+                ctx.chunk_attn(l, q_chunk, blob, L, o_chunk)
+            h0, h1 = ev(), ev()
+            h0.record(cs)
+            for l in range(nl):
+                ctx.chunk_attn(l, q_chunk, blob, L, o_chunk)
+            h1.record(cs)
             # question prefill attention alone
             ctx.assemble(pages, q_lens, table)
             for l in range(min(nl, 4)):
@@ -386,6 +396,8 @@ def main():
         us_pre = c.elapsed_time(d) * 1e3 / nl
         us_gemv = e.elapsed_time(f) * 1e3 / nl
         us_matq = g0.elapsed_time(g1) * 1e3 / nl
+        us_chunk = h0.elapsed_time(h1) * 1e3 / nl
+        fl_chunk = 4.0 * D * Hq * L * (L + 1) / 2
         fl_matq = 2.0 * total_q * Hd * 2 * Hkv * D
         fl_mat = 2.0 * L * Hd * 2 * Hkv * D
         fl_pre = sum(4.0 * q * (n + (q + 1) / 2) * D * Hq for q, n in zip(q_lens, n_ctx))
@@ -394,6 +406,8 @@ def main():
         other = {
             "materialize_chunk": {"tokens": L, "us_per_layer": round(us_mat, 2), "TFLOPs": round(fl_mat / us_mat / 1e6, 1),
                                   "frac_of_mfma_peak": round(fl_mat / us_mat / 1e6 / mfma_peak, 4)},
+            "chunk_attn": {"tokens": L, "us_per_layer": round(us_chunk, 2), "TFLOPs": round(fl_chunk / us_chunk / 1e6, 1),
+                           "frac_of_mfma_peak": round(fl_chunk / us_chunk / 1e6 / mfma_peak, 4)},
             "materialize_question": {"rows": total_q, "us_per_layer": round(us_matq, 2), "TFLOPs": round(fl_matq / us_matq / 1e6, 1),
                                      "frac_of_mfma_peak": round(fl_matq / us_matq / 1e6 / mfma_peak, 4)},
             "prefill_attn": {"us_per_layer": round(us_pre, 2), "TFLOPs": round(fl_pre / us_pre / 1e6, 1),
@@ -401,7 +415,7 @@ def main():
             "materialize_decode_token": {"us_per_layer": round(us_gemv, 2), "GBps": round(by_gemv / us_gemv / 1e3, 1),
                                          "frac_of_hbm_peak": round(by_gemv / us_gemv / 1e3 / HBM_PEAK_GBPS, 4)},
         }
-        del x_chunk, blob
+        del x_chunk, blob, q_chunk, o_chunk
 
     if args.calib_copy:
         with torch.cuda.stream(cs):

@@ -8,6 +8,7 @@
  * own KVs.  This library is that path and nothing else:
  *
  *   matkv_materialize       K = RoPE(X Wk^T), V = X Wv^T of one layer   (III-B steps 1-3)
+ *   matkv_chunk_attn        a chunk's own causal attention while it is materialized (III-B step 2)
  *   matkv_load              pinned-host KV blob -> HBM slot, side stream (IV, load_KV)
  *   matkv_load_file         the same from a file, through pinned bounce buffers (IV, load_KV)
  *   matkv_store_file        device blob -> file, through the same buffers       (IV, store_KV)
@@ -131,6 +132,20 @@ const char* matkv_last_error(const matkv_ctx* ctx);
 matkv_status matkv_materialize(matkv_ctx* ctx, const void* hidden, const void* w_k,
                                const void* w_v, int32_t n_tokens, int64_t pos0,
                                void* k_out, void* v_out, int64_t token_stride);
+
+/* The attention a chunk performs on itself while it is materialized (Section III-B: the chunk
+ * runs through the model's prefill alone, starting at the first input position): row i, head h
+ * (KV head h / (Hq/Hkv)) = softmax over the chunk's own tokens j <= i of scale * q.k, times V.
+ * Together with matkv_materialize this is the part of a chunk's forward pass that reads and
+ * writes K/V; the rest of the layer (norms, output projection, MLP) is the caller's.
+ * q, out: device [n_tokens][Hq][D], q already rotated to positions 0..n_tokens-1.  blob: device
+ * blob of n_tokens tokens whose `layer` section matkv_materialize has written (same stream, or
+ * ordered before this call).  Runs on the compute stream; capturable.  n_tokens = 0 is a no-op;
+ * at most 65535.  Shapes outside the matrix-core kernel (fp32, head_dim 64) keep one partial
+ * result per (row, head) in the workspace: MATKV_ENOMEM when the chunk has more rows than the
+ * configuration's workspace covers (max_batch * max_tail_tokens). */
+matkv_status matkv_chunk_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* blob,
+                              int32_t n_tokens, void* out);
 
 /* The same projection for the newest tail rows of every instance of a cache table
  * (question tokens at prefill, the generated token at each decode step); where rows go

@@ -23,7 +23,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "matkv_blob_bytes", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
     "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
-    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_load", "matkv_load_file", "matkv_store_file",
+    "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_chunk_attn", "matkv_load", "matkv_load_file", "matkv_store_file",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
@@ -91,6 +91,8 @@ def _load_library():
     for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
         fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         fn.restype = c_int32
+    lib.matkv_chunk_attn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32, c_void_p]
+    lib.matkv_chunk_attn.restype = c_int32
     lib.matkv_decode_step.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
     lib.matkv_decode_step.restype = c_int32
     lib.matkv_plan_decode_units.argtypes = [cfgp, POINTER(c_int32), c_int32, c_int32, c_int32,
@@ -273,6 +275,9 @@ class Context:
 
     def advance(self, table, n=1):
         self._check(_lib.matkv_advance(self._h, _ptr(table), n), "matkv_advance")
+
+    def chunk_attn(self, layer, q, blob, n_tokens, out):
+        self._check(_lib.matkv_chunk_attn(self._h, layer, _ptr(q), _ptr(blob), n_tokens, _ptr(out)), "matkv_chunk_attn")
 
     def prefill_attn(self, layer, q, table, tail_k, tail_v, out):
         self._check(_lib.matkv_prefill_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int kvh = blockIdx.y, tile = blockIdx.z;
+    // a chunk's own attention: tile t walks (t + 1) * RT / G keys, so the longest go first
+    const int kvh = blockIdx.y, tile = a.prefill == 2 ? gridDim.z - 1 - blockIdx.z : blockIdx.z;
     const int m0 = tile * RT;
 
     const Unit unit = units[blockIdx.x];
@@ -66,6 +67,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     if (m0 >= n_m) return;                              // whole workgroup leaves together
     const int r_last = (min(m0 + RT, n_m) - 1) / G;
     const bool wave_live = m0 + WR * wave < n_m;        // this wave has at least one real row
+    const int vis_min = (m0 + WR * wave) / G + 1;       // tail rows every row of this wave may see
 
     // Q in operand layout; padding rows repeat the last real row
     bf16x8 bq[MS][4];
@@ -176,10 +178,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
 
-    // masked: the block is ragged or lies in the tail (per-row causal limit); otherwise all TB
-    // rows are visible to every question row and no element needs a test.
+    // masked: the block is ragged, or lies in the tail and reaches past what the wave's first
+    // row may see (per-row causal limit); otherwise all TB rows are visible to every question
+    // row of the wave and no element needs a test.
     auto compute = [&](const BlockRef<T>& r, int buf) {
-        const bool masked = r.is_tail || r.tok_end - r.t0 != TB;
+        const bool masked = r.tok_end - r.t0 != TB || (r.is_tail && r.tok_end > vis_min);
         const uint16_t* kt = tiles + buf * TILE_ELEMS;
         const uint16_t* vt = kt + TB * KSTR;
         // S^T in 16-token quarters q: lane holds tokens t0 + 16q + 4*g4 + i of its row
@@ -404,6 +407,10 @@ hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
     if (a.rows * G <= 64) return launch_v<G, 1, 64>(a, s);
+    // A chunk's own attention has one workgroup per (row tile, KV head) and the last tile walks
+    // the whole chunk: until 128-row tiles give every compute unit two workgroups, 64-row
+    // tiles do (1024 tokens, 8 KV heads: 31 us against 36 us; 4096 tokens: 269 against 210).
+    if (a.prefill == 2 && (long)((a.rows * G + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64>(a, s);
     return launch_v<G, 2, 64>(a, s);
 }
 

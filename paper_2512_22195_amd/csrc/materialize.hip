@@ -280,6 +280,30 @@ hipError_t launch_probe_read(const void* src, size_t bytes, unsigned* sink, hipS
     return hipGetLastError();
 }
 
+// One instance, no pages, a "tail" of n_tokens rows all of which are question rows; one unit
+// whose single item is that tail.  Written by one thread: the three records are 160 bytes.
+__global__ void chunk_table_kernel(char* table, int n_tokens) {
+    if (threadIdx.x != 0) return;
+    InstanceInfo in;
+    in.pos_base = 0; in.tail_len = n_tokens; in.q_len = n_tokens; in.cu_q = 0;
+    in.dunit0 = 0; in.n_dunits = 0; in.punit0 = 0; in.n_punits = 1;
+    in.pad[0] = in.pad[1] = in.pad[2] = 0;
+    Item it;
+    it.base = 0; it.page_tokens = n_tokens; it.tok0 = 0; it.ntok = n_tokens;
+    it.pad[0] = it.pad[1] = it.pad[2] = 0;
+    Unit un;
+    un.inst = 0; un.item0 = 0; un.n_items = 1; un.idx_in_inst = 0; un.n_units_inst = 1;
+    un.unit0_inst = 0; un.has_tail = 1; un.page_tokens = 0; un.first = it;
+    *reinterpret_cast<InstanceInfo*>(table + kChunkOffInst) = in;
+    *reinterpret_cast<Item*>(table + kChunkOffItem) = it;
+    *reinterpret_cast<Unit*>(table + kChunkOffUnit) = un;
+}
+
+hipError_t launch_chunk_table(char* table, int n_tokens, hipStream_t s) {
+    hipLaunchKernelGGL(chunk_table_kernel, dim3(1), dim3(64), 0, s, table, n_tokens);
+    return hipGetLastError();
+}
+
 hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s) {
     hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(64), 0, s, table, off_inst, batch, n, max_tail);
     return hipGetLastError();

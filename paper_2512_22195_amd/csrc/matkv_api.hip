@@ -917,6 +917,45 @@ matkv_status matkv_decode_step(matkv_ctx* c, int32_t layer, const void* hidden, 
     return MATKV_OK;
 }
 
+matkv_status matkv_chunk_attn(matkv_ctx* c, int32_t layer, const void* q, const void* blob, int32_t n_tokens, void* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!q || !blob || !out) return fail(c, MATKV_EINVAL, "chunk_attn: null pointer");
+    if (!aligned16(q) || !aligned16(blob) || !aligned16(out)) return fail(c, MATKV_EINVAL, "chunk_attn: pointers must be 16-byte aligned");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MATKV_EINVAL, "chunk_attn: layer %d outside 0..%d", layer, c->cfg.n_layers - 1);
+    if (n_tokens < 0 || n_tokens > 65535) return fail(c, MATKV_EINVAL, "chunk_attn: n_tokens=%d outside 0..65535", n_tokens);
+    if (n_tokens == 0) return MATKV_OK;
+    const matkv_config& cfg = c->cfg;
+    const size_t head_bytes = (size_t)n_tokens * cfg.head_dim * elem_bytes(cfg);
+    const char* k_layer = static_cast<const char*>(blob) + (size_t)layer * 2 * cfg.n_kv_heads * head_bytes;
+    AttnArgs a{};
+    a.q = q; a.out = out;
+    a.tail_k = k_layer; a.tail_v = k_layer + (size_t)cfg.n_kv_heads * head_bytes;
+    a.table = c->workspace + c->wl.off_chunk;
+    a.off_inst = kChunkOffInst; a.off_items = kChunkOffItem; a.off_units = kChunkOffUnit;
+    a.partials = reinterpret_cast<float*>(c->workspace + c->wl.off_partials);
+    a.counters = reinterpret_cast<int32_t*>(c->workspace + c->wl.off_counters);
+    a.layer = 0; a.n_layers = cfg.n_layers;      // the layer is in the pointers: the kernels see a tail, not a blob
+    a.Hq = cfg.n_q_heads; a.Hkv = cfg.n_kv_heads; a.D = cfg.head_dim;
+    a.max_tail = n_tokens;
+    a.prefill = 2; a.rows = n_tokens; a.n_units = 1; a.max_units_inst = 1;
+    a.batch = 1; a.total_q = n_tokens; a.max_unit_items = 1;
+    a.scale_log2e = c->scale_log2e;
+    const bool tiles = attn_prefill_supported(a, cfg.dtype);
+    if (!tiles) {
+        // the row-per-workgroup kernel leaves a partial and a counter per (row, head) in the workspace
+        const size_t need_f = (size_t)n_tokens * cfg.n_q_heads * (cfg.head_dim + 4);
+        const size_t need_c = (size_t)n_tokens * cfg.n_kv_heads;
+        if (need_f > c->wl.partial_floats || need_c > c->wl.n_counters)
+            return fail(c, MATKV_ENOMEM, "chunk_attn: the workspace of this configuration holds the partial results of %zu rows, the chunk has %d",
+                        std::min(c->wl.partial_floats / ((size_t)cfg.n_q_heads * (cfg.head_dim + 4)), c->wl.n_counters / cfg.n_kv_heads), n_tokens);
+    }
+    HIP_TRY(c, launch_chunk_table(c->workspace + c->wl.off_chunk, n_tokens, c->compute));
+    if (tiles) HIP_TRY(c, launch_attn_prefill(a, cfg.dtype, c->compute));
+    else HIP_TRY(c, launch_attn_rows(a, cfg.dtype, c->compute));
+    return MATKV_OK;
+}
+
 matkv_status matkv_probe_read(matkv_ctx* c, const void* src, size_t bytes) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;

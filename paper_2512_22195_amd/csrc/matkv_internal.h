@@ -80,10 +80,14 @@ inline TableLayout table_layout(const matkv_config& c) {
     return L;
 }
 
+// The one-instance table of a chunk's own prefill attention (matkv_chunk_attn): the chunk is
+// an instance without pages whose "tail" is the chunk's K/V of one layer inside its blob.
+constexpr size_t kChunkOffInst = 0, kChunkOffItem = 64, kChunkOffUnit = 128, kChunkTableBytes = 256;
+
 // ---------------------------------------------------------------- workspace (device) ------
-// [ rope table | counters | partials ]
+// [ rope table | chunk table | counters | partials ]
 struct WorkspaceLayout {
-    size_t off_rope, off_counters, off_partials, bytes;
+    size_t off_rope, off_chunk, off_counters, off_partials, bytes;
     size_t n_counters, partial_floats;
 };
 
@@ -93,6 +97,7 @@ inline WorkspaceLayout workspace_layout(const matkv_config& c) {
     WorkspaceLayout W;
     size_t o = 0;
     W.off_rope = o;      o += 4096;   // D/2 entries of {double inv_freq; float hi, lo (turns)}
+    W.off_chunk = o;     o += kChunkTableBytes;
     W.off_counters = o;
     W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)max_q_rows(c);
     o += ((W.n_counters * sizeof(int32_t)) + 255) & ~(size_t)255;
@@ -129,7 +134,8 @@ struct AttnArgs {
     int32_t max_units_inst;    // most units any one instance is cut into
     int32_t batch, total_q;    // instances; rows of the packed Q / O tensors (prefill)
     int32_t max_unit_items;    // most items in any one unit of this launch
-    int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail
+    int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail;
+                               // 2: as 1 for a chunk's own attention (longest row tiles first)
     float scale_log2e;
     int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
                                // waves * 100 + loads in flight = plain-ALU kernel
@@ -175,5 +181,6 @@ bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtyp
 hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int dtype, hipStream_t s);   // projection + attention
 hipError_t launch_probe_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s);
 hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s);
+hipError_t launch_chunk_table(char* table, int n_tokens, hipStream_t s);
 
 }  // namespace matkv

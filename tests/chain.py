@@ -108,6 +108,14 @@ def make_chain_inputs(case: Case):
     return dict(w=w, x_chunk=x_chunk, x_q=x_q, x_dec=x_dec, q_pre=q_pre, q_dec=q_dec)
 
 
+def make_chunk_queries(case: Case):
+    """Queries of the chunks' own tokens (already rotated), for the materialization pass."""
+    c = case
+    qs = c.q_scale if c.q_scale is not None else c.scale
+    return {cid: normal((c.name, "q_chunk", cid), (c.n_layers, n, c.Hq, c.D), qs, c.tdtype)
+            for cid, n in c.chunk_lens.items()}
+
+
 # ------------------------------------------------------------------------------ GPU side ---
 def make_context(case: Case, device="cuda:0"):
     from paper_2512_22195_amd import binding as mk
@@ -289,6 +297,61 @@ def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False
 
 
 # --------------------------------------------------------------------------- oracle side ---
+def run_gpu_chunk_prefill(case: Case, inp, q_chunk, device="cuda:0"):
+    """Materialization pass of every chunk: per layer, K/V of the chunk's hidden states into its
+    blob (matkv_materialize), then the chunk's own causal attention over that section
+    (matkv_chunk_attn).  Returns (blobs, outputs) as CPU tensors keyed by chunk id."""
+    c = case
+    ctx = make_context(c, device)
+    try:
+        blobs, outs = {}, {}
+        with torch.cuda.stream(ctx.compute_stream):
+            w = inp["w"].to(device)
+            for cid, n in c.chunk_lens.items():
+                x, q = inp["x_chunk"][cid].to(device), q_chunk[cid].to(device)
+                blob = torch.zeros((c.n_layers, 2, c.Hkv, n, c.D), dtype=c.tdtype, device=device)
+                o = torch.full_like(q, float("nan"))
+                for l in range(c.n_layers):
+                    ctx.materialize(x[l], w[l, 0], w[l, 1], n, 0, blob[l, 0], blob[l, 1], n)
+                    ctx.chunk_attn(l, q[l], blob, n, o[l])
+                ctx.compute_stream.synchronize()
+                blobs[cid], outs[cid] = blob.cpu(), o.cpu()
+        return blobs, outs
+    finally:
+        ctx.close()
+
+
+def run_oracle_chunk_prefill(case: Case, inp, q_chunk):
+    """fp64: K/V of the chunk at positions 0.., rounded once to the storage type, then causal
+    attention of the chunk over itself.  Returns {(cid, layer): O [n, Hq, D]}."""
+    c = case
+    ref = {}
+    for cid, n in c.chunk_lens.items():
+        for l in range(c.n_layers):
+            K, V = oracle.materialize(to_f64(inp["x_chunk"][cid][l]), to_f64(inp["w"][l, 0]),
+                                      to_f64(inp["w"][l, 1]), c.Hkv, c.D, 0.0, c.rope_base)
+            ref[(cid, l)] = oracle.chunk_attn(to_f64(q_chunk[cid][l]), store_round(K, c.dtype),
+                                              store_round(V, c.dtype))
+    return ref
+
+
+def compare_chunk_prefill(case: Case, outs, ref):
+    atol, rtol = tolerances(case.dtype)
+    worst = 0.0
+    for (cid, l), r in ref.items():
+        got = to_f64(outs[cid][l])
+        assert np.isfinite(got).all(), f"chunk {cid} layer {l}: non-finite output"
+        err = np.abs(got - r)
+        # the relative gate is per row: the first rows average a handful of values and are an
+        # order of magnitude larger than rows that average hundreds
+        rms = np.sqrt((r ** 2).mean(axis=(1, 2), keepdims=True))
+        assert err.max() <= atol, f"chunk {cid} layer {l}: max abs {err.max():.3e} > {atol}"
+        bad = err > rtol * rms + store_slack(case.dtype, r)
+        assert not bad.any(), f"chunk {cid} layer {l}: max abs {err.max():.3e} at rows {np.unique(np.nonzero(bad)[0])[:8]}"
+        worst = max(worst, err.max())
+    return worst
+
+
 def cu_q(case: Case):
     cu = [0]
     for n in case.q_lens:

@@ -601,3 +601,91 @@ def test_assemble_refuses_pages_still_loading():
         assert ctx.query(tickets[-1])
     finally:
         ctx.close()
+
+
+# ------------------------------------------------- a chunk's own prefill attention (store side)
+@pytest.mark.parametrize("name,Hq,Hkv,D,dtype,lens,max_tail", [
+    ("chunk-g4", 8, 2, 128, "bf16", [1, 37, 64, 200, 1024], None),   # one row; ragged; one block; several tiles
+    ("chunk-g1", 2, 2, 128, "bf16", [130], None),
+    ("chunk-g2", 4, 2, 128, "bf16", [100, 129], None),
+    ("chunk-g8", 8, 1, 128, "bf16", [77, 300], None),
+    ("chunk-f32", 4, 2, 64, "f32", [50, 9], 56),                      # row-per-workgroup kernel
+    ("chunk-bf16-d64", 4, 1, 64, "bf16", [40], 40),
+])
+def test_chunk_prefill_attention(name, Hq, Hkv, D, dtype, lens, max_tail):
+    """Materialization pass (Section III-B): K/V of a chunk's hidden states, then the chunk's
+    causal attention over its own K/V, against the oracle's chain."""
+    case = Case(name, n_layers=2, Hq=Hq, Hkv=Hkv, D=D, hidden=256, dtype=dtype,
+                chunk_lens=dict(enumerate(lens)), retrieved=[[0]], q_lens=[1], steps=0,
+                scale=1.0 / 4.0, q_scale=1.0, max_tail=max_tail)
+    inp = chain.make_chain_inputs(case)
+    q_chunk = chain.make_chunk_queries(case)
+    blobs, outs = chain.run_gpu_chunk_prefill(case, inp, q_chunk)
+    ref = chain.run_oracle_chunk_prefill(case, inp, q_chunk)
+    worst = chain.compare_chunk_prefill(case, outs, ref)
+    print(f"{name}: worst abs err {worst:.3e}")
+
+
+def test_chunk_attn_arguments_and_workspace_limit():
+    from paper_2512_22195_amd import binding as mk
+    case = Case("chunk-args", n_layers=1, Hq=4, Hkv=2, D=64, hidden=128, dtype="f32",
+                chunk_lens={0: 64}, retrieved=[[0]], q_lens=[1], steps=0, max_tail=16)
+    ctx = chain.make_context(case)
+    try:
+        blob = torch.zeros((1, 2, 2, 64, 64), dtype=torch.float32, device="cuda")
+        q = torch.zeros((64, 4, 64), dtype=torch.float32, device="cuda")
+        o = torch.full_like(q, 7.0)
+        ctx.chunk_attn(0, q, blob, 0, o)                       # no rows: nothing is written
+        ctx.compute_stream.synchronize()
+        assert (o == 7.0).all()
+        with pytest.raises(mk.MatKVError) as e:
+            ctx.chunk_attn(1, q, blob, 8, o)
+        assert e.value.status == mk.EINVAL
+        with pytest.raises(mk.MatKVError) as e:
+            ctx.chunk_attn(0, q.view(-1)[1:], blob, 8, o)
+        assert e.value.status == mk.EINVAL
+        with pytest.raises(mk.MatKVError) as e:                # 64 rows, workspace sized for 16
+            ctx.chunk_attn(0, q, blob, 64, o)
+        assert e.value.status == mk.ENOMEM
+        ctx.chunk_attn(0, q, blob[:, :, :, :16].contiguous(), 16, o)     # zero scores: mean of zero V
+        ctx.compute_stream.synchronize()
+        assert (o[:16] == 0).all() and (o[16:] == 7.0).all()
+    finally:
+        ctx.close()
+
+
+@pytest.mark.parametrize("L,Hq,Hkv,rows", [
+    (1000, 32, 8, None),                                       # config 2's chunk, every row
+    (4096, 32, 8, [0, 1, 31, 32, 63, 64, 127, 128, 2047, 2048, 4000, 4095]),
+    (1000, 64, 8, [0, 15, 16, 17, 500, 999]),                  # config 4's heads (group 8)
+])
+def test_full_size_chunk_attention(L, Hq, Hkv, rows):
+    """A chunk's own attention at the shapes bench.py times (Llama-3-8B / 70B heads, D 128):
+    K/V drawn directly into a two-layer blob, layer 1 checked.  rows: the rows the oracle
+    computes one by one (None = the whole chunk)."""
+    from workload import normal, to_f64
+    import oracle
+    name = f"chunk-full-{L}-{Hq}"
+    case = Case(name, n_layers=2, Hq=Hq, Hkv=Hkv, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: L}, retrieved=[[0]], q_lens=[1], steps=0)
+    blob = normal((name, "blob"), (2, 2, Hkv, L, 128), 1.0, torch.bfloat16)
+    q = normal((name, "q"), (L, Hq, 128), 1.0, torch.bfloat16)
+    ctx = chain.make_context(case)
+    try:
+        with torch.cuda.stream(ctx.compute_stream):
+            o = torch.full((L, Hq, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ctx.chunk_attn(1, q.cuda(), blob.cuda(), L, o)
+            ctx.compute_stream.synchronize()
+        got = o.cpu()
+    finally:
+        ctx.close()
+    assert torch.isfinite(got.float()).all()
+    K, V = to_f64(blob[1, 0]), to_f64(blob[1, 1])
+    if rows is None:
+        ref = {(0, 0): oracle.chunk_attn(to_f64(q), K, V)}
+        outs = {0: got[None]}
+    else:
+        # row r alone: keys 0..r, the causal limit starting at row r
+        ref = {(i, 0): oracle.attn(to_f64(q[r:r + 1]), K[:, :r + 1], V[:, :r + 1], 0, r) for i, r in enumerate(rows)}
+        outs = {i: got[None, r:r + 1] for i, r in enumerate(rows)}
+    chain.compare_chunk_prefill(case, outs, ref)
