@@ -176,3 +176,61 @@ def decode_attn(q, chunks, tail_k, tail_v, scale=None):
     t_tail = np.asarray(tail_k).shape[1]
     o = attn(np.asarray(q)[None], K, V, n_ctx, t_tail - 1, scale)
     return o[0]
+
+
+# ------------------------------------------------------------------ compressed KV blobs ----
+# The paper names KV compression as the lever on storage cost and load time (Section III-C,
+# "Discussion"; related work on KV-size reduction) without fixing a scheme.  The scheme here is
+# the simplest one a loader can undo for free: 8-bit floating point codes (OCP FP8 E4M3, the
+# "fn" variant: no infinities, S.1111.111 is NaN, largest finite value 448) with one
+# power-of-two scale per (layer, K or V, KV head).
+
+def e4m3_decode(codes):
+    """Value of every E4M3 code, by the format's definition: 1 sign, 4 exponent (bias 7),
+    3 mantissa bits; exponent 0 = subnormal m/8 * 2^-6; S.1111.111 = NaN."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c >> 7, -1.0, 1.0)
+    e, m = (c >> 3) & 15, c & 7
+    val = np.where(e == 0, (m / 8.0) * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    val = np.where((e == 15) & (m == 7), np.nan, val)
+    return sign * val
+
+
+def e4m3_encode(y):
+    """Nearest E4M3 code of every element, ties to the even mantissa, magnitudes beyond 448
+    saturate to 448.  Below 2^-6 the codes step by 2^-9 (subnormals)."""
+    y = _f64(y)
+    a = np.minimum(np.abs(y), 448.0)
+    sub = a < 2.0 ** -6
+    q_sub = np.rint(a * 2.0 ** 9)                       # 0..8; 8 is the first normal code
+    an = np.where(sub, 1.0, a)                          # keep log2 away from 0
+    e = np.floor(np.log2(an))
+    q = np.rint((an / np.exp2(e) - 1.0) * 8.0)          # numpy rounds halves to even
+    e = np.where(q == 8, e + 1, e)
+    q = np.where(q == 8, 0, q)
+    code = np.where(sub, q_sub, (e + 7) * 8 + q).astype(np.int64)
+    code = np.minimum(code, 0x7E)
+    return (code | np.where(np.signbit(y), 0x80, 0)).astype(np.uint8)
+
+
+def kv_scale(amax):
+    """Smallest power of two s with amax <= 448 s (1 when amax is 0)."""
+    amax = _f64(amax)
+    m, e = np.frexp(np.where(amax > 0, amax, 1.0))      # amax = m 2^e, m in [0.5, 1)
+    k = np.where(2.0 * m <= 1.75, e - 1 - 8, e - 1 - 7)
+    return np.where(amax > 0, np.exp2(k.astype(np.float64)), 1.0)
+
+
+def compress(K, V):
+    """K, V [Hkv, L, D] (the stored values) -> codes [2, Hkv, L, D] uint8 and power-of-two
+    scales [2, Hkv]: code = e4m3(x / scale of its head), scale from the head's largest
+    magnitude over all tokens and dims."""
+    X = np.stack([_f64(K), _f64(V)])
+    scales = kv_scale(np.abs(X).max(axis=(2, 3)))
+    return e4m3_encode(X / scales[:, :, None, None]), scales
+
+
+def decompress(codes, scales):
+    """What a reader of a compressed blob sees: value(code) * scale.  Returns K, V."""
+    X = e4m3_decode(codes) * _f64(scales)[:, :, None, None]
+    return X[0], X[1]

@@ -332,3 +332,65 @@ def test_store_round_bf16_is_round_to_nearest_even():
     assert (np.abs(r - a) <= 2.0 ** -8 * np.abs(a)).all()    # half an ulp: unit roundoff 2^-8
     assert ((r.view(np.uint64) & np.uint64((1 << 45) - 1)) == 0).all()           # 7 mantissa bits
     np.testing.assert_array_equal(store_round(a, "f32"), a.astype(np.float32).astype(np.float64))
+
+
+# --------------------------------------------------------------------------- compressed blobs
+def test_e4m3_matches_library_cast_and_closed_forms():
+    """The 8-bit code of the compressed blobs against the library's cast (torch CPU,
+    float8_e4m3fn) on every code, on a dense grid with all midpoints, and on random values;
+    plus the values the format fixes."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib_vals = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    mine = oracle.e4m3_decode(codes)
+    assert np.array_equal(np.isnan(mine), np.isnan(lib_vals)) and np.isnan(mine).sum() == 2
+    ok = ~np.isnan(mine)
+    assert np.array_equal(mine[ok], lib_vals[ok])
+    # the format's fixed points
+    assert oracle.e4m3_decode([0x7E])[0] == 448.0 and oracle.e4m3_decode([0x01])[0] == 2.0 ** -9
+    assert oracle.e4m3_decode([0x38])[0] == 1.0 and oracle.e4m3_decode([0x08])[0] == 2.0 ** -6
+    assert np.array_equal(oracle.e4m3_encode(mine[ok]), codes[ok])          # every value is its own nearest
+    # ties go to the even mantissa; beyond the largest value the code saturates
+    assert oracle.e4m3_encode([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10, 1e4, -1e4]).tolist() == \
+        [0x38, 0x3A, 0x00, 0x02, 0x7E, 0xFE]
+    # every representable value, every midpoint between neighbours, and a step either side
+    pos = np.sort(mine[ok & (codes < 0x80)])
+    mids = (pos[1:] + pos[:-1]) / 2
+    grid = np.concatenate([pos, mids, mids * (1 + 2.0 ** -20), mids * (1 - 2.0 ** -20), RNG.uniform(0, 448, 4000)])
+    grid = np.concatenate([grid, -grid]).astype(np.float32)                 # all exactly fp32
+    lib = torch.from_numpy(grid).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = oracle.e4m3_encode(grid)
+    zero = grid == 0                                                         # the sign of zero is the input's
+    assert np.array_equal(got[~zero], lib[~zero])
+    # rounding error: half a step, i.e. 2^-4 relative for normals, 2^-10 absolute below 2^-6
+    back = oracle.e4m3_decode(got)
+    assert (np.abs(back - grid) <= np.maximum(2.0 ** -4 * np.abs(grid), 2.0 ** -10) * (1 + 1e-12)).all()
+
+
+def test_kv_scale_and_compress_roundtrip():
+    """Scale rule: the smallest power of two that brings the head's largest magnitude to at
+    most 448 (so it lands in (224, 448]); exact powers of two and the 1.75 boundary; a blob of
+    representable values survives compress -> decompress unchanged."""
+    amax = np.array([0.0, 448.0, 448.0001, 224.0, 224.0001, 1.0, 3.5, 3.50001, 1e-3, 7e4])
+    s = oracle.kv_scale(amax)
+    assert s[0] == 1.0
+    nz = amax > 0
+    assert (np.log2(s[nz]) == np.round(np.log2(s[nz]))).all()
+    r = amax[nz] / s[nz]
+    assert (r <= 448.0).all() and (r > 224.0).all()
+    assert s[1] == 1.0 and s[2] == 2.0 and s[3] == 0.5 and s[4] == 1.0 and s[6] == 2.0 ** -7 and s[7] == 2.0 ** -6
+    Hkv, L, D = 3, 11, 8
+    K, V = rand(Hkv, L, D, s=5.0), rand(Hkv, L, D, s=0.01)
+    codes, scales = oracle.compress(K, V)
+    assert codes.shape == (2, Hkv, L, D) and codes.dtype == np.uint8 and scales.shape == (2, Hkv)
+    Kd, Vd = oracle.decompress(codes, scales)
+    for X, Xd, sc in ((K, Kd, scales[0]), (V, Vd, scales[1])):
+        amax_h = np.abs(X).max(axis=(1, 2))
+        assert (amax_h / sc <= 448).all() and (amax_h / sc > 224).all()
+        # half a step of the head's grid: 2^-4 relative, or half a subnormal step of the scaled grid
+        assert (np.abs(Xd - X) <= np.maximum(2.0 ** -4 * np.abs(X), 2.0 ** -10 * sc[:, None, None]) * (1 + 1e-12)).all()
+    Kd2, Vd2 = oracle.decompress(*oracle.compress(Kd, Vd))                   # already on a grid: kept exactly
+    assert np.array_equal(Kd2, Kd) and np.array_equal(Vd2, Vd)              # (the scale may halve, the values stay)
+    # a head of zeros keeps scale 1 and code 0
+    c0, s0 = oracle.compress(np.zeros((1, 2, 4)), np.zeros((1, 2, 4)))
+    assert (c0 == 0).all() and (s0 == 1.0).all()
