@@ -9,6 +9,7 @@
  *
  *   matkv_materialize       K = RoPE(X Wk^T), V = X Wv^T of one layer   (III-B steps 1-3)
  *   matkv_chunk_attn        a chunk's own causal attention while it is materialized (III-B step 2)
+ *   matkv_compress          blob -> E4M3 codes + per-head power-of-two scales (III-C, compression)
  *   matkv_load              pinned-host KV blob -> HBM slot, side stream (IV, load_KV)
  *   matkv_load_file         the same from a file, through pinned bounce buffers (IV, load_KV)
  *   matkv_store_file        device blob -> file, through the same buffers       (IV, store_KV)
@@ -89,8 +90,13 @@ typedef struct {
 typedef struct {
     const void* slot;
     int32_t n_tokens;
-    int32_t reserved;
+    int32_t format;           /* matkv_page_format of the blob in the slot */
 } matkv_page;
+
+/* A slot holds either the blob as matkv_materialize writes it, or its compressed form
+ * (matkv_compress): one E4M3 byte per element and one power-of-two scale per
+ * (layer, K or V, KV head).  The pages of one cache table share one format. */
+typedef enum { MATKV_PAGE_PLAIN = 0, MATKV_PAGE_E4M3 = 1 } matkv_page_format;
 
 typedef struct { uint64_t id; } matkv_ticket;
 
@@ -98,6 +104,10 @@ typedef struct { uint64_t id; } matkv_ticket;
 
 /* Bytes of one chunk blob: n_layers * 2 * Hkv * n_tokens * D * s.  0 on a bad config. */
 size_t matkv_blob_bytes(const matkv_config* cfg, int32_t n_tokens);
+/* Bytes of the compressed form of a chunk blob (matkv_compress): the codes
+ * [n_layers][2][Hkv][n_tokens][D], one byte each, padded to 16 bytes; then the scales
+ * [n_layers][2][Hkv] as float, padded to 16 bytes.  0 on a bad config. */
+size_t matkv_compressed_blob_bytes(const matkv_config* cfg, int32_t n_tokens);
 /* Bytes of one layer's tail buffer (K or V): max_batch * Hkv * max_tail_tokens * D * s. */
 size_t matkv_tail_bytes(const matkv_config* cfg);
 /* Device bytes the caller must provide as workspace (split partials and counters). */
@@ -147,6 +157,18 @@ matkv_status matkv_materialize(matkv_ctx* ctx, const void* hidden, const void* w
 matkv_status matkv_chunk_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* blob,
                               int32_t n_tokens, void* out);
 
+/* Compressed form of a materialized chunk (the paper leaves KV compression as its lever on
+ * storage cost and load time, Section III-C; the scheme is this library's): for every
+ * (layer, K or V, KV head) the scale s is the smallest power of two with max|x| <= 448 s over
+ * the head's n_tokens x D values (1 if they are all zero, never below 2^-60), and every value
+ * becomes the E4M3 code (OCP FP8, largest value 448, round to nearest even) of x / s.  A reader
+ * sees code * s.  blob: device, bf16, matkv_blob_bytes(cfg, n_tokens); out: device,
+ * matkv_compressed_blob_bytes(cfg, n_tokens), 16-byte aligned, must not overlap blob.  Runs
+ * on the compute stream; capturable.  bf16 configurations only (else MATKV_EUNSUPPORTED).
+ * Load it like any blob (matkv_load / matkv_load_file accept either size) and name the format
+ * in matkv_page.format; attention over compressed pages needs bf16 and head_dim 128. */
+matkv_status matkv_compress(matkv_ctx* ctx, const void* blob, int32_t n_tokens, void* out);
+
 /* The same projection for the newest tail rows of every instance of a cache table
  * (question tokens at prefill, the generated token at each decode step); where rows go
  * and which positions they take is read on the device from the table, so the call can
@@ -163,7 +185,8 @@ matkv_status matkv_materialize_tail(matkv_ctx* ctx, const void* hidden, const vo
 
 /* Asynchronous byte-exact copy of one blob, pinned host memory -> device slot, on the load
  * stream.  host_blob must be pinned (hipHostMalloc) and stay valid until the ticket
- * completes; bytes must equal matkv_blob_bytes(cfg, n_tokens) and fit slot_bytes.  If a cache
+ * completes; bytes must equal matkv_blob_bytes(cfg, n_tokens) or
+ * matkv_compressed_blob_bytes(cfg, n_tokens) and fit slot_bytes.  If a cache
  * table still points into the slot, the copy is ordered after all compute work enqueued so
  * far; if that table has since been re-assembled onto other slots, only after the work that
  * was enqueued up to that re-assembly (so the next instance's load runs beside the current

@@ -214,10 +214,11 @@ def e4m3_encode(y):
 
 
 def kv_scale(amax):
-    """Smallest power of two s with amax <= 448 s (1 when amax is 0)."""
+    """Smallest power of two s with amax <= 448 s; 1 when amax is 0; never below 2^-60
+    (heads that small keep that scale and lose precision instead)."""
     amax = _f64(amax)
     m, e = np.frexp(np.where(amax > 0, amax, 1.0))      # amax = m 2^e, m in [0.5, 1)
-    k = np.where(2.0 * m <= 1.75, e - 1 - 8, e - 1 - 7)
+    k = np.maximum(np.where(2.0 * m <= 1.75, e - 1 - 8, e - 1 - 7), -60)
     return np.where(amax > 0, np.exp2(k.astype(np.float64)), 1.0)
 
 

@@ -18,10 +18,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmatkv.so")
 
 OK, EINVAL, EUNSUPPORTED, ENOTREADY, EBUSY, EHIP, ENOMEM, EIO = range(8)
+PAGE_PLAIN, PAGE_E4M3 = 0, 1
 F32, BF16 = 0, 1
 
 EXPORTS = [
-    "matkv_blob_bytes", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
+    "matkv_blob_bytes", "matkv_compressed_blob_bytes", "matkv_compress", "matkv_tail_bytes", "matkv_workspace_bytes", "matkv_table_bytes",
     "matkv_config_check", "matkv_status_string", "matkv_create", "matkv_destroy",
     "matkv_last_error", "matkv_materialize", "matkv_materialize_tail", "matkv_chunk_attn", "matkv_load", "matkv_load_file", "matkv_store_file",
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
@@ -39,7 +40,7 @@ class Config(Structure):
 
 
 class Page(Structure):
-    _fields_ = [("slot", c_void_p), ("n_tokens", c_int32), ("reserved", c_int32)]
+    _fields_ = [("slot", c_void_p), ("n_tokens", c_int32), ("format", c_int32)]
 
 
 class Ticket(Structure):
@@ -91,6 +92,10 @@ def _load_library():
     for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
         fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         fn.restype = c_int32
+    lib.matkv_compressed_blob_bytes.argtypes = [POINTER(Config), c_int32]
+    lib.matkv_compressed_blob_bytes.restype = c_size_t
+    lib.matkv_compress.argtypes = [c_void_p, c_void_p, c_int32, c_void_p]
+    lib.matkv_compress.restype = c_int32
     lib.matkv_chunk_attn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32, c_void_p]
     lib.matkv_chunk_attn.restype = c_int32
     lib.matkv_decode_step.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
@@ -128,6 +133,10 @@ def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, hidden, dtype, rope_b
 
 def blob_bytes(cfg: Config, n_tokens: int) -> int:
     return int(_lib.matkv_blob_bytes(byref(cfg), n_tokens))
+
+
+def compressed_blob_bytes(cfg: Config, n_tokens: int) -> int:
+    return int(_lib.matkv_compressed_blob_bytes(byref(cfg), n_tokens))
 
 
 def tail_bytes(cfg: Config) -> int:
@@ -223,6 +232,9 @@ class Context:
         self._check(_lib.matkv_materialize(self._h, _ptr(hidden), _ptr(w_k), _ptr(w_v), n_tokens, pos0,
                                            _ptr(k_out), _ptr(v_out), token_stride), "matkv_materialize")
 
+    def compress(self, blob, n_tokens, out):
+        self._check(_lib.matkv_compress(self._h, _ptr(blob), n_tokens, _ptr(out)), "matkv_compress")
+
     def materialize_tail(self, hidden, w_k, w_v, table, rows_per_instance, tail_k, tail_v):
         self._check(_lib.matkv_materialize_tail(self._h, _ptr(hidden), _ptr(w_k), _ptr(w_v), _ptr(table),
                                                 rows_per_instance, _ptr(tail_k), _ptr(tail_v)),
@@ -261,14 +273,14 @@ class Context:
         self._check(_lib.matkv_sync(self._h, ticket), "matkv_sync")
 
     def assemble(self, pages, q_len, table, pos_base=None):
-        """pages: per instance a list of (slot tensor or address, n_tokens)."""
+        """pages: per instance a list of (slot tensor or address, n_tokens[, format])."""
         c = self.cfg
         batch = len(pages)
         arr = (Page * (max(batch, 1) * max(c.max_pages, 1)))()
         npg = (c_int32 * batch)(*[len(p) for p in pages])
         for b, plist in enumerate(pages):
-            for i, (slot, n) in enumerate(plist[:c.max_pages]):
-                arr[b * c.max_pages + i] = Page(_ptr(slot), n, 0)
+            for i, pg in enumerate(plist[:c.max_pages]):
+                arr[b * c.max_pages + i] = Page(_ptr(pg[0]), pg[1], pg[2] if len(pg) > 2 else PAGE_PLAIN)
         ql = (c_int32 * batch)(*q_len)
         pb = (c_int64 * batch)(*pos_base) if pos_base is not None else None
         self._check(_lib.matkv_assemble(self._h, arr, npg, ql, pb, batch, _ptr(table)), "matkv_assemble")

@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libmatkv.so")
 
 SOURCES = ["matkv_api.hip", "attn_rows.hip", "attn_mfma.hip", "attn_prefill.hip", "materialize.hip",
-           "materialize_mfma.hip"]
+           "materialize_mfma.hip", "compress.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -33,6 +33,25 @@ __device__ __forceinline__ uint4 ldg16(const void* p) {
     return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+// 8-byte load through the global address space.
+__device__ __forceinline__ uint2 ldg8(const void* p) {
+    typedef const __attribute__((address_space(1))) u32x2* gptr;
+    const u32x2 r = *(gptr)(uintptr_t)p;
+    return make_uint2(r.x, r.y);
+}
+
+// Eight E4M3 codes to eight bf16 (exact: three mantissa bits fit seven), through fp32.
+__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint2 w) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, true);
+    return make_uint4(__builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2)),
+                      __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2)),
+                      __builtin_bit_cast(uint32_t, __builtin_convertvector(c, bf16x2)),
+                      __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2)));
+}
+
 // Agent-scope relaxed accesses: coherent across the chip's L2 slices without cache flushes.
 __device__ __forceinline__ void st_agent2(float* p, float x, float y) {
     const uint64_t v = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
@@ -87,12 +106,23 @@ struct BlockRef {
     int tok_end;     // one past the block's last valid row
     bool is_tail;
     bool valid;
+    float sk, sv;    // compressed page: scale of this head's K and V codes (else unused)
 };
+
+// Scales of KV head kvh of a compressed page at `layer`: the blob's scale table is
+// [layer][K|V][Hkv] floats, scales16 * 16 bytes behind its base.
+__device__ __forceinline__ void page_scales(const Item& it, int layer, int Hkv, int kvh, float& sk, float& sv) {
+    const float* t = reinterpret_cast<const float*>(it.base + (uint64_t)it.scales16 * 16) + (size_t)layer * 2 * Hkv + kvh;
+    sk = t[0];
+    sv = t[Hkv];
+}
 
 // The unit's items, end to end, form one run of token rows (the tail clipped to tail_visible).
 // Each wave takes an equal contiguous share of the run, rounded up to ALIGN rows, and walks it
 // in blocks of at most BLK rows that never straddle two items.  All state is wave-uniform.
-template <typename T, int D, int NW, int BLK, int ALIGN>
+// F8: the pages are compressed (one E4M3 byte per element): k / v of a page block then point at
+// the head's codes (row stride D bytes) and sk / sv carry the head's scales; the tail stays in T.
+template <typename T, int D, int NW, int BLK, int ALIGN, bool F8 = false>
 struct Walker {
     const KernelArgs& a;
     const Unit& unit;
@@ -100,11 +130,13 @@ struct Walker {
     int kvh, tail_visible;
     Item item;
     int item_i, item_pos0, pos, pos_end;
+    float sk, sv;                // scales of the current item (compressed pages)
 
     __device__ __forceinline__ Walker(const KernelArgs& a_, const Unit& u_, const Item* items_, int kvh_,
                                       int tail_visible_, int wave)
         : a(a_), unit(u_), items(items_), kvh(kvh_), tail_visible(tail_visible_), item(u_.first),
-          item_i(0), item_pos0(0) {
+          item_i(0), item_pos0(0), sk(1.f), sv(1.f) {
+        if (F8 && item.base) page_scales(item, a.layer, a.Hkv, kvh, sk, sv);
         int total = unit.page_tokens;
         if (unit.has_tail) total += min(a.max_tail, tail_visible);
         const int share = ((total + NW - 1) / NW + ALIGN - 1) / ALIGN * ALIGN;
@@ -113,6 +145,19 @@ struct Walker {
     }
     __device__ __forceinline__ int rows_of(const Item& it) const {
         return it.base ? it.ntok : min(it.ntok, tail_visible);
+    }
+    // row 0 of this KV head's K and V inside a page's blob
+    __device__ __forceinline__ void page_heads(const Item& it, BlockRef<T>& r) const {
+        const size_t head_elems = (size_t)it.page_tokens * D;
+        if (F8) {
+            const uint8_t* codes = reinterpret_cast<const uint8_t*>(it.base);
+            r.k = reinterpret_cast<const T*>(codes + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems);
+            r.v = reinterpret_cast<const T*>(codes + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems);
+        } else {
+            const T* blob = reinterpret_cast<const T*>(it.base);
+            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+        }
     }
     __device__ __forceinline__ BlockRef<T> next() {
         BlockRef<T> r;
@@ -124,12 +169,14 @@ struct Walker {
             if (++item_i >= unit.n_items) return r;
             item = items[unit.item0 + item_i];
             rows = rows_of(item);
+            if (F8) {
+                sk = 1.f; sv = 1.f;
+                if (item.base) page_scales(item, a.layer, a.Hkv, kvh, sk, sv);
+            }
         }
+        r.sk = sk; r.sv = sv;
         if (item.base) {
-            const size_t head_elems = (size_t)item.page_tokens * D;
-            const T* blob = reinterpret_cast<const T*>(item.base);
-            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
-            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+            page_heads(item, r);
         } else {
             const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
             r.k = reinterpret_cast<const T*>(a.tail_k) + off;
@@ -151,11 +198,9 @@ struct Walker {
         BlockRef<T> r = next();
         if (r.valid) return r;
         const Item& f = unit.first;
+        r.sk = 1.f; r.sv = 1.f;
         if (f.base) {
-            const size_t head_elems = (size_t)f.page_tokens * D;
-            const T* blob = reinterpret_cast<const T*>(f.base);
-            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
-            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+            page_heads(f, r);
         } else {
             const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
             r.k = reinterpret_cast<const T*>(a.tail_k) + off;

@@ -156,7 +156,10 @@ constexpr int kFusedMaxBatch = 4;
 // workgroup of a KV head arrives at the counter of EVERY instance of the batch once all its
 // work is out, so the last arrival at an instance's counter knows that instance's partials and
 // its newest K/V row are complete, whichever workgroups produced them.
-template <int G, int NW, int MS, int PF, int FR>
+// F8: the pages hold E4M3 codes with per-head power-of-two scales; a block's codes are widened
+// to bf16 in registers (exact), the K scale multiplies the block's scores and the V scale its
+// weights on their way to bf16 (exact too: powers of two), the row sums stay unscaled.
+template <int G, int NW, int MS, int PF, int FR, bool F8>
 __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void attn_mfma_kernel(
         KernelArgs a, StepArgs f, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
@@ -224,10 +227,28 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
 
     uint16_t* const vstrip = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * BLK * VSTR;
 
-    Walker<T, D, NW, BLK, 8> walk(a, unit, items, kvh, tail_visible, wave);
+    Walker<T, D, NW, BLK, 8, F8> walk(a, unit, items, kvh, tail_visible, wave);
 
     // Rows past the block's end are clamped to its last row and masked in the softmax.
+    // (Compressed pages: the same number of loads, half as wide, so that both sides of the
+    // branch leave the same count of loads in flight.)
     auto issue = [&](const BlockRef<T>& r, uint4 (*ak)[4], uint4* vr) {
+        if (F8 && !r.is_tail) {
+            const uint8_t* kc = reinterpret_cast<const uint8_t*>(r.k);
+            const uint8_t* vc = reinterpret_cast<const uint8_t*>(r.v);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint8_t* kp = kc + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 8 * g4;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { const uint2 w = ldg8(kp + 32 * c); ak[h][c] = make_uint4(w.x, w.y, 0u, 0u); }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint2 w = ldg8(vc + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
+                vr[u] = make_uint4(w.x, w.y, 0u, 0u);
+            }
+            return;
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const T* kp = r.k + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 8 * g4;
@@ -239,7 +260,17 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
             vr[u] = ldg16(r.v + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
     };
 
-    auto consume = [&](const BlockRef<T>& r, const uint4 (*ak)[4], const uint4* vr) {
+    auto consume = [&](const BlockRef<T>& r, const uint4 (*ak_in)[4], const uint4* vr_in) {
+        uint4 ak[2][4], vr[8];
+        const bool codes = F8 && !r.is_tail;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                ak[h][c] = codes ? e4m3x8_to_bf16x8(make_uint2(ak_in[h][c].x, ak_in[h][c].y)) : ak_in[h][c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) vr[u] = codes ? e4m3x8_to_bf16x8(make_uint2(vr_in[u].x, vr_in[u].y)) : vr_in[u];
+        const float sc_blk = F8 ? a.scale_log2e * r.sk : a.scale_log2e;
         // V rows into this wave's strip, as loaded
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -264,8 +295,8 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
             for (int i = 0; i < 4; ++i) {
                 ok[i] = tb + i < limit;
                 ok[4 + i] = tb + 16 + i < limit;
-                sv[i] = ok[i] ? s0[i] * a.scale_log2e : kNegBig;
-                sv[4 + i] = ok[4 + i] ? s1[i] * a.scale_log2e : kNegBig;
+                sv[i] = ok[i] ? s0[i] * sc_blk : kNegBig;
+                sv[4 + i] = ok[4 + i] ? s1[i] * sc_blk : kNegBig;
                 mx = fmaxf(mx, fmaxf(sv[i], sv[4 + i]));
             }
             mx = fmaxf(mx, lane_xor(mx, 16, lane));
@@ -282,7 +313,7 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
             }
             lrow[j] = lrow[j] * alpha + psum;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)p[i];
+            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)(F8 ? p[i] * r.sv : p[i]);
             if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's maximum moved
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
@@ -380,11 +411,11 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
     }
 }
 
-template <int G, int NW, int MS, int PF>
+template <int G, int NW, int MS, int PF, bool F8 = false>
 hipError_t launch_v(const AttnArgs& a, int tiles, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
     dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
-    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, MS, PF, 0>), grid, block, 0, s, k, StepArgs{},
+    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, MS, PF, 0, F8>), grid, block, 0, s, k, StepArgs{},
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
@@ -398,7 +429,8 @@ hipError_t launch_step_v(const AttnArgs& a, const MaterializeArgs& m, hipStream_
     f.hidden = m.hidden; f.w_k = m.w_k; f.w_v = m.w_v; f.rope = m.rope;
     f.Hd = m.Hd; f.batch = a.batch;
     dim3 grid(a.n_units, a.Hkv, 1), block(2 * NW * 64);
-    hipLaunchKernelGGL((attn_mfma_kernel<G, NW, 1, 2, FR>), grid, block, 0, s, k, f,
+    auto kern = a.kv_fmt == MATKV_PAGE_E4M3 ? attn_mfma_kernel<G, NW, 1, 2, FR, true> : attn_mfma_kernel<G, NW, 1, 2, FR, false>;
+    hipLaunchKernelGGL(kern, grid, block, 0, s, k, f,
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
@@ -412,10 +444,12 @@ hipError_t launch_step_g(const AttnArgs& a, const MaterializeArgs& m, hipStream_
 
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
+    const bool f8 = a.kv_fmt == MATKV_PAGE_E4M3;        // compressed pages: the default shapes only
     if (a.prefill) {
         const int tiles = (a.rows * G + 31) / 32;
-        return launch_v<G, 4, 2, 2>(a, tiles, s);
+        return f8 ? launch_v<G, 4, 2, 2, true>(a, tiles, s) : launch_v<G, 4, 2, 2>(a, tiles, s);
     }
+    if (f8) return launch_v<G, 4, 1, 2, true>(a, 1, s);
     // decode: variant 9000 + 10 * (blocks in flight) + waves
     switch (a.variant % 100) {
         case 24: return launch_v<G, 4, 1, 2>(a, 1, s);

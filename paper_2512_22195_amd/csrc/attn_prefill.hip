@@ -44,7 +44,12 @@ __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
 // TB = token rows per step (a multiple of 32).  64 against 32 halves the per-step costs that do
 // not depend on the number of tokens (walking the items, addresses, barrier, reference update)
 // and measured 5-12 % ahead.
-template <int G, int MS, int TB>
+// F8: the pages hold E4M3 codes with per-head power-of-two scales (the tail stays bf16).  Codes
+// are widened to bf16 on their way into the LDS tiles (exact).  The K scale multiplies a block's
+// maximum and its exponent factor instead of its scores; the V scale goes into the weights as
+// they are rounded to bf16 (exact: a power of two) and is taken out of the row sums by summing
+// with 1/scale instead of 1 - so the per-element work is the same as for plain pages.
+template <int G, int MS, int TB, bool F8>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
@@ -98,8 +103,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     // The unit's item list sits in LDS: fetching an item from global memory inside the loop
     // would put a memory wait there that also drains the block loads in flight.
     __shared__ __attribute__((aligned(16))) Item sm_items[kMaxPrefillItemsPerUnit];
+    __shared__ float sm_scale[F8 ? kMaxPrefillItemsPerUnit : 1][2];    // K and V scale of every item
     for (int i = tid; i < unit.n_items * 2; i += NW * 64)
         reinterpret_cast<uint4*>(sm_items)[i] = reinterpret_cast<const uint4*>(items + unit.item0)[i];
+    if (F8 && tid < unit.n_items) {
+        const Item it = items[unit.item0 + tid];
+        float sk = 1.f, sv = 1.f;
+        if (it.base) page_scales(it, a.layer, a.Hkv, kvh, sk, sv);
+        sm_scale[tid][0] = sk; sm_scale[tid][1] = sv;
+    }
     __syncthreads();
 
     // Every wave walks the same blocks: the unit's items end to end (the tail clipped to the
@@ -115,7 +127,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     // so that the loop below can issue its loads unconditionally.
     BlockRef<T> last_block;
     last_block.valid = false; last_block.is_tail = false; last_block.k = nullptr; last_block.v = nullptr;
-    last_block.t0 = 0; last_block.tok_end = 0;
+    last_block.t0 = 0; last_block.tok_end = 0; last_block.sk = 1.f; last_block.sv = 1.f;
     auto next_block = [&]() {
         BlockRef<T> r = last_block;
         r.valid = false;
@@ -125,11 +137,19 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             wk.rows = rows_of(wk.item);
             wk.left = wk.rows;
         }
+        r.sk = 1.f; r.sv = 1.f;
         if (wk.item.base) {
             const size_t head_elems = (size_t)wk.item.page_tokens * D;
-            const T* blob = reinterpret_cast<const T*>(wk.item.base);
-            r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
-            r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+            if (F8) {
+                const uint8_t* codes = reinterpret_cast<const uint8_t*>(wk.item.base);
+                r.k = reinterpret_cast<const T*>(codes + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems);
+                r.v = reinterpret_cast<const T*>(codes + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems);
+                r.sk = sm_scale[wk.item_i][0]; r.sv = sm_scale[wk.item_i][1];
+            } else {
+                const T* blob = reinterpret_cast<const T*>(wk.item.base);
+                r.k = blob + ((size_t)(a.layer * 2 + 0) * a.Hkv + kvh) * head_elems;
+                r.v = blob + ((size_t)(a.layer * 2 + 1) * a.Hkv + kvh) * head_elems;
+            }
         } else {
             const size_t off = ((size_t)unit.inst * a.Hkv + kvh) * (size_t)a.max_tail * D;
             r.k = reinterpret_cast<const T*>(a.tail_k) + off;
@@ -151,6 +171,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
     constexpr int SR = TB / 16;
     struct Stage { uint4 k[SR], v[SR]; };
     auto load_global = [&](const BlockRef<T>& r, Stage& g) {
+        if (F8 && !r.is_tail) {      // the same number of loads, half as wide (see the loop below)
+#pragma unroll
+            for (int i = 0; i < SR; ++i) {
+                const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
+                const uint2 kw = ldg8(reinterpret_cast<const uint8_t*>(r.k) + off);
+                const uint2 vw = ldg8(reinterpret_cast<const uint8_t*>(r.v) + off);
+                g.k[i] = make_uint4(kw.x, kw.y, 0u, 0u);
+                g.v[i] = make_uint4(vw.x, vw.y, 0u, 0u);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < SR; ++i) {
             const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
@@ -158,13 +189,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             g.v[i] = ldg16(r.v + off);
         }
     };
-    auto store_lds = [&](int buf, const Stage& g) {
+    auto store_lds = [&](int buf, const Stage& g, bool codes) {
         uint16_t* kt = tiles + buf * TILE_ELEMS;
         uint16_t* vt = kt + TB * KSTR;
 #pragma unroll
         for (int i = 0; i < SR; ++i) {
-            *reinterpret_cast<uint4*>(kt + (st_row + 16 * i) * KSTR + st_col) = g.k[i];
-            *reinterpret_cast<uint4*>(vt + (st_row + 16 * i) * VSTR + st_col) = g.v[i];
+            uint4 kw = g.k[i], vw = g.v[i];
+            if (F8 && codes) {
+                kw = e4m3x8_to_bf16x8(make_uint2(kw.x, kw.y));
+                vw = e4m3x8_to_bf16x8(make_uint2(vw.x, vw.y));
+            }
+            *reinterpret_cast<uint4*>(kt + (st_row + 16 * i) * KSTR + st_col) = kw;
+            *reinterpret_cast<uint4*>(vt + (st_row + 16 * i) * VSTR + st_col) = vw;
         }
     };
 
@@ -185,6 +221,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         const bool masked = r.tok_end - r.t0 != TB || (r.is_tail && r.tok_end > vis_min);
         const uint16_t* kt = tiles + buf * TILE_ELEMS;
         const uint16_t* vt = kt + TB * KSTR;
+        // compressed page: scores carry the factor 1 / sk until the exponent, weights the factor
+        // sv from the exponent on (nsv = log2 sv goes into the exponent's offset)
+        const float scb = F8 ? sc * r.sk : sc;
+        const float nsv = F8 ? __builtin_amdgcn_frexp_expf(r.sv) - 1.0f : 0.f;
+        bf16x8 ones_b = ones;
+        if (F8) {
+            const __bf16 iv = (__bf16)(1.0f / r.sv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ones_b[i] = iv;
+        }
         // S^T in 16-token quarters q: lane holds tokens t0 + 16q + 4*g4 + i of its row
         f32x4 st[MS][2 * NH];
 #pragma unroll
@@ -231,6 +277,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             for (int i = 1; i < 8 * NH; ++i) mx = fmaxf(mx, sv[i]);
             mx = fmaxf(mx, lane_xor(mx, 16, lane));
             mx = fmaxf(mx, lane_xor(mx, 32, lane));
+            if (F8) mx = mx > 0.5f * kNegBig ? mx * r.sk : kNegBig;     // into the units of the reference
             // The reference score of a row moves only when the block's maximum exceeds it by
             // more than kLazyLog2 powers of two: weights stay below 2^kLazyLog2, and the
             // accumulators are rescaled on few blocks instead of on most.
@@ -243,7 +290,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
 #pragma unroll
             for (int h = 0; h < NH; ++h)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) pb[j][h][i] = (__bf16)fast_exp2(fmaf(sv[8 * h + i], sc, nmc));
+                for (int i = 0; i < 8; ++i) pb[j][h][i] = (__bf16)fast_exp2(fmaf(sv[8 * h + i], scb, nmc + nsv));
             if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's reference moved
                 ol[j][0] *= alpha;
 #pragma unroll
@@ -252,7 +299,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
                 }
             }
 #pragma unroll
-            for (int h = 0; h < NH; ++h) ol[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[j][h], ol[j], 0, 0, 0);
+            for (int h = 0; h < NH; ++h) ol[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones_b, pb[j][h], ol[j], 0, 0, 0);
         }
         // lane (c16, g4) names 4 dims (4*(c16%4) ..) of token 4*g4 + c16/4 (+16 for the second
         // quarter) of a half and receives dim 16s + c16 of tokens 4*g4 .. 4*g4+3: the k order of P
@@ -283,7 +330,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         // then move into the other LDS tile
         Stage g;
         load_global(r0, g);
-        store_lds(0, g);
+        store_lds(0, g, !r0.is_tail);
         __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0) only
         lds_barrier();
         int buf = 0;
@@ -291,7 +338,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
             const BlockRef<T> r1 = next_block();
             load_global(r1, g);
             if (wave_live) compute(r0, buf);
-            store_lds(buf ^ 1, g);
+            store_lds(buf ^ 1, g, !r1.is_tail);
             lds_barrier();
             r0 = r1;
             buf ^= 1;
@@ -387,12 +434,12 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ((size_t)q_row * a.Hq + head) * D + 4 * hl) = o;
 }
 
-template <int G, int MS, int TB>
+template <int G, int MS, int TB, bool F8>
 hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
     const int tiles = (a.rows * G + NW * 16 * MS - 1) / (NW * 16 * MS);
     dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
-    hipLaunchKernelGGL((attn_prefill_kernel<G, MS, TB>), grid, block, 0, s, k,
+    hipLaunchKernelGGL((attn_prefill_kernel<G, MS, TB, F8>), grid, block, 0, s, k,
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
@@ -406,12 +453,13 @@ hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
 
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
-    if (a.rows * G <= 64) return launch_v<G, 1, 64>(a, s);
+    if (a.kv_fmt == MATKV_PAGE_E4M3) return a.rows * G <= 64 ? launch_v<G, 1, 64, true>(a, s) : launch_v<G, 2, 64, true>(a, s);
+    if (a.rows * G <= 64) return launch_v<G, 1, 64, false>(a, s);
     // A chunk's own attention has one workgroup per (row tile, KV head) and the last tile walks
     // the whole chunk: until 128-row tiles give every compute unit two workgroups, 64-row
     // tiles do (1024 tokens, 8 KV heads: 31 us against 36 us; 4096 tokens: 269 against 210).
-    if (a.prefill == 2 && (long)((a.rows * G + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64>(a, s);
-    return launch_v<G, 2, 64>(a, s);
+    if (a.prefill == 2 && (long)((a.rows * G + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64, false>(a, s);
+    return launch_v<G, 2, 64, false>(a, s);
 }
 
 }  // namespace

@@ -44,6 +44,7 @@ struct TableHost {
     int batch = 0, n_items = 0, n_dunits = 0, n_punits = 0, total_q = 0, max_q = 0;
     int max_punits_inst = 0;  // most prefill units of any one instance
     int max_punit_items = 0;  // most items of any one prefill unit
+    int kv_fmt = 0;           // matkv_page_format of its pages
     int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
     int min_tail_len = 0;
     std::vector<const void*> slots;   // distinct slots its pages point into
@@ -188,8 +189,9 @@ int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long toke
 // equal token counts, in 8-token granules.  A run is a list of items (page pieces); the tail
 // is one item and belongs to the last run.  Appends to items / units; returns the number of
 // units made (runs that would hold no tokens are dropped).
+template <typename ScalesOff>
 int build_units(const matkv_page* pages, int n_pages, int inst, int n_units, int tail_estimate,
-                int max_tail, Item* items, int* n_items, Unit* units, int* n_units_out) {
+                int max_tail, Item* items, int* n_items, Unit* units, int* n_units_out, ScalesOff scales_off) {
     long page_gran = 0;
     for (int p = 0; p < n_pages; ++p) page_gran += (pages[p].n_tokens + 7) / 8;
     const long tail_gran = (tail_estimate + 7) / 8;
@@ -218,6 +220,8 @@ int build_units(const matkv_page* pages, int n_pages, int inst, int n_units, int
             it.tok0 = (int)((g - p_g0) * 8);
             const int t1 = (int)((e - p_g0) * 8);
             it.ntok = (t1 < pages[p].n_tokens ? t1 : pages[p].n_tokens) - it.tok0;
+            it.fmt = pages[p].format;
+            it.scales16 = (int32_t)(scales_off(pages[p].n_tokens) / 16);
             un.page_tokens += it.ntok;
             items[(*n_items)++] = it;
             g = e;
@@ -280,6 +284,12 @@ size_t matkv_blob_bytes(const matkv_config* cfg, int32_t n_tokens) {
     const char* why;
     if (check_config(cfg, &why) != MATKV_OK || n_tokens < 0) return 0;
     return (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * (size_t)n_tokens * cfg->head_dim * elem_bytes(*cfg);
+}
+
+size_t matkv_compressed_blob_bytes(const matkv_config* cfg, int32_t n_tokens) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK || n_tokens < 0) return 0;
+    return compressed_codes_bytes(*cfg, n_tokens) + compressed_scales_bytes(*cfg);
 }
 
 size_t matkv_tail_bytes(const matkv_config* cfg) {
@@ -407,6 +417,21 @@ matkv_status matkv_materialize(matkv_ctx* c, const void* hidden, const void* w_k
     return MATKV_OK;
 }
 
+matkv_status matkv_compress(matkv_ctx* c, const void* blob, int32_t n_tokens, void* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    if (!blob || !out) return fail(c, MATKV_EINVAL, "compress: null pointer");
+    if (!aligned16(blob) || !aligned16(out)) return fail(c, MATKV_EINVAL, "compress: pointers must be 16-byte aligned");
+    if (c->cfg.dtype != MATKV_BF16) return fail(c, MATKV_EUNSUPPORTED, "compress: bf16 configurations only");
+    if (n_tokens < 1) return fail(c, MATKV_EINVAL, "compress: n_tokens=%d", n_tokens);
+    const char* a = static_cast<const char*>(blob);
+    const char* b = static_cast<const char*>(out);
+    if (a < b + matkv_compressed_blob_bytes(&c->cfg, n_tokens) && b < a + matkv_blob_bytes(&c->cfg, n_tokens))
+        return fail(c, MATKV_EINVAL, "compress: output overlaps the blob");
+    HIP_TRY(c, launch_compress(blob, out, c->cfg.n_layers, c->cfg.n_kv_heads, n_tokens, c->cfg.head_dim, c->compute));
+    return MATKV_OK;
+}
+
 matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void* w_k, const void* w_v,
                                     const void* table, int32_t rows_per_instance, void* tail_k,
                                     void* tail_v) {
@@ -441,8 +466,9 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
 static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, int32_t n_tokens,
                                  void* device_slot, size_t slot_bytes, Ticket** t_out) {
     if (n_tokens < 1) return fail(c, MATKV_EINVAL, "%s: n_tokens=%d", name, n_tokens);
-    const size_t want = matkv_blob_bytes(&c->cfg, n_tokens);
-    if (bytes != want) return fail(c, MATKV_EINVAL, "%s: %zu bytes given, a %d-token blob has %zu", name, bytes, n_tokens, want);
+    const size_t want = matkv_blob_bytes(&c->cfg, n_tokens), want_c = matkv_compressed_blob_bytes(&c->cfg, n_tokens);
+    if (bytes != want && bytes != want_c)
+        return fail(c, MATKV_EINVAL, "%s: %zu bytes given, a %d-token blob has %zu (compressed: %zu)", name, bytes, n_tokens, want, want_c);
     if (slot_bytes < bytes) return fail(c, MATKV_EINVAL, "%s: slot of %zu bytes cannot hold %zu", name, slot_bytes, bytes);
     if (!aligned16(device_slot)) return fail(c, MATKV_EINVAL, "%s: pointers must be 16-byte aligned", name);
     hipPointerAttribute_t attr;
@@ -672,6 +698,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     if (batch < 1 || batch > c->cfg.max_batch) return fail(c, MATKV_EINVAL, "assemble: batch=%d, max_batch=%d", batch, c->cfg.max_batch);
     const matkv_config& cfg = c->cfg;
     long total_tokens = 0;
+    int kv_fmt = -1;                   // format of the table's pages (-1: none seen yet)
     for (int b = 0; b < batch; ++b) {
         if (n_pages[b] < 0 || n_pages[b] > cfg.max_pages) return fail(c, MATKV_EINVAL, "assemble: instance %d has %d pages, max_pages=%d", b, n_pages[b], cfg.max_pages);
         if (n_pages[b] > 0 && !pages) return fail(c, MATKV_EINVAL, "assemble: pages is null");
@@ -681,6 +708,10 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
             const matkv_page& pg = pages[(size_t)b * cfg.max_pages + p];
             if (!pg.slot || !aligned16(pg.slot) || pg.n_tokens < 1)
                 return fail(c, MATKV_EINVAL, "assemble: instance %d page %d is invalid", b, p);
+            if (pg.format != MATKV_PAGE_PLAIN && pg.format != MATKV_PAGE_E4M3)
+                return fail(c, MATKV_EINVAL, "assemble: instance %d page %d has unknown format %d", b, p, pg.format);
+            if (kv_fmt < 0) kv_fmt = pg.format;
+            if (pg.format != kv_fmt) return fail(c, MATKV_EUNSUPPORTED, "assemble: plain and compressed pages in one table");
             auto it = c->slots.find(pg.slot);
             if (it != c->slots.end() && it->second.pending && !it->second.waited) {
                 Ticket& t = c->tickets[it->second.pending % kTicketRing];
@@ -701,6 +732,10 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     }
 
     (void)total_tokens;
+    if (kv_fmt < 0) kv_fmt = MATKV_PAGE_PLAIN;
+    if (kv_fmt == MATKV_PAGE_E4M3 && !(cfg.dtype == MATKV_BF16 && cfg.head_dim == 128))
+        return fail(c, MATKV_EUNSUPPORTED, "assemble: compressed pages need bf16 and head_dim 128");
+    auto scales_off = [&](int n_tokens) { return kv_fmt == MATKV_PAGE_E4M3 ? compressed_codes_bytes(cfg, n_tokens) : (size_t)0; };
     Staging& sg = c->staging[c->staging_next];
     c->staging_next = (c->staging_next + 1) % kStagingRing;
     if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.ev));
@@ -738,12 +773,12 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         // decode: fine partition, one workgroup per (unit, KV head)
         in.dunit0 = n_dunits;
         in.n_dunits = build_units(pg, n_pages[b], b, choose_decode_units(cfg, batch, inst_tokens + tail_est),
-                                  tail_est, cfg.max_tail_tokens, items, &n_items, dunits, &n_dunits);
+                                  tail_est, cfg.max_tail_tokens, items, &n_items, dunits, &n_dunits, scales_off);
         // prefill: coarse partition (the question rows supply most of the parallelism)
         const int pu = choose_prefill_units(cfg, prefill_tiles, inst_tokens + q_len[b]);
         in.punit0 = n_punits;
         in.n_punits = build_units(pg, n_pages[b], b, pu, q_len[b], cfg.max_tail_tokens, items, &n_items,
-                                  punits, &n_punits);
+                                  punits, &n_punits, scales_off);
         if (in.n_punits > th.max_punits_inst) th.max_punits_inst = in.n_punits;
         for (int u = in.punit0; u < n_punits; ++u)
             if (punits[u].n_items > th.max_punit_items) th.max_punit_items = punits[u].n_items;
@@ -760,7 +795,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     sg.used = true;
 
     th.batch = batch; th.n_items = n_items; th.n_dunits = n_dunits; th.n_punits = n_punits;
-    th.total_q = cu; th.max_q = max_q;
+    th.total_q = cu; th.max_q = max_q; th.kv_fmt = kv_fmt;
     // Slot bookkeeping: the table's old contents are dead from here on in stream order, so the
     // slots only they pointed into may be overwritten once the work enqueued so far is done.
     for (int b = 0; b < batch; ++b) {
@@ -799,7 +834,7 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
         if (page_tokens[p] < 1) return -1;
         pages[p].slot = reinterpret_cast<const void*>((uintptr_t)0x1000);   // never dereferenced
         pages[p].n_tokens = page_tokens[p];
-        pages[p].reserved = 0;
+        pages[p].format = MATKV_PAGE_PLAIN;
         inst_tokens += page_tokens[p];
     }
     const int tail_est = q_len + (cfg->max_tail_tokens - q_len) / 2;
@@ -807,7 +842,8 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
     std::vector<Unit> units((size_t)kMaxDecodeUnitsPerInstance);
     int n_items = 0, n_units = 0;
     const int made = build_units(pages.data(), n_pages, 0, choose_decode_units(*cfg, batch, inst_tokens + tail_est),
-                                 tail_est, cfg->max_tail_tokens, items.data(), &n_items, units.data(), &n_units);
+                                 tail_est, cfg->max_tail_tokens, items.data(), &n_items, units.data(), &n_units,
+                                 [](int) { return (size_t)0; });
     for (int u = 0; u < made && u < cap; ++u) {
         if (unit_tokens_out) unit_tokens_out[u] = units[u].page_tokens;
         if (unit_items_out) unit_items_out[u] = units[u].n_items - units[u].has_tail;
@@ -857,7 +893,7 @@ static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32
     a.rows = prefill ? th->max_q : 1;
     a.n_units = prefill ? th->n_punits : th->n_dunits;
     a.max_units_inst = prefill ? th->max_punits_inst : 0;
-    a.batch = th->batch; a.total_q = th->total_q;
+    a.batch = th->batch; a.total_q = th->total_q; a.kv_fmt = th->kv_fmt;
     a.max_unit_items = prefill ? th->max_punit_items : 0;
     a.scale_log2e = c->scale_log2e;
     a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
@@ -874,6 +910,7 @@ static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int
     const bool want_mfma = prefill || a.variant == 0 || a.variant >= 9000;
     if (attn_prefill_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_prefill(a, c->cfg.dtype, c->compute));
     else if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
+    else if (a.kv_fmt != MATKV_PAGE_PLAIN) return fail(c, MATKV_EUNSUPPORTED, "%s: compressed pages need the matrix-core kernels (decode_variant 0 or 90xx)", name);
     else HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
 }
@@ -910,8 +947,10 @@ matkv_status matkv_decode_step(matkv_ctx* c, int32_t layer, const void* hidden, 
         return MATKV_OK;
     }
     // shapes the fused kernel does not cover: the two launches it stands for
-    HIP_TRY(c, launch_materialize(m, c->cfg.dtype, c->compute));
     const bool want_mfma = a.variant == 0 || a.variant >= 9000;
+    if (a.kv_fmt != MATKV_PAGE_PLAIN && !(want_mfma && attn_mfma_supported(a, c->cfg.dtype)))
+        return fail(c, MATKV_EUNSUPPORTED, "decode_step: compressed pages need the matrix-core kernels (decode_variant 0 or 90xx)");
+    HIP_TRY(c, launch_materialize(m, c->cfg.dtype, c->compute));
     if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
     else HIP_TRY(c, launch_attn_rows(a, c->cfg.dtype, c->compute));
     return MATKV_OK;

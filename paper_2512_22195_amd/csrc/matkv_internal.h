@@ -23,7 +23,9 @@ struct Item {              // 32 bytes: a run of tokens inside one page, or the 
     int32_t page_tokens;   // tokens of the whole page (stride of a head inside the blob)
     int32_t tok0;          // first token of this piece
     int32_t ntok;          // tokens of this piece (tail: capacity, clipped by tail_len)
-    int32_t pad[3];
+    int32_t fmt;           // matkv_page_format of the page
+    int32_t scales16;      // compressed page: byte offset of its scale table inside the blob, / 16
+    int32_t pad;
 };
 
 struct Unit {              // 64 bytes: the work of one workgroup = consecutive items of one instance
@@ -137,6 +139,7 @@ struct AttnArgs {
     int32_t prefill;           // 0: decode units + whole tail; 1: prefill units + causal tail;
                                // 2: as 1 for a chunk's own attention (longest row tiles first)
     float scale_log2e;
+    int32_t kv_fmt;            // matkv_page_format of every page of the table
     int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
                                // waves * 100 + loads in flight = plain-ALU kernel
     size_t off_inst, off_items, off_units;
@@ -182,5 +185,14 @@ hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int d
 hipError_t launch_probe_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s);
 hipError_t launch_advance(char* table, size_t off_inst, int batch, int n, int max_tail, hipStream_t s);
 hipError_t launch_chunk_table(char* table, int n_tokens, hipStream_t s);
+hipError_t launch_compress(const void* blob, void* out, int n_layers, int Hkv, int n_tokens, int D, hipStream_t s);
+
+// Compressed blob: codes, then the scale table [layer][K|V][Hkv] (float), both padded to 16 bytes.
+inline size_t compressed_codes_bytes(const matkv_config& c, int n_tokens) {
+    return ((size_t)c.n_layers * 2 * c.n_kv_heads * (size_t)n_tokens * c.head_dim + 15) & ~(size_t)15;
+}
+inline size_t compressed_scales_bytes(const matkv_config& c) {
+    return ((size_t)c.n_layers * 2 * c.n_kv_heads * sizeof(float) + 15) & ~(size_t)15;
+}
 
 }  // namespace matkv

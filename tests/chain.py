@@ -36,6 +36,7 @@ class Case:
     decode_variant: int = 0
     max_tail: int | None = None
     needle: bool = False             # plant one key that dominates the softmax
+    compressed: bool = False         # chunk blobs go through matkv_compress before they are loaded
 
     @property
     def batch(self):
@@ -126,11 +127,37 @@ def make_context(case: Case, device="cuda:0"):
     return mk.Context(cfg, device=device)
 
 
+def page_format(case: Case):
+    from paper_2512_22195_amd import binding as mk
+    return mk.PAGE_E4M3 if case.compressed else mk.PAGE_PLAIN
+
+
+def pages_of(case: Case, slots: dict):
+    return [[(slots[cid], case.chunk_lens[cid], page_format(case)) for cid in r] for r in case.retrieved]
+
+
+def compress_on_gpu(ctx, case: Case, dev_blob, n_tokens):
+    """matkv_compress of a device blob; returns the compressed blob as a device byte tensor."""
+    from paper_2512_22195_amd import binding as mk
+    out = torch.empty(mk.compressed_blob_bytes(ctx.cfg, n_tokens), dtype=torch.uint8, device=dev_blob.device)
+    with torch.cuda.stream(ctx.compute_stream):
+        ctx.compress(dev_blob, n_tokens, out)
+        ctx.compute_stream.synchronize()
+    return out
+
+
 def load_blobs(ctx, case: Case, blobs: dict):
-    """store_KV stand-in: blobs sit in pinned host memory; load_KV: matkv_load into slots."""
+    """store_KV stand-in: blobs sit in pinned host memory; load_KV: matkv_load into slots.
+    With case.compressed the blob is compressed on the GPU first and its compressed form is
+    what sits in host memory and is loaded."""
     slots, keep = {}, []
     for cid, blob in blobs.items():
-        host = blob.contiguous().view(torch.uint8).reshape(-1).pin_memory()
+        if case.compressed:
+            with torch.cuda.stream(ctx.compute_stream):
+                dev = blob.contiguous().to(ctx.device)
+            host = compress_on_gpu(ctx, case, dev, case.chunk_lens[cid]).cpu().pin_memory()
+        else:
+            host = blob.contiguous().view(torch.uint8).reshape(-1).pin_memory()
         slot = ctx.new_slot(case.chunk_lens[cid])
         t = ctx.load(host, case.chunk_lens[cid], slot)
         ctx.wait(t)
@@ -151,7 +178,7 @@ def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=Non
             q_pre = inp["q_pre"].to(device)
             q_dec = inp["q_dec"].to(device)
             table = ctx.new_table()
-            pages = [[(slots[cid], c.chunk_lens[cid]) for cid in r] for r in c.retrieved]
+            pages = pages_of(c, slots)
             ctx.assemble(pages, c.q_lens, table)
             o_pre = torch.full_like(q_pre, float("nan"))
             o_dec = torch.full_like(q_dec, float("nan"))
@@ -233,7 +260,9 @@ def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False
             fd = os.open(path, os.O_RDWR | os.O_CREAT | os.O_TRUNC, 0o600)
             try:
                 offs, off = {}, 0
-                for cid, b in dev_blobs.items():                             # store_KV
+                stored = {cid: (compress_on_gpu(ctx, c, b, c.chunk_lens[cid]) if c.compressed else b)
+                          for cid, b in dev_blobs.items()}
+                for cid, b in stored.items():                                # store_KV
                     offs[cid] = off
                     ctx.store_file(fd, off, b)
                     off += (b.numel() * b.element_size() + 4095) // 4096 * 4096
@@ -241,13 +270,14 @@ def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False
                 slots = {}
                 for cid, n in c.chunk_lens.items():                          # load_KV
                     slots[cid] = ctx.new_slot(n)
-                    nb = dev_blobs[cid].numel() * dev_blobs[cid].element_size()
+                    nb = stored[cid].numel() * stored[cid].element_size()
                     ctx.wait(ctx.load_file(fd, offs[cid], nb, n, slots[cid]))
                 with open(path, "rb") as f:                                  # the file holds the blobs' bytes
-                    for cid, b in host_blobs.items():
+                    for cid, b in stored.items():
                         f.seek(offs[cid])
                         raw = f.read(b.numel() * b.element_size())
-                        assert raw == b.contiguous().view(torch.uint8).numpy().tobytes(), f"file bytes of chunk {cid}"
+                        assert raw == b.cpu().contiguous().view(torch.uint8).numpy().tobytes(), f"file bytes of chunk {cid}"
+                del stored
             finally:
                 os.close(fd)
             keep = None
@@ -257,7 +287,7 @@ def run_gpu_chain(case: Case, inp, device="cuda:0", fused=False, use_graph=False
         with torch.cuda.stream(ctx.compute_stream):
             tail = ctx.new_tail()
             table = ctx.new_table()
-            pages = [[(slots[cid], c.chunk_lens[cid]) for cid in r] for r in c.retrieved]
+            pages = pages_of(c, slots)
             ctx.assemble(pages, c.q_lens, table)                             # A
             x_q, x_dec = inp["x_q"].to(device), inp["x_dec"].to(device)
             q_pre, q_dec = inp["q_pre"].to(device), inp["q_dec"].to(device)
@@ -359,6 +389,14 @@ def cu_q(case: Case):
     return cu
 
 
+def as_loaded(case: Case, K, V):
+    """What the attention reads of a chunk's stored K/V: the values themselves, or - through a
+    compressed blob - their 8-bit codes times the head's scale."""
+    if not case.compressed:
+        return K, V
+    return oracle.decompress(*oracle.compress(K, V))
+
+
 def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=None, prefill_rows=None, proj=None):
     """fp64 oracle over the same generated K/V.  Returns dicts keyed by (layer) / (step, layer)
     of arrays shaped like the GPU outputs restricted to the sampled instances.
@@ -373,7 +411,7 @@ def run_oracle_attention(case: Case, inp, layers=None, steps=None, instances=Non
     pre, dec = {}, {}
     for l in layers:
         for b in instances:
-            chunks = [(to_f64(inp["blobs"][cid][l, 0]), to_f64(inp["blobs"][cid][l, 1])) for cid in c.retrieved[b]]
+            chunks = [as_loaded(c, to_f64(inp["blobs"][cid][l, 0]), to_f64(inp["blobs"][cid][l, 1])) for cid in c.retrieved[b]]
             lq = c.q_lens[b]
             tk, tv = to_f64(tail[l, 0, b]), to_f64(tail[l, 1, b])
             if prefill_rows is None:
@@ -422,7 +460,7 @@ def run_oracle_chain(case: Case, inp):
             Kt, Vt = oracle.materialize(np.concatenate(xs), wk, wv, c.Hkv, c.D, p0, c.rope_base)
             tails[(l, b)] = (Kt, Vt)
             Ktr, Vtr = store_round(Kt, c.dtype), store_round(Vt, c.dtype)
-            chunks = [(store_round(blobs[cid][l][0], c.dtype), store_round(blobs[cid][l][1], c.dtype))
+            chunks = [as_loaded(c, store_round(blobs[cid][l][0], c.dtype), store_round(blobs[cid][l][1], c.dtype))
                       for cid in c.retrieved[b]]
             pre[(l, b)] = oracle.prefill_attn(to_f64(inp["q_pre"][l, cu[b]:cu[b + 1]]), chunks,
                                               Ktr[:, :lq], Vtr[:, :lq])

@@ -689,3 +689,111 @@ def test_full_size_chunk_attention(L, Hq, Hkv, rows):
         ref = {(i, 0): oracle.attn(to_f64(q[r:r + 1]), K[:, :r + 1], V[:, :r + 1], 0, r) for i, r in enumerate(rows)}
         outs = {i: got[None, r:r + 1] for i, r in enumerate(rows)}
     chain.compare_chunk_prefill(case, outs, ref)
+
+
+# ------------------------------------------------------------------ compressed chunk blobs --
+def test_compress_is_bit_exact():
+    """matkv_compress against the oracle: every code byte and every scale.  Heads of very
+    different magnitudes, one head of zeros, one tiny head on the scale floor, values on exact
+    ties of the 8-bit grid, a largest value just above a power-of-two boundary."""
+    from paper_2512_22195_amd import binding as mk
+    from workload import normal, to_f64
+    import oracle
+    nl, Hkv, L, D = 2, 4, 77, 128
+    case = Case("compress", n_layers=nl, Hq=8, Hkv=Hkv, D=D, hidden=256, dtype="bf16",
+                chunk_lens={0: L}, retrieved=[[0]], q_lens=[1], steps=0)
+    blob = normal(("compress", "blob"), (nl, 2, Hkv, L, D), 1.0, torch.bfloat16)
+    blob[0, 0, 0] *= 1e-3
+    blob[0, 1, 1] *= 300.0
+    blob[1, 0, 2] = 0
+    blob[1, 1, 3] *= 1e-24
+    blob[1, 1, 0] = (blob[1, 1, 0].float().clamp(-3.4, 3.4)).to(torch.bfloat16)
+    blob[1, 1, 0, 0, 0] = 3.515625                                   # largest value: just above 3.5 = 448 / 128
+    blob[1, 1, 0, 1, :8] = torch.tensor([0.0625 * 17 / 16, 0.0625 * 19 / 16, 0.0625 * 21 / 16, -0.0625 * 23 / 16,
+                                          2.0 ** -16, 3 * 2.0 ** -16, -5 * 2.0 ** -16, 0.0]).to(torch.bfloat16)   # ties of the grid at scale 2^-6, normal and subnormal
+    ctx = chain.make_context(case)
+    try:
+        got = chain.compress_on_gpu(ctx, case, blob.cuda(), L).cpu()
+    finally:
+        ctx.close()
+    n_codes = nl * 2 * Hkv * L * D
+    assert got.numel() == mk.compressed_blob_bytes(ctx.cfg, L) == (n_codes + 15) // 16 * 16 + nl * 2 * Hkv * 4
+    codes = got[:n_codes].view(nl, 2, Hkv, L, D).numpy()
+    scales = got[(n_codes + 15) // 16 * 16:].view(torch.float32).view(nl, 2, Hkv).numpy()
+    for l in range(nl):
+        rc, rs = oracle.compress(to_f64(blob[l, 0]), to_f64(blob[l, 1]))
+        assert np.array_equal(scales[l].astype(np.float64), rs), f"layer {l} scales {scales[l]} vs {rs}"
+        # the sign of a zero is not information: compare the decoded values for equality, codes elsewhere
+        same = codes[l] == rc
+        zero = (rc & 0x7F) == 0
+        assert (same | (zero & ((codes[l] & 0x7F) == 0))).all(), f"layer {l}: {np.argwhere(~same)[:5]}"
+    assert scales[1, 0, 2] == 1.0 and (codes[1, 0, 2] & 0x7F == 0).all()       # head of zeros
+    assert scales[1, 1, 3] == 2.0 ** -60                                       # floor
+    assert scales[1, 1, 0] == 2.0 ** -6
+
+
+@pytest.mark.parametrize("name,Hq,Hkv,use_graph", [("g4", 8, 2, False), ("g1", 2, 2, False), ("g8", 8, 1, True), ("g2", 4, 2, False)])
+def test_attention_over_compressed_pages(name, Hq, Hkv, use_graph):
+    """Prefill and decode attention over pages loaded in compressed form against the oracle over
+    code * scale: ragged chunks, shared pages, an instance without pages, heads whose scales
+    differ by orders of magnitude."""
+    case = Case(f"f8-attn-{name}", n_layers=2, Hq=Hq, Hkv=Hkv, D=128, hidden=256, dtype="bf16",
+                chunk_lens={0: 200, 1: 137, 2: 64, 3: 1000}, retrieved=[[0, 1], [2, 0, 3], [], [3]],
+                q_lens=[9, 40, 3, 1], steps=4, scale=1.0, q_scale=1.0, compressed=True)
+    inp = chain.make_attention_inputs(case)
+    inp["blobs"][1][:, 1] *= 1.0 / 64.0    # chunk 1: small V
+    inp["blobs"][2][:, 0] *= 1.0 / 32.0    # chunk 2: small K
+    inp["blobs"][3][:, 0, 0] *= 2.0        # chunk 3: KV head 0 has larger K than the others
+    o_pre, o_dec = chain.run_gpu_attention(case, inp, use_graph=use_graph)
+    pre, dec = chain.run_oracle_attention(case, inp)
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+
+
+@pytest.mark.parametrize("batch,fused,files", [(1, True, False), (3, True, True), (6, False, False)])
+def test_chain_with_compressed_blobs(batch, fused, files, tmp_path):
+    """materialize -> compress -> (file ->) load -> assemble -> prefill -> decode steps (one launch
+    per layer where the fused step covers the batch) against the oracle's chain with the same
+    compression of the stored values."""
+    retrieved = [[0, 1], [1], [0], [1, 0], [], [0]][:batch]
+    case = Case(f"f8-chain-{batch}", n_layers=2, Hq=8, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 150, 1: 333}, retrieved=retrieved, q_lens=[5, 17, 1, 8, 3, 33][:batch],
+                steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0, compressed=True)
+    inp = chain.make_chain_inputs(case)
+    gpu = chain.run_gpu_chain(case, inp, fused=fused, blob_dir=str(tmp_path) if files else None)
+    ref = chain.run_oracle_chain(case, inp)
+    chain.compare_attention(case, gpu["o_pre"], gpu["o_dec"], ref["pre"], ref["dec"])
+
+
+def test_compressed_pages_argument_checks():
+    from paper_2512_22195_amd import binding as mk
+    case = Case("f8-args", n_layers=1, Hq=4, Hkv=2, D=128, hidden=128, dtype="bf16",
+                chunk_lens={0: 32}, retrieved=[[0, 0]], q_lens=[4], steps=1)
+    ctx = chain.make_context(case)
+    try:
+        slot, table = ctx.new_slot(32), ctx.new_table()
+        with pytest.raises(mk.MatKVError) as e:                       # two formats in one table
+            ctx.assemble([[(slot, 32, mk.PAGE_PLAIN), (slot, 32, mk.PAGE_E4M3)]], [4], table)
+        assert e.value.status == mk.EUNSUPPORTED
+        with pytest.raises(mk.MatKVError) as e:                       # unknown format
+            ctx.assemble([[(slot, 32, 7)]], [4], table)
+        assert e.value.status == mk.EINVAL
+        blob = torch.zeros(mk.blob_bytes(ctx.cfg, 32), dtype=torch.uint8, device="cuda")
+        with pytest.raises(mk.MatKVError) as e:                       # output inside the input
+            ctx.compress(blob, 32, blob[16:])
+        assert e.value.status == mk.EINVAL
+        host = torch.zeros(mk.compressed_blob_bytes(ctx.cfg, 32) + 16, dtype=torch.uint8).pin_memory()
+        with pytest.raises(mk.MatKVError) as e:                       # neither of the two blob sizes
+            ctx.load(host, 32, slot)
+        assert e.value.status == mk.EINVAL
+        ctx.sync(ctx.load(host[:-16], 32, slot))
+    finally:
+        ctx.close()
+    case64 = Case("f8-args-64", n_layers=1, Hq=4, Hkv=2, D=64, hidden=128, dtype="bf16",
+                  chunk_lens={0: 32}, retrieved=[[0]], q_lens=[4], steps=1)
+    ctx = chain.make_context(case64)
+    try:
+        with pytest.raises(mk.MatKVError) as e:                       # head_dim 64 has no matrix-core kernel
+            ctx.assemble([[(ctx.new_slot(32), 32, mk.PAGE_E4M3)]], [4], ctx.new_table())
+        assert e.value.status == mk.EUNSUPPORTED
+    finally:
+        ctx.close()

@@ -379,6 +379,7 @@ def test_kv_scale_and_compress_roundtrip():
     r = amax[nz] / s[nz]
     assert (r <= 448.0).all() and (r > 224.0).all()
     assert s[1] == 1.0 and s[2] == 2.0 and s[3] == 0.5 and s[4] == 1.0 and s[6] == 2.0 ** -7 and s[7] == 2.0 ** -6
+    assert oracle.kv_scale([1e-30])[0] == 2.0 ** -60 and oracle.kv_scale([448 * 2.0 ** -60])[0] == 2.0 ** -60
     Hkv, L, D = 3, 11, 8
     K, V = rand(Hkv, L, D, s=5.0), rand(Hkv, L, D, s=0.01)
     codes, scales = oracle.compress(K, V)
