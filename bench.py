@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-load", action="store_true", help="skip the kv_load leg")
     ap.add_argument("--no-batch16", action="store_true", help="skip the batch-16 decode-attention leg")
+    ap.add_argument("--no-compressed", action="store_true", help="skip the leg with the chunks held as compressed blobs")
     ap.add_argument("--with-others", action="store_true",
                     help="with --roofline-only: also run the other kernels' leg (few eager launches each)")
     ap.add_argument("--unfused", action="store_true",
@@ -135,6 +136,123 @@ def batch16_decode_leg(reps=10, nl=8):
                             f"({len(chunk_ids)} distinct chunks)",
                 "bytes_per_launch": nbytes, "us_per_launch": round(us, 3), "GBps": round(nbytes / us / 1e3, 1),
                 "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+    finally:
+        ctx.close()
+
+
+def compressed_leg(config_id, reps=5):
+    """The same workload with the chunks held as compressed blobs (E4M3 codes + per-head scales,
+    matkv_compress): compression rate, load rate, the whole pass, and the decode step alone."""
+    import torch
+    from paper_2512_22195_amd import binding as mk
+    from workload import CONFIGS, normal, question_lengths, retrieved_chunks
+    shape = CONFIGS[config_id]
+    dev = torch.device("cuda:0")
+    tdt, vs = shape.torch_dtype, shape.value_scale
+    B, nl, Hq, Hkv, D, Hd, L = shape.batch, shape.n_layers, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.hidden, shape.chunk_tokens
+    q_lens, retrieved = question_lengths(shape), retrieved_chunks(shape)
+    chunk_ids = sorted({c for r in retrieved for c in r})
+    max_tail = (max(q_lens) + shape.decode_steps + 7) // 8 * 8
+    cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B, max_pages=shape.n_chunks,
+                         max_tail_tokens=max_tail)
+    ctx = mk.Context(cfg, device=dev)
+    cs = ctx.compute_stream
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    try:
+        cbytes, pbytes = mk.compressed_blob_bytes(cfg, L), mk.blob_bytes(cfg, L)
+        with torch.cuda.stream(cs):
+            slots, t_comp = {}, []
+            for cid in chunk_ids:
+                blob = normal((shape.name, "blob", cid), (nl, 2, Hkv, L, D), vs, tdt, dev)
+                slots[cid] = torch.empty(cbytes, dtype=torch.uint8, device=dev)
+                a, b = ev(), ev()
+                a.record(cs)
+                ctx.compress(blob, L, slots[cid])
+                b.record(cs)
+                t_comp.append((a, b))
+                cs.synchronize()
+                del blob
+            us_comp = min(a.elapsed_time(b) for a, b in t_comp[1:] or t_comp) * 1e3
+            # load: one compressed blob from pinned host memory into a spare slot, several times
+            host = slots[chunk_ids[0]].cpu().pin_memory()
+            spare = torch.empty(cbytes, dtype=torch.uint8, device=dev)
+        t0 = time.perf_counter()
+        n_load = 10
+        for _ in range(n_load):
+            tk = ctx.load(host, L, spare)
+        ctx.sync(tk)
+        load_s = (time.perf_counter() - t0) / n_load
+        with torch.cuda.stream(cs):
+            w = normal((shape.name, "w"), (nl, 2, Hkv * D, Hd), vs, tdt, dev)
+            total_q = sum(q_lens)
+            x_q = normal((shape.name, "x_q"), (nl, total_q, Hd), vs, tdt, dev)
+            x_dec = normal((shape.name, "x_dec"), (nl, B, Hd), vs, tdt, dev)
+            q_pre = normal((shape.name, "q_pre"), (nl, total_q, Hq, D), vs, tdt, dev)
+            q_dec = normal((shape.name, "q_dec"), (nl, B, Hq, D), vs, tdt, dev)
+            o_pre, o_dec = torch.empty_like(q_pre), torch.empty_like(q_dec)
+            tail, table = ctx.new_tail(), ctx.new_table()
+            pages = [[(slots[cid], L, mk.PAGE_E4M3) for cid in r] for r in retrieved]
+
+            def prefill_phase():
+                ctx.assemble(pages, q_lens, table)
+                for l in range(nl):
+                    ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
+                    ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+
+            prefill_phase()
+            ctx.graph_begin()
+            ctx.advance(table, 1)
+            for l in range(nl):
+                ctx.decode_step(l, x_dec[l], w[l, 0], w[l, 1], q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            g_step = ctx.graph_end()
+            ctx.graph_begin()
+            for l in range(nl):
+                ctx.decode_step(l, x_dec[l], w[l, 0], w[l, 1], q_dec[l], table, tail[l, 0], tail[l, 1], o_dec[l])
+            g_fixed = ctx.graph_end()
+            for _ in range(shape.decode_steps):
+                ctx.graph_launch(g_step)
+            cs.synchronize()
+            # the whole pass
+            a, b, c = ev(), ev(), ev()
+            a.record(cs)
+            prefill_phase()
+            b.record(cs)
+            for _ in range(shape.decode_steps):
+                ctx.graph_launch(g_step)
+            c.record(cs)
+            # the decode step alone, tail at its mid-run length
+            ctx.assemble(pages, q_lens, table)
+            ctx.advance(table, shape.decode_steps // 2)
+            for _ in range(2):
+                ctx.graph_launch(g_fixed)
+            d, e = ev(), ev()
+            d.record(cs)
+            for _ in range(reps):
+                ctx.graph_launch(g_fixed)
+            e.record(cs)
+            # question prefill attention alone
+            f0, f1 = ev(), ev()
+            f0.record(cs)
+            for l in range(nl):
+                ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+            f1.record(cs)
+            cs.synchronize()
+            ctx.graph_destroy(g_step); ctx.graph_destroy(g_fixed)
+        ms_pass = a.elapsed_time(c)
+        us_step = d.elapsed_time(e) * 1e3 / (reps * nl)
+        page_b = sum(L * len(r) for r in retrieved) * 2 * Hkv * D                       # one byte per element
+        tail_b = sum(q + shape.decode_steps // 2 for q in q_lens) * shape.kv_bytes_per_token_layer()
+        proj_b = 2 * Hkv * D * Hd * shape.elem_bytes + B * Hd * shape.elem_bytes
+        nbytes = page_b + tail_b + proj_b + 2 * B * Hq * D * shape.elem_bytes
+        return {"format": "E4M3 codes + one power-of-two scale per (layer, K/V, KV head)",
+                "blob_bytes": cbytes, "plain_blob_bytes": pbytes,
+                "compress": {"us_per_chunk": round(us_comp, 1), "GBps_read_plus_written": round((pbytes + cbytes) / us_comp / 1e3, 1)},
+                "load": {"GBps": round(cbytes / load_s / 1e9, 2), "ms_per_chunk": round(load_s * 1e3, 3)},
+                "tokens_per_s": round(B * shape.decode_steps / (ms_pass * 1e-3), 2),
+                "phases_ms": {"assemble+materialize+prefill": round(a.elapsed_time(b), 3), "decode": round(b.elapsed_time(c), 3)},
+                "decode_step": {"bytes_per_launch": nbytes, "us_per_launch": round(us_step, 3), "GBps": round(nbytes / us_step / 1e3, 1),
+                                "frac_of_hbm_peak": round(nbytes / us_step / 1e3 / HBM_PEAK_GBPS, 4)},
+                "prefill_attn_us_per_layer": round(f0.elapsed_time(f1) * 1e3 / nl, 2)}
     finally:
         ctx.close()
 
@@ -528,6 +646,12 @@ def main():
         except torch.cuda.OutOfMemoryError:
             roofline["decode_attn_batch16"] = None
 
+    # ------------------------------------------- the same workload over compressed blobs -----
+    compressed = None
+    if not args.roofline_only and not args.no_compressed and shape.dtype == "bf16" and D == 128 and args.variant == 0:
+        print("bench: compressed-blob leg", file=sys.stderr, flush=True)
+        compressed = compressed_leg(args.config)
+
     # ------------------------------------------------------------------------ cpu_baseline ---
     cpu = None
     if not args.no_cpu:
@@ -574,7 +698,8 @@ def main():
                    "batch": B, "cached_tokens": n_ctx if B > 1 else n_ctx[0], "decode_units": args.units, "decode_variant": args.variant},
         "phases_ms": {"assemble+materialize+prefill": round(ms_prefill, 3), "decode": round(ms_decode, 3),
                       "decode_us_per_layer_step": round(ms_decode * 1e3 / (steps_dec * nl), 3)},
-        "roofline": roofline, "other_kernels": other, "kv_load": kv_load, "cpu_baseline": cpu,
+        "roofline": roofline, "other_kernels": other, "kv_load": kv_load, "compressed_kv": compressed,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out))
     ctx.graph_destroy(g_step)

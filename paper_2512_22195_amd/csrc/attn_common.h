@@ -112,7 +112,10 @@ struct BlockRef {
 // Scales of KV head kvh of a compressed page at `layer`: the blob's scale table is
 // [layer][K|V][Hkv] floats, scales16 * 16 bytes behind its base.
 __device__ __forceinline__ void page_scales(const Item& it, int layer, int Hkv, int kvh, float& sk, float& sv) {
-    const float* t = reinterpret_cast<const float*>(it.base + (uint64_t)it.scales16 * 16) + (size_t)layer * 2 * Hkv + kvh;
+    // read through the constant address space: with a wave-uniform address these are scalar
+    // loads, which do not touch the counter of the vector loads in flight
+    typedef const __attribute__((address_space(4))) float* cptr;
+    const cptr t = (cptr)(uintptr_t)(it.base + (uint64_t)it.scales16 * 16) + ((size_t)layer * 2 * Hkv + kvh);
     sk = t[0];
     sv = t[Hkv];
 }

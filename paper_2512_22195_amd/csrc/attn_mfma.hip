@@ -210,8 +210,11 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
         if constexpr (FR > 0)
             projection_tasks<FR>(a, f, insts, kvh, (int)blockIdx.x * NW + (wave - NW), (int)gridDim.x * NW, lane);
     } else {
-    // Q in operand layout: lane (c16, g4) holds, for sub-tile j and 32-dim chunk c, the 8 dims
-    // 32c + 8*g4 .. +8 of row m0 + 16j + c16.  Padding rows repeat the last real row.
+    // Q in operand layout: lane (c16, g4) holds, for sub-tile j and chunk c of the head
+    // dimension, the 8 dims dim0(c) .. +8 of row m0 + 16j + c16: 32c + 8*g4 for plain pages; with
+    // compressed pages 16*g4 + 8*(c%2) + 64*(c/2), so that the two chunks of a pair are the 16
+    // codes of one 16-byte load.  Padding rows repeat the last real row.
+    auto dim0 = [&](int c) { return F8 ? 16 * g4 + 8 * (c & 1) + 64 * (c >> 1) : 32 * c + 8 * g4; };
     bf16x8 bq[MS][4];
     int vis[MS];                                        // tail rows this lane's row may see
 #pragma unroll
@@ -219,63 +222,52 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
         const int m = min(m0 + 16 * j + c16, n_m - 1);
         const int r = m / G, g = m % G;
         const int q_row = a.prefill ? q_row0 + r : q_row0;
-        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D + 8 * g4;
+        const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + 32 * c));
+        for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + dim0(c)));
         vis[j] = a.prefill ? r + 1 : tail_len;
     }
 
     uint16_t* const vstrip = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * BLK * VSTR;
 
-    Walker<T, D, NW, BLK, 8, F8> walk(a, unit, items, kvh, tail_visible, wave);
+    // One block's loads in registers.  Plain rows: lane (c16, g4) holds, per 16-token half, the
+    // 8 dims of each of the 4 chunks of its token row, and 8 V rows' worth of 8 dims.  Code rows
+    // (one byte per element): 16 dims per load, so half as many loads carry the same tokens.
+    struct PlainBuf { uint4 k[2][4], v[8]; };
+    struct CodeBuf { uint4 k[2][2], v[4]; };
 
     // Rows past the block's end are clamped to its last row and masked in the softmax.
-    // (Compressed pages: the same number of loads, half as wide, so that both sides of the
-    // branch leave the same count of loads in flight.)
-    auto issue = [&](const BlockRef<T>& r, uint4 (*ak)[4], uint4* vr) {
-        if (F8 && !r.is_tail) {
-            const uint8_t* kc = reinterpret_cast<const uint8_t*>(r.k);
-            const uint8_t* vc = reinterpret_cast<const uint8_t*>(r.v);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint8_t* kp = kc + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 8 * g4;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) { const uint2 w = ldg8(kp + 32 * c); ak[h][c] = make_uint4(w.x, w.y, 0u, 0u); }
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const uint2 w = ldg8(vc + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
-                vr[u] = make_uint4(w.x, w.y, 0u, 0u);
-            }
-            return;
-        }
+    auto issue_plain = [&](const BlockRef<T>& r, PlainBuf& b) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const T* kp = r.k + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 8 * g4;
+            const T* kp = r.k + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) ak[h][c] = ldg16(kp + 32 * c);
+            for (int c = 0; c < 4; ++c) b.k[h][c] = ldg16(kp + dim0(c));
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            vr[u] = ldg16(r.v + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
+            b.v[u] = ldg16(r.v + (size_t)min(r.t0 + 4 * u + g4, r.tok_end - 1) * D + 8 * c16);
+    };
+    // K: the two 16-byte pieces of the lane's token row that hold its dims (chunks 0-1, 2-3);
+    // V: lane l takes 16 dims (l % 8) of token row 8u + l / 8.
+    auto issue_codes = [&](const BlockRef<T>& r, CodeBuf& b) {
+        const uint8_t* kc = reinterpret_cast<const uint8_t*>(r.k);
+        const uint8_t* vc = reinterpret_cast<const uint8_t*>(r.v);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint8_t* kp = kc + (size_t)min(r.t0 + 16 * h + c16, r.tok_end - 1) * D + 16 * g4;
+            b.k[h][0] = ldg16(kp);
+            b.k[h][1] = ldg16(kp + 64);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            b.v[u] = ldg16(vc + (size_t)min(r.t0 + 8 * u + (lane >> 3), r.tok_end - 1) * D + 16 * (lane & 7));
     };
 
-    auto consume = [&](const BlockRef<T>& r, const uint4 (*ak_in)[4], const uint4* vr_in) {
-        uint4 ak[2][4], vr[8];
-        const bool codes = F8 && !r.is_tail;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                ak[h][c] = codes ? e4m3x8_to_bf16x8(make_uint2(ak_in[h][c].x, ak_in[h][c].y)) : ak_in[h][c];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) vr[u] = codes ? e4m3x8_to_bf16x8(make_uint2(vr_in[u].x, vr_in[u].y)) : vr_in[u];
-        const float sc_blk = F8 ? a.scale_log2e * r.sk : a.scale_log2e;
-        // V rows into this wave's strip, as loaded
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            *reinterpret_cast<uint4*>(vstrip + (4 * u + g4) * VSTR + 8 * c16) = vr[u];
-
+    // Scores, online softmax and P V of one block whose K operands are in ak and whose V rows
+    // are in this wave's strip.  sc_blk: score scale of the block; pv_scale: factor of its
+    // weights on their way to bf16 (both carry a compressed page's power-of-two scales).
+    auto attend = [&](const BlockRef<T>& r, const uint4 (*ak)[4], float sc_blk, float pv_scale) {
         bf16x8 pb[MS];
 #pragma unroll
         for (int j = 0; j < MS; ++j) {
@@ -313,7 +305,7 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
             }
             lrow[j] = lrow[j] * alpha + psum;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)(F8 ? p[i] * r.sv : p[i]);
+            for (int i = 0; i < 8; ++i) pb[j][i] = (__bf16)(p[i] * pv_scale);
             if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {   // wave-uniform: some row's maximum moved
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
@@ -338,26 +330,70 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
         __builtin_amdgcn_wave_barrier();                // and the next block's writes behind them
     };
 
+    auto consume_plain = [&](const BlockRef<T>& r, const PlainBuf& b) {
+        // V rows into this wave's strip, as loaded
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            *reinterpret_cast<uint4*>(vstrip + (4 * u + g4) * VSTR + 8 * c16) = b.v[u];
+        attend(r, b.k, a.scale_log2e, 1.0f);
+    };
+    auto consume_codes = [&](const BlockRef<T>& r, const CodeBuf& b) {
+        uint4 ak[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            ak[h][0] = e4m3x8_to_bf16x8(make_uint2(b.k[h][0].x, b.k[h][0].y));
+            ak[h][1] = e4m3x8_to_bf16x8(make_uint2(b.k[h][0].z, b.k[h][0].w));
+            ak[h][2] = e4m3x8_to_bf16x8(make_uint2(b.k[h][1].x, b.k[h][1].y));
+            ak[h][3] = e4m3x8_to_bf16x8(make_uint2(b.k[h][1].z, b.k[h][1].w));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            uint16_t* dst = vstrip + (8 * u + (lane >> 3)) * VSTR + 16 * (lane & 7);
+            *reinterpret_cast<uint4*>(dst) = e4m3x8_to_bf16x8(make_uint2(b.v[u].x, b.v[u].y));
+            *reinterpret_cast<uint4*>(dst + 8) = e4m3x8_to_bf16x8(make_uint2(b.v[u].z, b.v[u].w));
+        }
+        attend(r, ak, a.scale_log2e * r.sk, r.sv);
+    };
+
     // PF blocks of loads stay in flight: block i + PF is issued right after block i is consumed.
     // The loads are issued without a branch (past the end of the wave's share they all fall on
     // one row) and the loop has one exit: only then can the compiler count the loads in flight
     // exactly, instead of waiting for all of them before each block.
-    {
-        uint4 kb[PF][2][4], vb[PF][8];
+    auto stream = [&](auto& walk, auto buf_tag, auto issue, auto consume) {
+        decltype(buf_tag) b[PF];
         BlockRef<T> rb[PF];
 #pragma unroll
         for (int i = 0; i < PF; ++i) {
             rb[i] = walk.next_safe();
-            issue(rb[i], kb[i], vb[i]);
+            issue(rb[i], b[i]);
         }
         do {
 #pragma unroll
             for (int i = 0; i < PF; ++i) {
-                if (rb[i].valid) consume(rb[i], kb[i], vb[i]);
+                if (rb[i].valid) consume(rb[i], b[i]);
                 rb[i] = walk.next_safe();
-                issue(rb[i], kb[i], vb[i]);
+                issue(rb[i], b[i]);
             }
         } while (rb[0].valid);
+    };
+    if constexpr (!F8) {
+        Walker<T, D, NW, BLK, 8> walk(a, unit, items, kvh, tail_visible, wave);
+        stream(walk, PlainBuf{}, issue_plain, consume_plain);
+    } else {
+        // Compressed pages first, then the (plain) tail, each in a loop of its own: one loop
+        // over both kinds would put the two load patterns under a branch.
+        {
+            Walker<T, D, NW, BLK, 8, true> walk(a, unit, items, kvh, 0, wave);
+            stream(walk, CodeBuf{}, issue_codes, consume_codes);
+        }
+        if (unit.has_tail && tail_visible > 0) {
+            Unit tu = unit;                             // the unit's last item, alone
+            tu.item0 = unit.item0 + unit.n_items - 1; tu.n_items = 1; tu.page_tokens = 0;
+            tu.first.base = 0; tu.first.page_tokens = a.max_tail; tu.first.tok0 = 0; tu.first.ntok = a.max_tail;
+            tu.first.fmt = 0; tu.first.scales16 = 0;
+            Walker<T, D, NW, BLK, 8> walk(a, tu, items, kvh, tail_visible, wave);
+            stream(walk, PlainBuf{}, issue_plain, consume_plain);
+        }
     }
 
 #pragma unroll
