@@ -797,3 +797,21 @@ def test_compressed_pages_argument_checks():
         assert e.value.status == mk.EUNSUPPORTED
     finally:
         ctx.close()
+
+
+def test_config2_full_size_compressed_sampled():
+    """The compressed leg of bench.py: Llama-3-8B layer shape, 10 x 1000 cached tokens held as
+    compressed blobs, all 32 layers resident, decode steps through matkv_decode_step recorded
+    once and replayed.  The oracle checks layers {0, 31}: four question rows and decode steps
+    {0, 5} (all heads) over code * scale."""
+    from workload import normal
+    case = chain.case_from_config(2)
+    case.steps = 6
+    case.compressed = True
+    inp = chain.make_attention_inputs(case)
+    proj = dict(w=normal((case.name, "w"), (case.n_layers, 2, case.Hkv * case.D, case.hidden), case.scale, case.tdtype),
+                x_dec=normal((case.name, "x_dec"), (case.steps, case.n_layers, case.batch, case.hidden), 1.0, case.tdtype))
+    o_pre, o_dec = chain.run_gpu_attention(case, inp, proj=proj)
+    pre, dec = chain.run_oracle_attention(case, inp, layers=[0, 31], steps=[0, 5], prefill_rows=[0, 17, 40, 63], proj=proj)
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+    assert torch.isfinite(o_dec.float()).all() and torch.isfinite(o_pre.float()).all()
