@@ -89,7 +89,7 @@ def file_load_leg(ctx, host, dst, L, nbytes, with_fd=None):
             os.remove(path)
 
 
-def batch16_decode_leg(reps=10, nl=8):
+def batch16_decode_leg(reps=10, nl=8, compressed=False):
     """Decode attention at BASELINE config 3's shape (batch 16, five 1000-token chunks each from a
     pool of 200, question lengths 32..128, tails at mid-run), nl layers resident: the launch size
     at which the kernel is bandwidth-bound rather than bound by its fixed cost per launch."""
@@ -108,13 +108,20 @@ def batch16_decode_leg(reps=10, nl=8):
     cs = ctx.compute_stream
     try:
         with torch.cuda.stream(cs):
-            slots = {cid: normal((shape.name, "blob", cid), (nl, 2, Hkv, L, D), shape.value_scale, shape.torch_dtype, dev)
-                     for cid in chunk_ids}
+            slots = {}
+            for cid in chunk_ids:
+                slots[cid] = normal((shape.name, "blob", cid), (nl, 2, Hkv, L, D), shape.value_scale, shape.torch_dtype, dev)
+                if compressed:
+                    out = torch.empty(mk.compressed_blob_bytes(cfg, L), dtype=torch.uint8, device=dev)
+                    ctx.compress(slots[cid], L, out)
+                    cs.synchronize()
+                    slots[cid] = out
+            fmt = mk.PAGE_E4M3 if compressed else mk.PAGE_PLAIN
             q = normal((shape.name, "q_dec"), (nl, B, Hq, D), shape.value_scale, shape.torch_dtype, dev)
             o = torch.empty_like(q)
             tail = normal((shape.name, "tail"), (nl, 2, B, Hkv, max_tail, D), shape.value_scale, shape.torch_dtype, dev)
             table = ctx.new_table()
-            ctx.assemble([[(slots[cid], L) for cid in r] for r in retrieved], q_lens, table)
+            ctx.assemble([[(slots[cid], L, fmt) for cid in r] for r in retrieved], q_lens, table)
             ctx.advance(table, shape.decode_steps // 2)
             ctx.graph_begin()
             for l in range(nl):
@@ -130,7 +137,8 @@ def batch16_decode_leg(reps=10, nl=8):
             cs.synchronize()
             ctx.graph_destroy(g)
         us = a.elapsed_time(b) * 1e3 / (reps * nl)
-        nbytes = sum((L * len(r) + ql + shape.decode_steps // 2) * shape.kv_bytes_per_token_layer()
+        page_token_bytes = 2 * Hkv * D if compressed else shape.kv_bytes_per_token_layer()
+        nbytes = sum(L * len(r) * page_token_bytes + (ql + shape.decode_steps // 2) * shape.kv_bytes_per_token_layer()
                      for r, ql in zip(retrieved, q_lens)) + 2 * B * Hq * D * shape.elem_bytes
         return {"workload": f"BASELINE config 3 shape: batch {B}, {shape.n_chunks} x {L} tokens each, {nl} layers resident "
                             f"({len(chunk_ids)} distinct chunks)",
@@ -651,6 +659,8 @@ def main():
     if not args.roofline_only and not args.no_compressed and shape.dtype == "bf16" and D == 128 and args.variant == 0:
         print("bench: compressed-blob leg", file=sys.stderr, flush=True)
         compressed = compressed_leg(args.config)
+        if not args.no_batch16:
+            compressed["decode_attn_batch16"] = batch16_decode_leg(compressed=True)
 
     # ------------------------------------------------------------------------ cpu_baseline ---
     cpu = None
