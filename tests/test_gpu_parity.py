@@ -270,12 +270,25 @@ def test_prefill_group8_two_row_tiles():
     _attention_parity(case)
 
 
-def test_prefill_many_small_pages_takes_the_other_kernel():
+@pytest.mark.parametrize("compressed", [False, True])
+def test_prefill_many_small_pages_takes_the_other_kernel(compressed):
     """More pages in one unit than the item list of the row-parallel prefill kernel holds
-    (64): the launch falls back to the token-parallel matrix-core kernel."""
+    (64): the launch falls back to the token-parallel matrix-core kernel (plain and compressed
+    pages; every page has its own scales, and blocks never reach across two pages)."""
     lens = {i: 3 + (i % 4) for i in range(90)}
     case = Case("prefill-small-pages", n_layers=1, Hq=8, Hkv=2, D=128, hidden=64, dtype="bf16",
-                chunk_lens=lens, retrieved=[list(range(90))], q_lens=[9], steps=1, scale=0.5)
+                chunk_lens=lens, retrieved=[list(range(90))], q_lens=[9], steps=1, scale=0.5,
+                compressed=compressed)
+    _attention_parity(case)
+
+
+@pytest.mark.parametrize("compressed", [False, True])
+def test_prefill_mixed_unit_counts_compressed_and_question_of_one_page(compressed):
+    """The mixed batch of test_prefill_mixed_unit_counts_and_row_tiles with a fourth instance
+    whose question is longer than its one short page, both page formats."""
+    case = Case("prefill-mixed-f8", n_layers=2, Hq=8, Hkv=2, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 1203, 1: 997, 2: 85, 3: 8}, retrieved=[[0, 1, 0], [2], [], [3]],
+                q_lens=[41, 19, 1, 70], steps=2, scale=0.5, compressed=compressed)
     _attention_parity(case)
 
 
