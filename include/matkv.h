@@ -241,6 +241,16 @@ matkv_status matkv_assemble(matkv_ctx* ctx, const matkv_page* pages_host,
 int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tokens_host,
                                 int32_t n_pages, int32_t batch, int32_t q_len,
                                 int32_t* unit_tokens_out, int32_t* unit_items_out, int32_t cap);
+/* Decode work units of the table's shared partition, 0 if matkv_assemble built none, -1 if the
+ * table is unknown.  When two or more instances of a batch point at the same slot (the same
+ * chunk, retrieved by several requests), matkv_assemble cuts the DISTINCT pages into pieces
+ * and lists with each piece the instances that use it: the decode attention then reads a
+ * shared chunk once for up to 16 / (Hq/Hkv) instances at a time instead of once per
+ * instance.  Built only when at most half of the batch's page tokens are distinct (below that
+ * the cache hierarchy serves the repeated reads well enough), for plain pages, bf16,
+ * head_dim 128, decode_units = 0 and decode_variant = 0; results are the same as without it (every instance still gets exact
+ * attention over its own cache). */
+int32_t matkv_table_shared_units(matkv_ctx* ctx, const void* table);
 /* tail_len[b] += n for every instance of the table (a one-wave kernel; capturable). */
 matkv_status matkv_advance(matkv_ctx* ctx, void* table, int32_t n);
 

@@ -28,6 +28,7 @@ EXPORTS = [
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
+    "matkv_table_shared_units",
 ]
 
 
@@ -96,6 +97,8 @@ def _load_library():
     lib.matkv_compressed_blob_bytes.restype = c_size_t
     lib.matkv_compress.argtypes = [c_void_p, c_void_p, c_int32, c_void_p]
     lib.matkv_compress.restype = c_int32
+    lib.matkv_table_shared_units.argtypes = [c_void_p, c_void_p]
+    lib.matkv_table_shared_units.restype = c_int32
     lib.matkv_chunk_attn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32, c_void_p]
     lib.matkv_chunk_attn.restype = c_int32
     lib.matkv_decode_step.argtypes = [c_void_p, c_int32] + [c_void_p] * 8
@@ -284,6 +287,9 @@ class Context:
         ql = (c_int32 * batch)(*q_len)
         pb = (c_int64 * batch)(*pos_base) if pos_base is not None else None
         self._check(_lib.matkv_assemble(self._h, arr, npg, ql, pb, batch, _ptr(table)), "matkv_assemble")
+
+    def table_shared_units(self, table) -> int:
+        return int(_lib.matkv_table_shared_units(self._h, _ptr(table)))
 
     def advance(self, table, n=1):
         self._check(_lib.matkv_advance(self._h, _ptr(table), n), "matkv_advance")

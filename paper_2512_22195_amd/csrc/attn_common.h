@@ -221,6 +221,7 @@ struct RowMap {
     int slot_row;    // row index inside the partial buffer (question row; 0 for decode)
     int head;        // query head
     int q_row;       // row of the packed Q / O tensors
+    int unit_slot = -1;   // partial slot of the row's unit; -1 = the workgroup's own (blockIdx.x)
 };
 
 // Last-arrival merge of all units' partials into the output rows (see finish_unit).
@@ -349,7 +350,8 @@ __device__ __forceinline__ void publish_partial(const KernelArgs& a, const float
             ay = fmaf(src[1], c, ay);
             lv = fmaf(sm_l[w * ROWS + i], c, lv);
         }
-        float* prow = a.partials + (((size_t)blockIdx.x * a.rows + rm.slot_row) * a.Hq + rm.head) * PSTRIDE;
+        const size_t uslot = rm.unit_slot >= 0 ? (size_t)rm.unit_slot : (size_t)blockIdx.x;
+        float* prow = a.partials + ((uslot * a.rows + rm.slot_row) * a.Hq + rm.head) * PSTRIDE;
         st_agent2(prow + d, ax, ay);
         if (d == 0) st_agent2(prow + D, mn, lv);
     }

@@ -150,6 +150,72 @@ __device__ __forceinline__ void projection_tasks(const KernelArgs& a, const Step
 
 constexpr int kFusedMaxBatch = 4;
 
+// Shared decode units: fold, for every user of this unit at whose counter the workgroup arrived
+// last, that instance's partial slots into its G output rows - all such users at once.  A thread
+// owns pairs of output elements; a wave's 64 pairs are one (user, head) row, so the number of
+// slots is uniform within a wave.  users[u] = {instance, this unit's slot, first slot, slots}.
+template <int G, int NT>
+__device__ __forceinline__ void merge_shared(const KernelArgs& a, const int4* users, const int* lastv, int n_users, int kvh) {
+    typedef uint16_t T;
+    constexpr int PSTRIDE = kPartialStride(D), CB = 4, UPC = 8;
+    const int total = n_users * G * (D / 2);
+    const size_t ustride = (size_t)a.Hq * PSTRIDE;                     // decode: one row per slot
+    for (int c0 = threadIdx.x; c0 < total; c0 += NT * CB) {
+        float M[CB], L[CB], ox[CB], oy[CB];
+        const float* src[CB];
+        int n[CB], inst[CB], head[CB], dd[CB];
+        int nmax = 0;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            const int col = min(c0 + cb * NT, total - 1);
+            const int row = col / (D / 2), u = row / G;
+            const int4 us = users[u];
+            const bool live = c0 + cb * NT < total && lastv[u];
+            inst[cb] = us.x; head[cb] = kvh * G + row % G; dd[cb] = (col % (D / 2)) * 2;
+            n[cb] = live ? us.w : 0;
+            nmax = max(nmax, n[cb]);
+            src[cb] = a.partials + ((size_t)us.z * a.Hq + head[cb]) * PSTRIDE;
+            M[cb] = kNegBig; L[cb] = 0.f; ox[cb] = 0.f; oy[cb] = 0.f;
+        }
+        for (int u0 = 0; u0 < nmax; u0 += UPC) {
+            float2 av[CB][UPC], ml[CB][UPC];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) {
+                    const size_t uo = (size_t)min(u0 + k, max(n[cb], 1) - 1) * ustride;
+                    ml[cb][k] = ld_agent2(src[cb] + uo + D);
+                    av[cb][k] = ld_agent2(src[cb] + uo + dd[cb]);
+                }
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                float mn = M[cb];
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) mn = fmaxf(mn, (u0 + k < n[cb]) ? ml[cb][k].x : kNegBig);
+                const float cold = fast_exp2(M[cb] - mn);
+                L[cb] *= cold; ox[cb] *= cold; oy[cb] *= cold;
+                M[cb] = mn;
+#pragma unroll
+                for (int k = 0; k < UPC; ++k) {
+                    const float c = (u0 + k < n[cb]) ? fast_exp2(ml[cb][k].x - mn) : 0.f;
+                    L[cb] = fmaf(ml[cb][k].y, c, L[cb]);
+                    ox[cb] = fmaf(av[cb][k].x, c, ox[cb]);
+                    oy[cb] = fmaf(av[cb][k].y, c, oy[cb]);
+                }
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            if (n[cb] == 0) continue;
+            const float inv = 1.0f / L[cb];
+            *reinterpret_cast<uint32_t*>(reinterpret_cast<T*>(a.out) + ((size_t)inst[cb] * a.Hq + head[cb]) * D + dd[cb]) =
+                (uint32_t)f32_to_bf16_rne(ox[cb] * inv) | ((uint32_t)f32_to_bf16_rne(oy[cb] * inv) << 16);
+        }
+    }
+}
+
+// (Second launch bound: two waves per SIMD, i.e. at most 256 registers, wherever the decode
+// tile fits them - a few registers more would halve the workgroups resident per compute unit.)
 // FR = 0: attention only, NW waves.  FR > 0: fused decode step - the workgroup has NW more
 // waves, which project the newest token's K/V (FR instances per task) while the first NW walk
 // the cache; every compute unit then holds both kinds of work side by side.  In that form each
@@ -159,14 +225,20 @@ constexpr int kFusedMaxBatch = 4;
 // F8: the pages hold E4M3 codes with per-head power-of-two scales; a block's codes are widened
 // to bf16 in registers (exact), the K scale multiplies the block's scores and the V scale its
 // weights on their way to bf16 (exact too: powers of two), the row sums stay unscaled.
-template <int G, int NW, int MS, int PF, int FR, bool F8>
-__global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void attn_mfma_kernel(
+// SH: decode over the shared partition - `units` are SUnit records: one piece of a page (or one
+// instance's tail) and up to 16 / G instances whose newest tokens attend to it; the rows of the
+// tile are (user, query head) pairs, the piece is streamed once for all of them, every user gets
+// its own partial, and the workgroup arrives at every user's counter: the last arrival at an
+// instance's counter folds that instance's partial slots.
+template <int G, int NW, int MS, int PF, int FR, bool F8, bool SH = false>
+__global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && PF <= 2)) ? 2 : 1) void attn_mfma_kernel(
         KernelArgs a, StepArgs f, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
     constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
     constexpr int NT = (FR > 0 ? 2 : 1) * NW * 64;      // threads of the workgroup
     typedef uint16_t T;
-    __shared__ int sm_last, sm_lastv[FR > 0 ? kFusedMaxBatch : 1];
+    static_assert(!SH || (FR == 0 && MS == 1 && !F8), "shared units: plain decode tiles only");
+    __shared__ int sm_last, sm_lastv[SH ? kMaxSharedUsers : (FR > 0 ? kFusedMaxBatch : 1)];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -174,10 +246,16 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
     const int kvh = blockIdx.y, tile = blockIdx.z;
     const int m0 = tile * ROWS;
 
-    const Unit unit = units[blockIdx.x];
+    const SUnit* const su = reinterpret_cast<const SUnit*>(units) + blockIdx.x;     // SH only
+    const Unit unit = SH ? su->u : units[blockIdx.x];
 
     int n_m, q_row0, tail_len = 0, tail_visible;
-    if (a.prefill) {
+    if (SH) {
+        n_m = su->n_users * G;
+        q_row0 = 0;
+        if (unit.has_tail) tail_len = insts[unit.inst].tail_len;
+        tail_visible = tail_len;
+    } else if (a.prefill) {
         const InstanceInfo inst = insts[unit.inst];
         n_m = inst.q_len * G;
         if (m0 >= n_m) return;                          // whole workgroup leaves together
@@ -206,6 +284,13 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
     __shared__ __attribute__((aligned(16))) char smem[V_BYTES > ACC_BYTES ? V_BYTES : ACC_BYTES];
     __shared__ float sm_m[NW * ROWS], sm_l[NW * ROWS];
 
+    // shared unit: its users with their slot ranges, for the publishing and folding at the end
+    __shared__ int4 sm_users[SH ? kMaxSharedUsers : 1];
+    if (SH && tid < su->n_users) {
+        const int inst = su->users[tid].inst;
+        sm_users[tid] = make_int4(inst, su->users[tid].slot, insts[inst].sslot0, insts[inst].n_sslots);
+    }
+
     if (FR > 0 && wave >= NW) {
         if constexpr (FR > 0)
             projection_tasks<FR>(a, f, insts, kvh, (int)blockIdx.x * NW + (wave - NW), (int)gridDim.x * NW, lane);
@@ -221,11 +306,18 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
     for (int j = 0; j < MS; ++j) {
         const int m = min(m0 + 16 * j + c16, n_m - 1);
         const int r = m / G, g = m % G;
-        const int q_row = a.prefill ? q_row0 + r : q_row0;
+        int q_row = a.prefill ? q_row0 + r : q_row0;
+        if (SH) {           // the record's user list comes through scalar loads; pick this lane's
+#pragma unroll
+            for (int k = 0; k < kMaxSharedUsers; ++k) {
+                const int v = su->users[k].inst;
+                q_row = (r == k) ? v : q_row;
+            }
+        }
         const T* qp = reinterpret_cast<const T*>(a.q) + ((size_t)q_row * a.Hq + (size_t)kvh * G + g) * D;
 #pragma unroll
         for (int c = 0; c < 4; ++c) bq[j][c] = as_bf16x8(ldg16(qp + dim0(c)));
-        vis[j] = a.prefill ? r + 1 : tail_len;
+        vis[j] = (a.prefill && !SH) ? r + 1 : tail_len;
     }
 
     uint16_t* const vstrip = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * BLK * VSTR;
@@ -421,12 +513,29 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, FR > 0 ? 2 : 1) void at
         RowMap rm;
         const int m = m0 + i;
         const int r = m / G, g = m % G;
-        rm.slot_row = prefill ? r : 0;
+        rm.slot_row = (prefill && !SH) ? r : 0;
         rm.head = kvh * G + g;
         rm.q_row = prefill ? q_row0 + r : q_row0;
+        if (SH) { const int4 us = sm_users[r]; rm.q_row = us.x; rm.unit_slot = us.y; }
         return rm;
     };
-    if constexpr (FR == 0) {
+    if constexpr (SH) {
+        publish_partial<T, D, NT, NW, ROWS, ACCS>(a, sm_acc, sm_m, sm_l, n_m, map);
+        // arrival at the counter of every user of this unit
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        const int n_users = n_m / G;
+        if (tid < n_users) {
+            const int4 us = sm_users[tid];
+            const int prev = __hip_atomic_fetch_add(&a.counters[(us.x * a.Hkv + kvh) * a.rows], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sm_lastv[tid] = (prev == us.w - 1);
+            if (prev == us.w - 1)                       // ready for the next launch
+                __hip_atomic_store(&a.counters[(us.x * a.Hkv + kvh) * a.rows], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        merge_shared<G, NT>(a, sm_users, sm_lastv, n_users, kvh);
+    } else if constexpr (FR == 0) {
         finish_unit<T, D, NW, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
     } else {
         publish_partial<T, D, NT, NW, ROWS, ACCS>(a, sm_acc, sm_m, sm_l, G, map);
@@ -486,6 +595,14 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
         return f8 ? launch_v<G, 4, 2, 2, true>(a, tiles, s) : launch_v<G, 4, 2, 2>(a, tiles, s);
     }
     if (f8) return launch_v<G, 4, 1, 2, true>(a, 1, s);
+    if (a.shared) {
+        const KernelArgs k = make_kernel_args(a);
+        hipLaunchKernelGGL((attn_mfma_kernel<G, 4, 1, 2, 0, false, true>), dim3(a.n_units, a.Hkv, 1), dim3(4 * 64), 0, s, k, StepArgs{},
+                           reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
+                           reinterpret_cast<const Item*>(a.table + a.off_items),
+                           reinterpret_cast<const Unit*>(a.table + a.off_units));
+        return hipGetLastError();
+    }
     // decode: variant 9000 + 10 * (blocks in flight) + waves
     switch (a.variant % 100) {
         case 24: return launch_v<G, 4, 1, 2>(a, 1, s);
@@ -525,7 +642,7 @@ bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtyp
     // Measured: the single launch wins while every projection wave has one task (up to four
     // instances) at the 8B shape; at group size 8 with hidden 8192 (config 4) it is 3 % behind
     // the two launches (76.6 against 74.3 us per layer and step), so it stops at group size 4.
-    return attn_mfma_supported(a, dtype) && !a.prefill && a.variant == 0 && (m.Hd % 4096) == 0 &&
+    return attn_mfma_supported(a, dtype) && !a.prefill && !a.shared && a.variant == 0 && (m.Hd % 4096) == 0 &&
            a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4;
 }
 

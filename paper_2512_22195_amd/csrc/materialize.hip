@@ -287,7 +287,7 @@ __global__ void chunk_table_kernel(char* table, int n_tokens) {
     InstanceInfo in;
     in.pos_base = 0; in.tail_len = n_tokens; in.q_len = n_tokens; in.cu_q = 0;
     in.dunit0 = 0; in.n_dunits = 0; in.punit0 = 0; in.n_punits = 1;
-    in.pad[0] = in.pad[1] = in.pad[2] = 0;
+    in.sslot0 = 0; in.n_sslots = 0; in.pad = 0;
     Item it;
     it.base = 0; it.page_tokens = n_tokens; it.tok0 = 0; it.ntok = n_tokens;
     it.fmt = 0; it.scales16 = 0; it.pad = 0;

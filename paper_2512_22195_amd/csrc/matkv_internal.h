@@ -40,6 +40,20 @@ struct Unit {              // 64 bytes: the work of one workgroup = consecutive 
     Item first;            // copy of items[item0]: one fetch is enough to start streaming
 };
 
+// A shared decode unit (instances of a batch that retrieved the same chunk read it once): one
+// piece of one page, or one instance's tail, and the instances whose newest tokens attend to
+// it in this workgroup.  Every (unit, user) pair owns one partial slot of that user; an
+// instance's slots are consecutive (InstanceInfo::sslot0 .. + n_sslots).
+constexpr int kMaxSharedUsers = 16;             // rows of one matrix tile / smallest group size
+constexpr int kMaxSharedUnitsPerInstance = 64;  // table capacity per instance of max_batch
+
+struct SUnit {             // 208 bytes
+    Unit u;                // one item (u.first); u.inst names the instance of a tail unit
+    int32_t n_users;
+    int32_t pad[3];
+    struct { int32_t inst, slot; } users[kMaxSharedUsers];
+};
+
 struct InstanceInfo {      // 48 bytes
     int64_t pos_base;      // position of tail row 0
     int32_t tail_len;      // valid tail rows (advanced on the device)
@@ -47,7 +61,8 @@ struct InstanceInfo {      // 48 bytes
     int32_t cu_q;          // first row of this instance in the packed Q / O / hidden
     int32_t dunit0, n_dunits;   // decode units of this instance (global unit index, count)
     int32_t punit0, n_punits;   // prefill units
-    int32_t pad[3];
+    int32_t sslot0, n_sslots;   // shared decode partition: this instance's partial slots
+    int32_t pad;
 };
 
 struct TableHeader {       // 64 bytes
@@ -62,14 +77,15 @@ struct TableHeader {       // 64 bytes
 
 // Byte offsets of the table's sections, all derived from the configuration.
 struct TableLayout {
-    size_t off_inst, off_items, off_dunits, off_punits, bytes;
-    int max_items, max_dunits, max_punits;
+    size_t off_inst, off_items, off_dunits, off_punits, off_sunits, bytes;
+    int max_items, max_dunits, max_punits, max_sunits;
 };
 
 inline TableLayout table_layout(const matkv_config& c) {
     TableLayout L;
     // every unit boundary and every page boundary starts a new item, in both partitions
-    L.max_items = c.max_batch * (kMaxDecodeUnitsPerInstance + kMaxPrefillUnitsPerInstance + 2 * c.max_pages + 2);
+    // (and once more for the private runs of the shared decode partition)
+    L.max_items = c.max_batch * (kMaxDecodeUnitsPerInstance + kMaxPrefillUnitsPerInstance + kMaxDecodeUnitsPerInstance / 2 + 3 * c.max_pages + 4);
     L.max_dunits = c.max_batch * kMaxDecodeUnitsPerInstance;
     L.max_punits = c.max_batch * kMaxPrefillUnitsPerInstance;
     size_t o = sizeof(TableHeader);
@@ -78,6 +94,8 @@ inline TableLayout table_layout(const matkv_config& c) {
     L.off_items = o;  o += sizeof(Item) * (size_t)L.max_items;
     L.off_dunits = o; o += sizeof(Unit) * (size_t)L.max_dunits;
     L.off_punits = o; o += sizeof(Unit) * (size_t)L.max_punits;
+    L.max_sunits = c.max_batch * (kMaxSharedUnitsPerInstance + 1);
+    L.off_sunits = o; o += sizeof(SUnit) * (size_t)L.max_sunits;
     L.bytes = (o + 255) & ~(size_t)255;
     return L;
 }
@@ -140,6 +158,7 @@ struct AttnArgs {
                                // 2: as 1 for a chunk's own attention (longest row tiles first)
     float scale_log2e;
     int32_t kv_fmt;            // matkv_page_format of every page of the table
+    int32_t shared;            // decode over the shared partition (units = SUnit records)
     int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
                                // waves * 100 + loads in flight = plain-ALU kernel
     size_t off_inst, off_items, off_units;

@@ -166,8 +166,9 @@ def load_blobs(ctx, case: Case, blobs: dict):
     return slots, keep
 
 
-def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=None, proj=None):
-    """Returns (prefill O [n_layers, total_q, Hq, D], decode O [steps, n_layers, B, Hq, D]) as CPU tensors."""
+def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=None, proj=None, info=None):
+    """Returns (prefill O [n_layers, total_q, Hq, D], decode O [steps, n_layers, B, Hq, D]) as CPU tensors.
+    info: a dict that receives what the table reports about itself (shared_units)."""
     c = case
     own = ctx is None
     ctx = ctx or make_context(c, device)
@@ -180,6 +181,8 @@ def run_gpu_attention(case: Case, inp, device="cuda:0", use_graph=False, ctx=Non
             table = ctx.new_table()
             pages = pages_of(c, slots)
             ctx.assemble(pages, c.q_lens, table)
+            if info is not None:
+                info["shared_units"] = ctx.table_shared_units(table)
             o_pre = torch.full_like(q_pre, float("nan"))
             o_dec = torch.full_like(q_dec, float("nan"))
             for l in range(c.n_layers):

@@ -828,3 +828,51 @@ def test_config2_full_size_compressed_sampled():
     pre, dec = chain.run_oracle_attention(case, inp, layers=[0, 31], steps=[0, 5], prefill_rows=[0, 17, 40, 63], proj=proj)
     chain.compare_attention(case, o_pre, o_dec, pre, dec)
     assert torch.isfinite(o_dec.float()).all() and torch.isfinite(o_pre.float()).all()
+
+
+# ------------------------------------------------- decode over pages that instances share ---
+@pytest.mark.parametrize("name,Hq,Hkv,batch,use_graph", [
+    ("g4", 8, 2, 6, False),      # 4 users per tile: the hot page needs two groups
+    ("g1", 2, 2, 21, False),     # 16 users per tile, 21 users of the hot page
+    ("g8", 16, 2, 6, True),      # 2 users per tile
+    ("g2", 4, 2, 9, False),
+])
+def test_decode_over_shared_pages(name, Hq, Hkv, batch, use_graph):
+    """Requests of one batch that retrieved the same chunks (the paper's access-skew argument,
+    Section II-C): the decode attention runs over the shared partition - every distinct page is
+    read once per group of users - and every instance still gets exact attention over its own
+    cache: one hot chunk used by everybody, chunks used by two or three, private chunks, an
+    instance without pages, ragged lengths, different question lengths."""
+    lens = {0: 700, 1: 333, 2: 64, 3: 129, 4: 1000, 5: 17}
+    pool = [[0, 1], [0], [2, 0, 3], [0, 4], [], [3, 0], [0, 5, 1], [4, 0], [0, 2]]
+    retrieved = [pool[i % len(pool)] if i != 4 else [] for i in range(batch)]
+    case = Case(f"shared-{name}", n_layers=2, Hq=Hq, Hkv=Hkv, D=128, hidden=256, dtype="bf16",
+                chunk_lens=lens, retrieved=retrieved, q_lens=[1 + (5 * i) % 23 for i in range(batch)],
+                steps=3, scale=1.0, q_scale=1.0)
+    inp = chain.make_attention_inputs(case)
+    info = {}
+    o_pre, o_dec = chain.run_gpu_attention(case, inp, use_graph=use_graph, info=info)
+    assert info["shared_units"] > batch, info                 # the shared partition was built and holds page units
+    pre, dec = chain.run_oracle_attention(case, inp)
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+
+
+def test_shared_partition_is_built_only_where_it_applies():
+    from paper_2512_22195_amd import binding as mk
+    def units(case, pages_fn):
+        ctx = chain.make_context(case)
+        try:
+            slots = {cid: ctx.new_slot(n) for cid, n in case.chunk_lens.items()}
+            table = ctx.new_table()
+            ctx.assemble(pages_fn(slots), case.q_lens, table)
+            return ctx.table_shared_units(table)
+        finally:
+            ctx.close()
+    base = dict(n_layers=1, Hq=8, Hkv=2, D=128, hidden=256, dtype="bf16", chunk_lens={0: 300, 1: 40},
+                retrieved=[[0, 1], [0], [0]], q_lens=[3, 4, 2], steps=1)
+    shared = lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], [(s[0], 300)]]
+    assert units(Case("sh-yes", **base), shared) == 4      # the shared page; instance 0's private page + tail; two more tails
+    assert units(Case("sh-private", **base), lambda s: [[(s[0], 300)], [(s[1], 40)], []]) == 0  # nothing shared
+    assert units(Case("sh-little", **base), lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], []]) == 0   # 340 of 640 page tokens distinct
+    assert units(Case("sh-units", **{**base, "decode_units": 2}), shared) == 0                  # explicit partition
+    assert units(Case("sh-f32", **{**base, "dtype": "f32", "D": 64}), shared) == 0              # other kernels
