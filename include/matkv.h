@@ -203,7 +203,8 @@ matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int
  * stream keeps running; the ticket then behaves as matkv_load's.  A descriptor opened with
  * O_DIRECT needs offset and bytes to be multiples of the device's block size (4096 is safe; a
  * blob of a multiple of 8 tokens is a multiple of 4096 at head_dim 128); where the system cannot
- * do direct I/O into pinned GPU-visible memory the pieces pass through one more host copy.  On MATKV_EIO (read
+ * do direct I/O into pinned GPU-visible memory the pieces pass through one more host copy
+ * (read by a helper thread of this call, so that reading and copying overlap).  On MATKV_EIO (read
  * error, file shorter than the blob) no ticket is issued and part of the slot may have been
  * overwritten.  Other errors as matkv_load. */
 matkv_status matkv_load_file(matkv_ctx* ctx, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,

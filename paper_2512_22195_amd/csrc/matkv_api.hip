@@ -10,7 +10,10 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <condition_variable>
+#include <mutex>
 #include <new>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -84,6 +87,7 @@ struct matkv_ctx {
     Staging bounce[kBounceRing];              // allocated at the first matkv_load_file
     int bounce_next = 0;
     char* plain_buf = nullptr;                // see matkv_load_file: direct reads that cannot target pinned memory
+    char* plain_buf2 = nullptr;               // second one: a reader thread fills one while the other is copied out
     bool read_via_plain = false;
     hipEvent_t fence_ev = nullptr;
     hipEvent_t release_ev[kReleaseRing] = {};
@@ -525,6 +529,7 @@ matkv_status matkv_destroy(matkv_ctx* c) {
         if (c->bounce[i].host) (void)hipHostFree(c->bounce[i].host);
     }
     free(c->plain_buf);
+    free(c->plain_buf2);
     for (int i = 0; i < kReleaseRing; ++i)
         if (c->release_ev[i]) (void)hipEventDestroy(c->release_ev[i]);
     if (c->fence_ev) (void)hipEventDestroy(c->fence_ev);
@@ -674,6 +679,83 @@ matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32
     return load_finish(c, t, device_slot, out);
 }
 
+// File -> two plain page-aligned buffers (a reader thread, one pread per piece) -> pinned bounce
+// ring (this thread's memcpy) -> load stream.  Used where direct I/O cannot target the pinned
+// buffers: the file read of piece k+1 then overlaps the host copy and the enqueue of piece k.
+static matkv_status load_file_via_plain(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, char* device_dst) {
+    if (!c->plain_buf2 && posix_memalign(reinterpret_cast<void**>(&c->plain_buf2), 4096, kBounceBytes) != 0) {
+        c->plain_buf2 = nullptr;
+        return fail(c, MATKV_ENOMEM, "load_file: out of host memory");
+    }
+    char* plain[2] = {c->plain_buf, c->plain_buf2};
+    const size_t n_pieces = (bytes + kBounceBytes - 1) / kBounceBytes;
+    auto piece_bytes = [&](size_t k) { return std::min(kBounceBytes, bytes - k * kBounceBytes); };
+    std::mutex mu;
+    std::condition_variable cv;
+    bool full[2] = {false, false};
+    bool stop = false;
+    int read_errno = 0;            // > 0: pread failed; -1: file ended early
+    uint64_t bad_at = 0;
+    std::thread reader([&] {
+        for (size_t k = 0; k < n_pieces; ++k) {
+            {
+                std::unique_lock<std::mutex> lk(mu);
+                cv.wait(lk, [&] { return !full[k & 1] || stop; });
+                if (stop) return;
+            }
+            const size_t piece = piece_bytes(k);
+            size_t got = 0;
+            int err = 0;
+            while (got < piece) {
+                ssize_t r = pread(fd, plain[k & 1] + got, piece - got, (off_t)(offset + k * kBounceBytes + got));
+                if (r < 0 && errno == EINTR) continue;
+                if (r <= 0) { err = r < 0 ? errno : -1; break; }
+                got += (size_t)r;
+            }
+            std::lock_guard<std::mutex> lk(mu);
+            if (err) { read_errno = err; bad_at = offset + k * kBounceBytes + got; stop = true; cv.notify_all(); return; }
+            full[k & 1] = true;
+            cv.notify_all();
+        }
+    });
+    matkv_status st = MATKV_OK;
+    hipError_t he = hipSuccess;
+    for (size_t k = 0; k < n_pieces && st == MATKV_OK; ++k) {
+        {
+            std::unique_lock<std::mutex> lk(mu);
+            cv.wait(lk, [&] { return full[k & 1] || stop; });
+            if (!full[k & 1]) break;                   // the reader gave up
+        }
+        Staging& b = c->bounce[c->bounce_next];
+        c->bounce_next = (c->bounce_next + 1) % kBounceRing;
+        if (b.used) he = hipEventSynchronize(b.ev);
+        const size_t piece = piece_bytes(k);
+        if (he == hipSuccess) {
+            memcpy(b.host, plain[k & 1], piece);
+            he = hipMemcpyAsync(device_dst + k * kBounceBytes, b.host, piece, hipMemcpyHostToDevice, c->load);
+        }
+        if (he == hipSuccess) he = hipEventRecord(b.ev, c->load);
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            full[k & 1] = false;
+            if (he != hipSuccess) stop = true;
+            cv.notify_all();
+        }
+        if (he != hipSuccess) break;
+        b.used = true;
+    }
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        stop = true;
+        cv.notify_all();
+    }
+    reader.join();
+    if (he != hipSuccess) return hip_fail(c, he, "load_file: copy of a piece");
+    if (read_errno > 0) return fail(c, MATKV_EIO, "load_file: pread at %llu: %s", (unsigned long long)bad_at, strerror(read_errno));
+    if (read_errno < 0) return fail(c, MATKV_EIO, "load_file: file ends %llu bytes short of the blob", (unsigned long long)(offset + bytes - bad_at));
+    return st;
+}
+
 matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
                              void* device_slot, size_t slot_bytes, matkv_ticket* out) {
     matkv_status st = precheck(c);
@@ -691,6 +773,11 @@ matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes
     // piece k+1 is read from the file while the copies of the pieces before it are in flight
     size_t done = 0;
     while (done < bytes) {
+        if (c->read_via_plain) {
+            st = load_file_via_plain(c, fd, offset + done, bytes - done, static_cast<char*>(device_slot) + done);
+            if (st != MATKV_OK) return st;
+            break;
+        }
         Staging& b = c->bounce[c->bounce_next];
         c->bounce_next = (c->bounce_next + 1) % kBounceRing;
         if (b.used) HIP_TRY(c, hipEventSynchronize(b.ev));
