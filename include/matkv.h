@@ -295,7 +295,12 @@ matkv_status matkv_probe_read(matkv_ctx* ctx, const void* src, size_t bytes);
 /* Between begin and end, calls to materialize_tail / advance / prefill_attn / decode_attn /
  * decode_step are recorded from the compute stream instead of executed.  Captured work reads tail
  * lengths and positions from the table on the device, so one recording of a decode step
- * serves every step. */
+ * serves every step.  Launch shapes are fixed at recording time: a table may be re-assembled
+ * between replays (other slots, other chunk and question lengths), but if the new batch is cut
+ * differently where the recording looks - for recorded decode calls another number of
+ * instances or decode units or another page format, for recorded prefill calls also another
+ * number of question rows - matkv_graph_launch returns MATKV_EINVAL and the calls have to be
+ * recorded again. */
 matkv_status matkv_graph_begin(matkv_ctx* ctx);
 matkv_status matkv_graph_end(matkv_ctx* ctx, matkv_graph** out);
 matkv_status matkv_graph_launch(matkv_ctx* ctx, matkv_graph* g);

@@ -49,6 +49,7 @@ struct TableHost {
     int max_punit_items = 0;  // most items of any one prefill unit
     int kv_fmt = 0;           // matkv_page_format of its pages
     int n_sunits = 0;         // units of the shared decode partition; 0 = the batch shares no page
+    uint64_t sig_decode = 0, sig_prefill = 0;   // of what a recorded decode / prefill launch bakes in
     int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
     int min_tail_len = 0;
     std::vector<const void*> slots;   // distinct slots its pages point into
@@ -66,6 +67,8 @@ struct matkv_graph {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
     std::vector<std::pair<void*, int>> advances;   // (table, n) recorded during capture
+    struct TableUse { const void* table; bool decode, prefill; uint64_t sig_decode, sig_prefill; };
+    std::vector<TableUse> tables;                  // every table the recording reads, with its partition signatures
 };
 
 struct matkv_ctx {
@@ -399,6 +402,24 @@ TableHost* find_table(matkv_ctx* c, const void* t) {
     return it == c->tables.end() ? nullptr : &it->second;
 }
 
+// Launch shapes and kernel choices are fixed when a call is recorded; they follow from these.
+uint64_t fnv(std::initializer_list<int> f) {
+    uint64_t h = 1469598103934665603ull;
+    for (int v : f) { h ^= (uint64_t)(uint32_t)v; h *= 1099511628211ull; }
+    return h;
+}
+void sign_partition(TableHost& th) {
+    th.sig_decode = fnv({th.batch, th.n_dunits, th.n_sunits, th.kv_fmt});
+    th.sig_prefill = fnv({th.batch, th.n_punits, th.total_q, th.max_q, th.max_punits_inst, th.max_punit_items, th.kv_fmt});
+}
+// While a graph is being recorded: remember that it reads this table's decode or prefill side.
+void note_table_use(matkv_ctx* c, const void* table, const TableHost& th, bool prefill) {
+    if (!c->capturing || !c->cap) return;
+    for (auto& e : c->cap->tables)
+        if (e.table == table) { (prefill ? e.prefill : e.decode) = true; return; }
+    c->cap->tables.push_back({table, !prefill, prefill, th.sig_decode, th.sig_prefill});
+}
+
 matkv_status precheck(matkv_ctx* c) {
     if (!c) return MATKV_EINVAL;
     if (c->sticky_hip) return MATKV_EHIP;
@@ -593,6 +614,7 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
     TableHost* th = find_table(c, table);
     if (!th) return fail(c, MATKV_EINVAL, "materialize_tail: table was not built by matkv_assemble");
     if (rows_per_instance == 0) return fail(c, MATKV_EINVAL, "materialize_tail: rows_per_instance is 0");
+    note_table_use(c, table, *th, rows_per_instance < 0);
     if (rows_per_instance > 0 && rows_per_instance > th->min_tail_len)
         return fail(c, MATKV_EINVAL, "materialize_tail: %d newest rows but a tail holds only %d",
                     rows_per_instance, th->min_tail_len);
@@ -1036,6 +1058,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
 
     th.batch = batch; th.n_items = n_items; th.n_dunits = n_dunits; th.n_punits = n_punits;
     th.total_q = cu; th.max_q = max_q; th.kv_fmt = kv_fmt; th.n_sunits = n_sunits;
+    sign_partition(th);
     // Slot bookkeeping: the table's old contents are dead from here on in stream order, so the
     // slots only they pointed into may be overwritten once the work enqueued so far is done.
     for (int b = 0; b < batch; ++b) {
@@ -1103,6 +1126,7 @@ matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
     TableHost* th = find_table(c, table);
     if (!th) return fail(c, MATKV_EINVAL, "advance: table was not built by matkv_assemble");
     if (n < 1) return fail(c, MATKV_EINVAL, "advance: n=%d", n);
+    note_table_use(c, table, *th, false);
     if (c->capturing) {
         c->cap->advances.emplace_back(table, n);
     } else {
@@ -1126,6 +1150,7 @@ static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32
     if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MATKV_EINVAL, "%s: layer %d outside 0..%d", name, layer, c->cfg.n_layers - 1);
     TableHost* th = find_table(c, table);
     if (!th) return fail(c, MATKV_EINVAL, "%s: table was not built by matkv_assemble", name);
+    note_table_use(c, table, *th, prefill != 0);
     AttnArgs a{};
     a.q = q; a.out = out; a.tail_k = tail_k; a.tail_v = tail_v;
     a.table = reinterpret_cast<const char*>(table);
@@ -1290,6 +1315,13 @@ matkv_status matkv_graph_launch(matkv_ctx* c, matkv_graph* g) {
     if (st != MATKV_OK) return st;
     if (!g || !g->exec) return fail(c, MATKV_EINVAL, "graph_launch: null graph");
     if (c->capturing) return fail(c, MATKV_EBUSY, "graph_launch: a capture is open");
+    // the tables must still be cut the way they were when the calls were recorded
+    for (auto& e : g->tables) {
+        TableHost* th = find_table(c, e.table);
+        if (!th) return fail(c, MATKV_EINVAL, "graph_launch: a recorded table no longer exists");
+        if ((e.decode && th->sig_decode != e.sig_decode) || (e.prefill && th->sig_prefill != e.sig_prefill))
+            return fail(c, MATKV_EINVAL, "graph_launch: a table has been re-assembled into a different partition since the recording");
+    }
     // the recorded tail advances must still fit
     for (auto& adv : g->advances) {
         TableHost* th = find_table(c, adv.first);

@@ -876,3 +876,41 @@ def test_shared_partition_is_built_only_where_it_applies():
     assert units(Case("sh-little", **base), lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], []]) == 0   # 340 of 640 page tokens distinct
     assert units(Case("sh-units", **{**base, "decode_units": 2}), shared) == 0                  # explicit partition
     assert units(Case("sh-f32", **{**base, "dtype": "f32", "D": 64}), shared) == 0              # other kernels
+
+
+def test_graph_refuses_a_table_cut_differently():
+    """A recorded decode step bakes in the launch shape of its table: replaying it after the
+    table was re-assembled with the same shape works (and reads the new contents), after a
+    re-assembly into another partition it is refused."""
+    from paper_2512_22195_amd import binding as mk
+    case = Case("graph-sig", n_layers=1, Hq=8, Hkv=2, D=128, hidden=256, dtype="bf16",
+                chunk_lens={0: 300, 1: 520}, retrieved=[[0], [1]], q_lens=[3, 5], steps=4)
+    ctx = chain.make_context(case)
+    try:
+        with torch.cuda.stream(ctx.compute_stream):
+            s0, s1 = ctx.new_slot(300), ctx.new_slot(520)
+            s0.zero_(); s1.zero_()
+            table, tail = ctx.new_table(), ctx.new_tail()
+            tail.zero_()
+            q = torch.zeros((2, 8, 128), dtype=torch.bfloat16, device="cuda")
+            o = torch.ones_like(q)
+            ctx.assemble([[(s0, 300)], [(s1, 520)]], [3, 5], table)
+            ctx.graph_begin()
+            ctx.advance(table, 1)
+            ctx.decode_attn(0, q, table, tail[0, 0], tail[0, 1], o)
+            g = ctx.graph_end()
+            ctx.graph_launch(g)
+            ctx.assemble([[(s1, 520)], [(s0, 300)]], [2, 4], table)          # same partition, other contents
+            ctx.graph_launch(g)
+            ctx.compute_stream.synchronize()
+            assert (o == 0).all()                                            # zero V: zero output
+            ctx.assemble([[(s0, 300)]], [3], table)                          # one instance instead of two
+            with pytest.raises(mk.MatKVError) as e:
+                ctx.graph_launch(g)
+            assert e.value.status == mk.EINVAL
+            ctx.assemble([[(s0, 300)], [(s1, 520)]], [3, 5], table)
+            ctx.graph_launch(g)
+            ctx.compute_stream.synchronize()
+            ctx.graph_destroy(g)
+    finally:
+        ctx.close()
