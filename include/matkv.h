@@ -83,7 +83,9 @@ typedef struct {
     int32_t max_pages;        /* chunks per instance */
     int32_t max_tail_tokens;  /* question + generated tokens per instance, multiple of 8 */
     int32_t decode_units;     /* decode workgroups per (instance, KV head); 0 = chosen per table */
-    int32_t decode_variant;   /* decode kernel shape; 0 = default (see the design doc for the codes) */
+    int32_t decode_variant;   /* decode kernel shape; 0 = default.  9000 + 10 * (blocks of loads in flight)
+                               * + waves = matrix-core kernel (9024, 9034, 9028, 9022 are built);
+                               * 100 * waves + loads in flight = plain-ALU kernel (402 .. 108) */
 } matkv_config;
 
 /* One loaded chunk: the device slot that holds its blob and its token count (host struct). */

@@ -1,6 +1,6 @@
 """GPU parity: libmatkv (through the C-ABI) against the fp64 oracle, element by element.
 
-Bars (written here, derived in the design doc): attention outputs max-abs <= 1e-5 (fp32 path) or
+Bars (written in tests/chain.py): attention outputs max-abs <= 1e-5 (fp32 path) or
 <= 1e-2 (bf16 inputs, fp32 accumulation), plus a gate relative to the rms of the oracle's
 output (1e-4 / 2e-2); stored K/V within half an ulp of the storage type plus fp32
 accumulation error of the unrounded fp64 value.
