@@ -72,7 +72,7 @@ typedef enum { MATKV_F32 = 0, MATKV_BF16 = 1 } matkv_dtype;
 
 typedef struct {
     int32_t n_layers;
-    int32_t n_q_heads;        /* Hq, multiple of n_kv_heads; Hq/Hkv in {1,2,4,8} */
+    int32_t n_q_heads;        /* Hq, multiple of n_kv_heads; Hq/Hkv in {1,2,3,4,8} */
     int32_t n_kv_heads;       /* Hkv */
     int32_t head_dim;         /* D in {64, 128} */
     int32_t hidden;           /* Hd, multiple of 64 */

@@ -620,7 +620,7 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
 
 bool attn_mfma_supported(const AttnArgs& a, int dtype) {
     const int g = a.Hq / a.Hkv;
-    return dtype == MATKV_BF16 && a.D == 128 && (g == 1 || g == 2 || g == 4 || g == 8);
+    return dtype == MATKV_BF16 && a.D == 128 && group_size_built(g);
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
@@ -629,6 +629,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
     switch (a.Hq / a.Hkv) {
         case 1: return launch_g<1>(a, s);
         case 2: return launch_g<2>(a, s);
+        case 3: return launch_g<3>(a, s);
         case 4: return launch_g<4>(a, s);
         case 8: return launch_g<8>(a, s);
     }
@@ -651,6 +652,7 @@ hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int d
     switch (a.Hq / a.Hkv) {
         case 1: return launch_step_g<1>(a, m, s);
         case 2: return launch_step_g<2>(a, m, s);
+        case 3: return launch_step_g<3>(a, m, s);
         case 4: return launch_step_g<4>(a, m, s);
         case 8: return launch_step_g<8>(a, m, s);
     }

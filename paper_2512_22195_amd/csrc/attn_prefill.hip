@@ -466,7 +466,7 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
 
 bool attn_prefill_supported(const AttnArgs& a, int dtype) {
     const int g = a.Hq / a.Hkv;
-    return a.prefill && dtype == MATKV_BF16 && a.D == 128 && (g == 1 || g == 2 || g == 4 || g == 8) &&
+    return a.prefill && dtype == MATKV_BF16 && a.D == 128 && group_size_built(g) &&
            a.max_unit_items <= kMaxPrefillItemsPerUnit;
 }
 
@@ -476,6 +476,7 @@ hipError_t launch_attn_prefill(const AttnArgs& a, int dtype, hipStream_t s) {
     switch (a.Hq / a.Hkv) {
         case 1: return launch_g<1>(a, s);
         case 2: return launch_g<2>(a, s);
+        case 3: return launch_g<3>(a, s);
         case 4: return launch_g<4>(a, s);
         case 8: return launch_g<8>(a, s);
     }

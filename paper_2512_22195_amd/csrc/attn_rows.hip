@@ -317,6 +317,7 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
     switch (a.Hq / a.Hkv) {
         case 1: return launch_t<T, D, 1>(a, s);
         case 2: return launch_t<T, D, 2>(a, s);
+        case 3: return launch_t<T, D, 3>(a, s);
         case 4: return launch_t<T, D, 4>(a, s);
         case 8: return launch_t<T, D, 8>(a, s);
     }

@@ -148,7 +148,7 @@ matkv_status check_config(const matkv_config* c, const char** why) {
     if (c->max_batch > 1024 || c->max_pages > 4096) { *why = "max_batch <= 1024, max_pages <= 4096"; return MATKV_EINVAL; }
     if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return MATKV_EUNSUPPORTED; }
     const int g = c->n_q_heads / c->n_kv_heads;
-    if (g != 1 && g != 2 && g != 4 && g != 8) { *why = "group size must be 1, 2, 4 or 8"; return MATKV_EUNSUPPORTED; }
+    if (!group_size_built(g)) { *why = "group size must be 1, 2, 3, 4 or 8"; return MATKV_EUNSUPPORTED; }
     return MATKV_OK;
 }
 
@@ -180,7 +180,7 @@ int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
 // The other kernels launch a workgroup per question row and want few units.
 int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long tokens) {
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
-    const bool mfma = cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && (g == 1 || g == 2 || g == 4 || g == 8);
+    const bool mfma = cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && group_size_built(g);
     long pu;
     if (mfma) {
         const long wgs_per_unit = std::max<long>(1, tiles_in_batch * cfg.n_kv_heads);
@@ -1040,7 +1040,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     const int grp = cfg.n_q_heads / cfg.n_kv_heads;
     int n_sunits = 0;
     if (batch >= 2 && pages && cfg.decode_units == 0 && cfg.decode_variant == 0 && kv_fmt == MATKV_PAGE_PLAIN &&
-        cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && (grp == 1 || grp == 2 || grp == 4 || grp == 8))
+        cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && group_size_built(grp))
         n_sunits = build_shared_units(cfg, pages, n_pages, batch, c->tl.max_sunits, c->tl.max_items, insts, items, &n_items,
                                       reinterpret_cast<SUnit*>(h + c->tl.off_sunits));
     hdr->batch = batch; hdr->n_items = n_items; hdr->n_dunits = n_dunits; hdr->n_punits = n_punits;

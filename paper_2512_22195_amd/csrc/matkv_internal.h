@@ -9,6 +9,9 @@
 
 namespace matkv {
 
+// Query heads per KV head the kernels are instantiated for (3: Llama-3.2-3B's 24 / 8).
+inline bool group_size_built(int g) { return g == 1 || g == 2 || g == 3 || g == 4 || g == 8; }
+
 // ---------------------------------------------------------------- cache table (device) ----
 // One table describes the assembled cache of a batch (paper Section IV, put_KV): for each
 // instance its pages cut into work items, then one item for its tail.  Built on the host by

@@ -914,3 +914,40 @@ def test_graph_refuses_a_table_cut_differently():
             ctx.graph_destroy(g)
     finally:
         ctx.close()
+
+
+# ------------------------------------------- three query heads per KV head (Llama-3.2-3B) ---
+@pytest.mark.parametrize("compressed,fused", [(False, False), (True, False), (False, True)])
+def test_group_of_three_chain(compressed, fused):
+    """The 3B model of the paper's model-size experiment has 24 query / 8 KV heads: full chain at
+    that grouping (6 / 2 heads here), hidden 3072 (two launches per decode step) or 4096 (one),
+    a batch in which two instances share a chunk, plain and compressed blobs."""
+    case = Case(f"g3-chain-{int(compressed)}{int(fused)}", n_layers=2, Hq=6, Hkv=2, D=128,
+                hidden=4096 if fused else 3072, dtype="bf16", chunk_lens={0: 150, 1: 333, 2: 40},
+                retrieved=[[0, 1], [1, 2], []], q_lens=[5, 47, 2], steps=3, rope_base=500000.0,
+                scale=1.0 / 8.0, q_scale=1.0, compressed=compressed)
+    _chain_parity(case, fused=fused)
+
+
+def test_group_of_three_shared_pages_and_chunk_attention():
+    case = Case("g3-shared", n_layers=1, Hq=6, Hkv=2, D=128, hidden=256, dtype="bf16",
+                chunk_lens={0: 500, 1: 77}, retrieved=[[0, 1], [0], [0], [1, 0], [0], [0], [0]],
+                q_lens=[3, 1, 9, 2, 5, 4, 1], steps=2, scale=1.0, q_scale=1.0)
+    inp = chain.make_attention_inputs(case)
+    info = {}
+    o_pre, o_dec = chain.run_gpu_attention(case, inp, info=info)
+    assert info["shared_units"] > 0                       # five users per tile: the hot page needs two groups
+    pre, dec = chain.run_oracle_attention(case, inp)
+    chain.compare_attention(case, o_pre, o_dec, pre, dec)
+    ccase = Case("g3-chunk", n_layers=1, Hq=6, Hkv=2, D=128, hidden=256, dtype="bf16",
+                 chunk_lens={0: 301}, retrieved=[[0]], q_lens=[1], steps=0, scale=1.0 / 4.0, q_scale=1.0)
+    cinp = chain.make_chain_inputs(ccase)
+    q_chunk = chain.make_chunk_queries(ccase)
+    _, outs = chain.run_gpu_chunk_prefill(ccase, cinp, q_chunk)
+    chain.compare_chunk_prefill(ccase, outs, chain.run_oracle_chunk_prefill(ccase, cinp, q_chunk))
+
+
+def test_group_of_three_fp32():
+    case = Case("g3-f32", n_layers=1, Hq=6, Hkv=2, D=64, hidden=128, dtype="f32",
+                chunk_lens={0: 90, 1: 33}, retrieved=[[0, 1], [1]], q_lens=[7, 3], steps=2, scale=0.5)
+    _attention_parity(case)
