@@ -318,7 +318,7 @@ def main():
             ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
 
     # does matkv_decode_step run as one kernel here?  (bf16, head_dim 128, hidden % 4096, default shape)
-    fused_kernel = (not args.unfused and shape.dtype == "bf16" and D == 128 and Hd % 4096 == 0
+    fused_kernel = (not args.unfused and shape.dtype == "bf16" and D == 128 and (Hd % 4096 == 0 or Hd % 3072 == 0)
                     and args.variant == 0 and B <= 4 and Hq // Hkv <= 4)
 
     # one decode step of all layers, recorded once, replayed for every step

@@ -130,7 +130,8 @@ __device__ __forceinline__ void projection_tasks(const KernelArgs& a, const Step
         const T* w1 = w0 + (size_t)(D / 2) * f.Hd;
         const T* x = reinterpret_cast<const T*>(f.hidden) + (size_t)b0 * f.Hd;
         float acc0[FR], acc1[FR];
-        gemv::pair_dots<FR>(w0, w1, x, (size_t)f.Hd, f.batch - b0, f.Hd, lane, acc0, acc1);
+        if (f.Hd % 4096 == 0) gemv::pair_dots<FR, 8>(w0, w1, x, (size_t)f.Hd, f.batch - b0, f.Hd, lane, acc0, acc1);
+        else                  gemv::pair_dots<FR, 6>(w0, w1, x, (size_t)f.Hd, f.batch - b0, f.Hd, lane, acc0, acc1);   // multiples of 3072
         if (lane < FR && b0 + lane < f.batch) {
             float r0 = 0.f, r1 = 0.f;
 #pragma unroll
@@ -643,7 +644,7 @@ bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtyp
     // Measured: the single launch wins while every projection wave has one task (up to four
     // instances) at the 8B shape; at group size 8 with hidden 8192 (config 4) it is 3 % behind
     // the two launches (76.6 against 74.3 us per layer and step), so it stops at group size 4.
-    return attn_mfma_supported(a, dtype) && !a.prefill && !a.shared && a.variant == 0 && (m.Hd % 4096) == 0 &&
+    return attn_mfma_supported(a, dtype) && !a.prefill && !a.shared && a.variant == 0 && ((m.Hd % 4096) == 0 || (m.Hd % 3072) == 0) &&
            a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4;
 }
 

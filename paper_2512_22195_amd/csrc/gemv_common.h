@@ -43,26 +43,27 @@ __device__ __forceinline__ float wave_sum(float v, int lane) {
 }
 
 // Dot products of R token rows (x + r * x_stride, rows past n_rows repeat the last) with the
-// two weight rows w0, w1 of one rotary pair; Hd a multiple of 4096.  All 16 weight loads of a
-// 4096-column pass are issued before anything is consumed.  Sums are complete in every lane.
-template <int R>
+// two weight rows w0, w1 of one rotary pair; Hd a multiple of 512 * NL (NL = 8: passes of 4096
+// columns; NL = 6: of 3072).  All 2 * NL weight loads of a pass are issued before anything is
+// consumed.  Sums are complete in every lane.
+template <int R, int NL = 8>
 __device__ __forceinline__ void pair_dots(const uint16_t* w0, const uint16_t* w1, const uint16_t* x, size_t x_stride,
                                           int n_rows, int Hd, int lane, float (&acc0)[R], float (&acc1)[R]) {
 #pragma unroll
     for (int r = 0; r < R; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
     w0 += lane * 8; w1 += lane * 8; x += lane * 8;
-    for (int c0 = 0; c0 < Hd; c0 += 4096) {
-        uint4 wa[8], wb[8], xv[R][8];
+    for (int c0 = 0; c0 < Hd; c0 += 512 * NL) {
+        uint4 wa[NL], wb[NL], xv[R][NL];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { wa[i] = ldg16(w0 + c0 + 512 * i); wb[i] = ldg16(w1 + c0 + 512 * i); }
+        for (int i = 0; i < NL; ++i) { wa[i] = ldg16(w0 + c0 + 512 * i); wb[i] = ldg16(w1 + c0 + 512 * i); }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const uint16_t* xr = x + (size_t)min(r, n_rows - 1) * x_stride + c0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) xv[r][i] = ldg16(xr + 512 * i);
+            for (int i = 0; i < NL; ++i) xv[r][i] = ldg16(xr + 512 * i);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < NL; ++i)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 acc0[r] = dot8(wa[i], xv[r][i], acc0[r]);

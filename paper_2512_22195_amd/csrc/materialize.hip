@@ -167,8 +167,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_rows_kernel(M
 }
 
 // ---- bf16 GEMV form: a handful of token rows (a decode step), hidden a multiple of 4096 ------
+// (NL = 8) or of 3072 (NL = 6: Llama-3.2-3B).
 // One wave per rotary pair, as above, but shaped for latency (see gemv_common.h).
-template <int R>
+template <int R, int NL>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(MaterializeArgs a) {
     typedef uint16_t T;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
     const T* x = reinterpret_cast<const T*>(a.hidden) + (size_t)row0 * a.Hd;
 
     float acc0[R], acc1[R];
-    gemv::pair_dots<R>(w0, w1, x, (size_t)a.Hd, a.n_tokens - row0, a.Hd, lane, acc0, acc1);
+    gemv::pair_dots<R, NL>(w0, w1, x, (size_t)a.Hd, a.n_tokens - row0, a.Hd, lane, acc0, acc1);
 
     if (lane < R) {
         float r0 = 0.f, r1 = 0.f;
@@ -206,16 +207,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(M
 constexpr int kGemmMinRows = 64;
 constexpr int kSkinnyMinRows = 32;
 
-bool gemv_supported(const MaterializeArgs& a, int dtype) { return dtype == MATKV_BF16 && (a.Hd % 4096) == 0; }
+bool gemv_supported(const MaterializeArgs& a, int dtype) {
+    return dtype == MATKV_BF16 && ((a.Hd % 4096) == 0 || (a.Hd % 3072) == 0);
+}
 
-hipError_t launch_gemv(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+template <int NL>
+hipError_t launch_gemv_nl(const MaterializeArgs& a, int total_rows, hipStream_t s) {
     const int n_tasks = 2 * a.Hkv * (a.D / 2);
     const int bx = (n_tasks + kWavesPerBlock - 1) / kWavesPerBlock;
     const dim3 block(kWavesPerBlock * 64);
-    if (total_rows == 1) hipLaunchKernelGGL((materialize_gemv_kernel<1>), dim3(bx, 1), block, 0, s, a);
-    else if (total_rows == 2) hipLaunchKernelGGL((materialize_gemv_kernel<2>), dim3(bx, 1), block, 0, s, a);
-    else hipLaunchKernelGGL((materialize_gemv_kernel<4>), dim3(bx, (total_rows + 3) / 4), block, 0, s, a);
+    if (total_rows == 1) hipLaunchKernelGGL((materialize_gemv_kernel<1, NL>), dim3(bx, 1), block, 0, s, a);
+    else if (total_rows == 2) hipLaunchKernelGGL((materialize_gemv_kernel<2, NL>), dim3(bx, 1), block, 0, s, a);
+    else hipLaunchKernelGGL((materialize_gemv_kernel<4, NL>), dim3(bx, (total_rows + 3) / 4), block, 0, s, a);
     return hipGetLastError();
+}
+hipError_t launch_gemv(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    return (a.Hd % 4096) == 0 ? launch_gemv_nl<8>(a, total_rows, s) : launch_gemv_nl<6>(a, total_rows, s);
 }
 
 __global__ void advance_kernel(char* table, size_t off_inst, int batch, int n, int max_tail) {

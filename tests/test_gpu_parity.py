@@ -167,6 +167,31 @@ def test_materialize_row_count_forms_bf16(T):
         ctx.close()
 
 
+@pytest.mark.parametrize("hidden,T", [(3072, 1), (3072, 3), (3072, 9), (6144, 2), (3072, 40), (3072, 300), (4096, 7)])
+def test_materialize_hidden_sizes_bf16(hidden, T):
+    """Hidden sizes of the paper's models beside 4096 and 8192: 3072 (the 3B model; passes of
+    six loads in the GEMV form) and a multiple of it, at row counts that take the GEMV form, the
+    skinny form and the tiled GEMM."""
+    case = Case(f"bf16-hidden-{hidden}", n_layers=1, Hq=6, Hkv=2, D=128, hidden=hidden, dtype="bf16",
+                chunk_lens={0: 8}, retrieved=[[0]], q_lens=[1], steps=0, rope_base=500000.0, scale=1.0 / 8.0)
+    from workload import normal, to_f64
+    import oracle
+    ctx = chain.make_context(case)
+    try:
+        with torch.cuda.stream(ctx.compute_stream):
+            w = normal(("hidden", hidden, "w"), (2, 2 * 128, hidden), 1.0 / 8.0, torch.bfloat16).cuda()
+            x = normal(("hidden", hidden, "x", T), (T, hidden), 1.0 / 8.0, torch.bfloat16).cuda()
+            k = torch.zeros((2, T, 128), dtype=torch.bfloat16, device="cuda")
+            v = torch.zeros_like(k)
+            ctx.materialize(x, w[0], w[1], T, 77, k, v, T)
+            ctx.compute_stream.synchronize()
+        K, V = oracle.materialize(to_f64(x), to_f64(w[0]), to_f64(w[1]), 2, 128, 77.0, 500000.0)
+        chain.compare_materialized(case, k.cpu(), K, f"K, hidden {hidden}, {T} rows")
+        chain.compare_materialized(case, v.cpu(), V, f"V, hidden {hidden}, {T} rows")
+    finally:
+        ctx.close()
+
+
 def test_bf16_chain_batch17_decode_rows_on_matrix_cores():
     """Seventeen instances: the decode-token projection has 17 rows (skinny form, ragged second
     16-row block), the question projection 17 ragged groups of rows."""
@@ -917,13 +942,14 @@ def test_graph_refuses_a_table_cut_differently():
 
 
 # ------------------------------------------- three query heads per KV head (Llama-3.2-3B) ---
-@pytest.mark.parametrize("compressed,fused", [(False, False), (True, False), (False, True)])
-def test_group_of_three_chain(compressed, fused):
-    """The 3B model of the paper's model-size experiment has 24 query / 8 KV heads: full chain at
-    that grouping (6 / 2 heads here), hidden 3072 (two launches per decode step) or 4096 (one),
-    a batch in which two instances share a chunk, plain and compressed blobs."""
-    case = Case(f"g3-chain-{int(compressed)}{int(fused)}", n_layers=2, Hq=6, Hkv=2, D=128,
-                hidden=4096 if fused else 3072, dtype="bf16", chunk_lens={0: 150, 1: 333, 2: 40},
+@pytest.mark.parametrize("compressed,fused,hidden", [(False, False, 3072), (True, False, 3072), (False, True, 4096),
+                                                     (False, True, 3072), (True, True, 3072)])
+def test_group_of_three_chain(compressed, fused, hidden):
+    """The 3B model of the paper's model-size experiment has 24 query / 8 KV heads and hidden
+    size 3072: full chain at that grouping (6 / 2 heads here), decode steps as two launches or as
+    one, a batch in which two instances share a chunk, plain and compressed blobs."""
+    case = Case(f"g3-chain-{int(compressed)}{int(fused)}-{hidden}", n_layers=2, Hq=6, Hkv=2, D=128,
+                hidden=hidden, dtype="bf16", chunk_lens={0: 150, 1: 333, 2: 40},
                 retrieved=[[0, 1], [1, 2], []], q_lens=[5, 47, 2], steps=3, rope_base=500000.0,
                 scale=1.0 / 8.0, q_scale=1.0, compressed=compressed)
     _chain_parity(case, fused=fused)
