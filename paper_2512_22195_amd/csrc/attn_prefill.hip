@@ -2,9 +2,9 @@
 // time": row i of the question attends to every chunk key and to question keys j <= i).
 //
 // The M dimension is the flattened (question row, query head of one KV head) index.  A
-// workgroup owns a tile of 64*MS such rows and one work unit of the cache; its four waves split
-// the ROWS (16*MS each) and walk the unit's tokens TOGETHER, 64 at a time: each K/V block is
-// fetched from HBM once per workgroup with coalesced 16-byte loads into double-buffered LDS
+// workgroup owns a tile of NW*16*MS such rows (NW = 4 or 8 waves) and one work unit of the cache;
+// its waves split the ROWS (16*MS each) and walk the unit's tokens TOGETHER, 64 at a time: each
+// K/V block is fetched from HBM once per workgroup with coalesced 16-byte loads into double-buffered LDS
 // tiles and shared by all waves -
 //   S^T = K Q^T     A = K rows from the LDS tile (padded rows, conflict-free 16-byte reads),
 //                   B = Q held in registers
@@ -12,7 +12,7 @@
 //                   running maximum through register swaps
 //   O^T += V^T P^T  A = V through the transposing LDS read, B = P rounded to bf16
 // The next block's loads are in flight (in registers) while the current one is computed out of
-// LDS; two workgroups share a compute unit.
+// LDS; eight waves share a compute unit (two four-wave workgroups, or one of eight).
 // A wave owns its rows outright, so nothing is merged between waves.  An instance whose cache
 // is one unit gets its output rows straight from the registers; otherwise every unit leaves an
 // unnormalised partial (accumulator, running maximum, sum) per row and a second, chip-wide
@@ -33,7 +33,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 constexpr int D = 128;
 constexpr int KSTR = D + 8;         // bf16 per LDS row of the K tile
 constexpr int VSTR = D + 16;        // bf16 per LDS row of the V tile
-constexpr int NW = 4;
 constexpr float kLazyLog2 = 8.0f;     // slack of the running reference exponent, in powers of two
 
 __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
@@ -49,7 +48,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
 // maximum and its exponent factor instead of its scores; the V scale goes into the weights as
 // they are rounded to bf16 (exact: a power of two) and is taken out of the row sums by summing
 // with 1/scale instead of 1 - so the per-element work is the same as for plain pages.
-template <int G, int MS, int TB, bool F8>
+template <int G, int MS, int TB, bool F8, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         KernelArgs a, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
@@ -166,15 +165,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         return r;
     };
 
-    // cooperative staging: thread t moves rows t/16 + 16i (i < TB/16), columns 8*(t%16), of K and of V
+    // cooperative staging: thread t moves rows t/16 + RPP*i, columns 8*(t%16), of K and of V
+    constexpr int RPP = NW * 4;                         // rows the workgroup moves per pass
     const int st_row = tid >> 4, st_col = (tid & 15) * 8;
-    constexpr int SR = TB / 16;
+    constexpr int SR = TB / RPP;
     struct Stage { uint4 k[SR], v[SR]; };
     auto load_global = [&](const BlockRef<T>& r, Stage& g) {
         if (F8 && !r.is_tail) {      // the same number of loads, half as wide (see the loop below)
 #pragma unroll
             for (int i = 0; i < SR; ++i) {
-                const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
+                const size_t off = (size_t)min(r.t0 + st_row + RPP * i, r.tok_end - 1) * D + st_col;
                 const uint2 kw = ldg8(reinterpret_cast<const uint8_t*>(r.k) + off);
                 const uint2 vw = ldg8(reinterpret_cast<const uint8_t*>(r.v) + off);
                 g.k[i] = make_uint4(kw.x, kw.y, 0u, 0u);
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         }
 #pragma unroll
         for (int i = 0; i < SR; ++i) {
-            const size_t off = (size_t)min(r.t0 + st_row + 16 * i, r.tok_end - 1) * D + st_col;
+            const size_t off = (size_t)min(r.t0 + st_row + RPP * i, r.tok_end - 1) * D + st_col;
             g.k[i] = ldg16(r.k + off);
             g.v[i] = ldg16(r.v + off);
         }
@@ -199,8 +199,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
                 kw = e4m3x8_to_bf16x8(make_uint2(kw.x, kw.y));
                 vw = e4m3x8_to_bf16x8(make_uint2(vw.x, vw.y));
             }
-            *reinterpret_cast<uint4*>(kt + (st_row + 16 * i) * KSTR + st_col) = kw;
-            *reinterpret_cast<uint4*>(vt + (st_row + 16 * i) * VSTR + st_col) = vw;
+            *reinterpret_cast<uint4*>(kt + (st_row + RPP * i) * KSTR + st_col) = kw;
+            *reinterpret_cast<uint4*>(vt + (st_row + RPP * i) * VSTR + st_col) = vw;
         }
     };
 
@@ -434,12 +434,12 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ((size_t)q_row * a.Hq + head) * D + 4 * hl) = o;
 }
 
-template <int G, int MS, int TB, bool F8>
+template <int G, int MS, int TB, bool F8, int NW = 4>
 hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
     const int tiles = (a.rows * G + NW * 16 * MS - 1) / (NW * 16 * MS);
     dim3 grid(a.n_units, a.Hkv, tiles), block(NW * 64);
-    hipLaunchKernelGGL((attn_prefill_kernel<G, MS, TB, F8>), grid, block, 0, s, k,
+    hipLaunchKernelGGL((attn_prefill_kernel<G, MS, TB, F8, NW>), grid, block, 0, s, k,
                        reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                        reinterpret_cast<const Item*>(a.table + a.off_items),
                        reinterpret_cast<const Unit*>(a.table + a.off_units));
@@ -453,13 +453,26 @@ hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
 
 template <int G>
 hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
-    if (a.kv_fmt == MATKV_PAGE_E4M3) return a.rows * G <= 64 ? launch_v<G, 1, 64, true>(a, s) : launch_v<G, 2, 64, true>(a, s);
-    if (a.rows * G <= 64) return launch_v<G, 1, 64, false>(a, s);
-    // A chunk's own attention has one workgroup per (row tile, KV head) and the last tile walks
-    // the whole chunk: until 128-row tiles give every compute unit two workgroups, 64-row
-    // tiles do (1024 tokens, 8 KV heads: 31 us against 36 us; 4096 tokens: 269 against 210).
-    if (a.prefill == 2 && (long)((a.rows * G + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64, false>(a, s);
-    return launch_v<G, 2, 64, false>(a, s);
+    const long rg = (long)a.rows * G;                   // (row, head) rows of the longest question
+    if (a.prefill == 2) {
+        // A chunk's own attention has one workgroup per (row tile, KV head) and the last tile walks
+        // the whole chunk: until 128-row tiles give every compute unit two workgroups, 64-row
+        // tiles do (1024 tokens, 8 KV heads: 31 us against 36 us; 4096 tokens: 269 against 210).
+        if (rg <= 64 || ((rg + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64, false>(a, s);
+        return launch_v<G, 2, 64, false>(a, s);
+    }
+    // Up to 64 rows: one 16-row block per wave.  Up to 128: two.  Beyond: eight waves share the
+    // K/V tiles of a 256-row workgroup, which halves the reads of the cache per question row
+    // (config 3: 202 -> 187 us per layer, config 4: 418 -> 376 us; config 2, exactly 256 rows:
+    // 33.2 -> 32.3 us).
+    if (a.kv_fmt == MATKV_PAGE_E4M3) {
+        if (rg <= 64) return launch_v<G, 1, 64, true>(a, s);
+        if (rg <= 128) return launch_v<G, 2, 64, true>(a, s);
+        return launch_v<G, 2, 64, true, 8>(a, s);
+    }
+    if (rg <= 64) return launch_v<G, 1, 64, false>(a, s);
+    if (rg <= 128) return launch_v<G, 2, 64, false>(a, s);
+    return launch_v<G, 2, 64, false, 8>(a, s);
 }
 
 }  // namespace

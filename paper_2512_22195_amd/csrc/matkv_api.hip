@@ -170,19 +170,25 @@ int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
 }
 
 // Units one instance's cache is cut into for the question prefill.  The matrix-core kernel runs
-// one workgroup per (unit, KV head, 128-row tile); every extra unit costs a partial per question
-// row and a share of the fold launch.  So: as many units as it takes to give every compute unit
-// a workgroup (none shorter than 256 tokens), and twice that - two resident workgroups per
-// compute unit overlap each other's matrix and vector phases - only while a unit keeps at least
-// 4096 tokens to amortise its partial over.  Measured per layer: config 2 (16 workgroups
-// uncut) 33 us at 16 or 32 units; config 3 (320 uncut) 217 us uncut against 233 us in two
-// units; config 4 (256 uncut, 20 128 tokens) 569 us uncut against 432 us in two.
+// one workgroup per (unit, KV head, row tile); every extra unit costs a partial per question row
+// and a share of the fold launch.  Four-wave workgroups (128-row tiles, questions of up to 128
+// (row, head) rows): as many units as it takes to give every compute unit a workgroup (none
+// shorter than 256 tokens), and twice that - two resident workgroups per compute unit overlap
+// each other's matrix and vector phases - only while a unit keeps at least 4096 tokens to
+// amortise its partial over.  Eight-wave workgroups (256-row tiles): see below.
 // The other kernels launch a workgroup per question row and want few units.
-int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long tokens) {
+int choose_prefill_units(const matkv_config& cfg, long tiles_in_batch, long tile_rows, long tokens) {
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
     const bool mfma = cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && group_size_built(g);
     long pu;
-    if (mfma) {
+    if (mfma && tile_rows > 128) {
+        // eight-wave workgroups fill a compute unit alone: about 256 of them, and rather a few
+        // compute units idle than one more cut (config 3, 216 workgroups uncut: 187 us against
+        // 218 us in two units; config 4, 128 uncut: 376 us in two units against 414 us in four)
+        const long wgs_per_unit = std::max<long>(1, tiles_in_batch * cfg.n_kv_heads);
+        pu = (256 + wgs_per_unit / 2) / wgs_per_unit;
+        pu = std::max<long>(1, std::min<long>(pu, tokens / 256));
+    } else if (mfma) {
         const long wgs_per_unit = std::max<long>(1, tiles_in_batch * cfg.n_kv_heads);
         pu = (256 + wgs_per_unit - 1) / wgs_per_unit;
         pu = std::max<long>(1, std::min<long>(pu, tokens / 256));
@@ -1002,9 +1008,13 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     int n_items = 0, n_dunits = 0, n_punits = 0, cu = 0, max_q = 0;
     TableHost th;
     th.min_tail_len = cfg.max_tail_tokens;
-    long prefill_tiles = 0;            // 128-row tiles of (question row, query head of one KV head) over the batch
+    // row tiles of (question row, query head of one KV head) over the batch: the matrix-core prefill
+    // kernel takes 256-row workgroups once the longest question has more than 128 such rows
+    long prefill_tiles = 0, max_rg = 0;
+    for (int b = 0; b < batch; ++b) max_rg = std::max<long>(max_rg, (long)q_len[b] * (cfg.n_q_heads / cfg.n_kv_heads));
+    const long tile_rows = max_rg > 128 ? 256 : 128;
     for (int b = 0; b < batch; ++b)
-        prefill_tiles += ((long)q_len[b] * (cfg.n_q_heads / cfg.n_kv_heads) + 127) / 128;
+        prefill_tiles += ((long)q_len[b] * (cfg.n_q_heads / cfg.n_kv_heads) + tile_rows - 1) / tile_rows;
     for (int b = 0; b < batch; ++b) {
         InstanceInfo& in = insts[b];
         memset(&in, 0, sizeof(in));
@@ -1028,7 +1038,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
         in.n_dunits = build_units(pg, n_pages[b], b, choose_decode_units(cfg, batch, inst_tokens + tail_est),
                                   tail_est, cfg.max_tail_tokens, items, &n_items, dunits, &n_dunits, scales_off);
         // prefill: coarse partition (the question rows supply most of the parallelism)
-        const int pu = choose_prefill_units(cfg, prefill_tiles, inst_tokens + q_len[b]);
+        const int pu = choose_prefill_units(cfg, prefill_tiles, tile_rows, inst_tokens + q_len[b]);
         in.punit0 = n_punits;
         in.n_punits = build_units(pg, n_pages[b], b, pu, q_len[b], cfg.max_tail_tokens, items, &n_items,
                                   punits, &n_punits, scales_off);
