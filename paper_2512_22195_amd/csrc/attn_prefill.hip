@@ -458,6 +458,8 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
         // A chunk's own attention has one workgroup per (row tile, KV head) and the last tile walks
         // the whole chunk: until 128-row tiles give every compute unit two workgroups, 64-row
         // tiles do (1024 tokens, 8 KV heads: 31 us against 36 us; 4096 tokens: 269 against 210).
+        // (from 512 eight-wave workgroups on, 256-row tiles are a little ahead: 4096 tokens 188 against 196 us)
+        if (((rg + 255) / 256) * a.Hkv >= 512) return launch_v<G, 2, 64, false, 8>(a, s);
         if (rg <= 64 || ((rg + 127) / 128) * a.Hkv < 512) return launch_v<G, 1, 64, false>(a, s);
         return launch_v<G, 2, 64, false>(a, s);
     }
