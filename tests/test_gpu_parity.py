@@ -977,3 +977,14 @@ def test_group_of_three_fp32():
     case = Case("g3-f32", n_layers=1, Hq=6, Hkv=2, D=64, hidden=128, dtype="f32",
                 chunk_lens={0: 90, 1: 33}, retrieved=[[0, 1], [1]], q_lens=[7, 3], steps=2, scale=0.5)
     _attention_parity(case)
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_decode_step_over_shared_pages(use_graph):
+    """matkv_decode_step on a batch whose instances share their chunks: the table carries the
+    shared partition, so the step runs as projection + shared decode attention (two launches),
+    eagerly and recorded in a graph."""
+    case = Case(f"shared-step-{int(use_graph)}", n_layers=2, Hq=8, Hkv=2, D=128, hidden=4096, dtype="bf16",
+                chunk_lens={0: 400, 1: 90}, retrieved=[[0, 1], [0], [1, 0], [0]], q_lens=[4, 9, 1, 17],
+                steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case, fused=True, use_graph=use_graph)
