@@ -85,8 +85,16 @@ struct KernelArgs {
     float* __restrict__ partials;
     int32_t* __restrict__ counters;
     int32_t layer, Hq, Hkv, max_tail, rows, prefill;
+    int32_t cstride;             // ints between two arrival counters
     float scale_log2e;
 };
+
+// Arrival counter of (instance, KV head, row z).  Decode launches keep every counter on a
+// 128-byte line of its own: agent-scope atomics on one line are served one after the other, and
+// a launch's workgroups arrive within a microsecond or two of each other.
+__device__ __forceinline__ int counter_index(const KernelArgs& a, int inst, int kvh, int z) {
+    return ((inst * a.Hkv + kvh) * a.rows + z) * a.cstride;
+}
 
 inline KernelArgs make_kernel_args(const AttnArgs& a) {
     KernelArgs k;
@@ -94,6 +102,7 @@ inline KernelArgs make_kernel_args(const AttnArgs& a) {
     k.partials = a.partials; k.counters = a.counters;
     k.layer = a.layer; k.Hq = a.Hq; k.Hkv = a.Hkv; k.max_tail = a.max_tail; k.rows = a.rows;
     k.prefill = a.prefill; k.scale_log2e = a.scale_log2e;
+    k.cstride = a.prefill ? 1 : kDecodeCounterStride;
     return k;
 }
 
@@ -369,7 +378,7 @@ template <typename T, int D, int NW, int NS, int ROWS, int ACC_STRIDE, typename 
 __device__ __forceinline__ void finish_unit(const KernelArgs& a, const Unit& unit, int kvh, int zidx,
                                             const float* sm_acc, const float* sm_m, const float* sm_l,
                                             int* sm_last, int n_valid_rows, MapFn map) {
-    const int cidx = ((unit.inst * a.Hkv) + kvh) * a.rows + zidx;
+    const int cidx = counter_index(a, unit.inst, kvh, zidx);
     if (!publish_unit<T, D, NW, NS, ROWS, ACC_STRIDE>(a, cidx, unit.n_units_inst, sm_acc, sm_m, sm_l, sm_last, n_valid_rows, map))
         return;
     merge_dispatch<T, D, NW * 64>(a, unit.unit0_inst, unit.n_units_inst, n_valid_rows * (D / 2), map);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "matkv.h"
 
 namespace matkv {
@@ -18,6 +20,7 @@ inline bool group_size_built(int g) { return g == 1 || g == 2 || g == 3 || g == 
 // matkv_assemble, read by the attention and tail-materialize kernels.
 
 constexpr int kMaxDecodeUnitsPerInstance = 256;
+constexpr int kDecodeCounterStride = 32;         // ints: decode arrival counters sit 128 bytes apart
 constexpr int kMaxPrefillUnitsPerInstance = 32;
 constexpr int kMaxPrefillItemsPerUnit = 64;      // item list the matrix-core prefill kernel keeps in LDS
 
@@ -122,7 +125,10 @@ inline WorkspaceLayout workspace_layout(const matkv_config& c) {
     W.off_rope = o;      o += 4096;   // D/2 entries of {double inv_freq; float hi, lo (turns)}
     W.off_chunk = o;     o += kChunkTableBytes;
     W.off_counters = o;
-    W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)max_q_rows(c);
+    // prefill: one per (instance, KV head, question row); decode: one per (instance, KV head), each
+    // on a 128-byte line of its own (the two kinds of launch never overlap, and every counter is
+    // back at zero when its launch ends)
+    W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)std::max(max_q_rows(c), kDecodeCounterStride);
     o += ((W.n_counters * sizeof(int32_t)) + 255) & ~(size_t)255;
     W.off_partials = o;
     size_t stride = (size_t)c.n_q_heads * (c.head_dim + 4);   // acc[D] + {m, l} (padded)
@@ -202,6 +208,7 @@ struct MaterializeArgs {
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s);
 bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows);
 hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s);
+int decode_step_form(const AttnArgs& a, const MaterializeArgs& m, int dtype);     // 0 none, 1 wave-, 2 block-specialised
 bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype);
 hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int dtype, hipStream_t s);   // projection + attention
 hipError_t launch_probe_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s);
