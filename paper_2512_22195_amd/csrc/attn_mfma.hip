@@ -52,8 +52,6 @@ struct StepArgs {
     const void* w_v;
     const RopeEntry* rope;
     int32_t Hd, batch;
-    int32_t dbg;
-    int32_t n_proj;             // block-specialised form: projection workgroups per KV head (the last of grid.x)
 };
 
 // Last arrival of a fused decode step at instance b, KV head kvh: folds the units' partials and
@@ -152,7 +150,6 @@ __device__ __forceinline__ void projection_tasks(const KernelArgs& a, const Step
 }
 
 constexpr int kFusedMaxBatch = 4;
-constexpr int kBlockFusedMaxBatch = 64;
 
 // Shared decode units: fold, for every user of this unit at whose counter the workgroup arrived
 // last, that instance's partial slots into its G output rows - all such users at once.  A thread
@@ -234,22 +231,15 @@ __device__ __forceinline__ void merge_shared(const KernelArgs& a, const int4* us
 // tile are (user, query head) pairs, the piece is streamed once for all of them, every user gets
 // its own partial, and the workgroup arrives at every user's counter: the last arrival at an
 // instance's counter folds that instance's partial slots.
-// BS (with FR > 0): the block-specialised fused step for larger batches - the projection runs in
-// workgroups of its own (the last f.n_proj of grid.x, four waves each) beside the attention
-// workgroups, which keep their usual shape and number per compute unit.  An attention workgroup
-// arrives at its own instance's counter only; a projection workgroup, once its rows are out,
-// at every instance's; the last arrival at a counter (units of the instance + projection
-// workgroups) folds that instance.
-template <int G, int NW, int MS, int PF, int FR, bool F8, bool SH = false, bool BS = false>
-__global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && PF <= 2)) ? 2 : 1) void attn_mfma_kernel(
+template <int G, int NW, int MS, int PF, int FR, bool F8, bool SH = false>
+__global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && PF <= 2)) ? 2 : 1) void attn_mfma_kernel(
         KernelArgs a, StepArgs f, const InstanceInfo* __restrict__ insts, const Item* __restrict__ items,
         const Unit* __restrict__ units) {
     constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
-    constexpr int NT = (FR > 0 && !BS ? 2 : 1) * NW * 64;   // threads of the workgroup
+    constexpr int NT = (FR > 0 ? 2 : 1) * NW * 64;      // threads of the workgroup
     typedef uint16_t T;
     static_assert(!SH || (FR == 0 && MS == 1 && !F8), "shared units: plain decode tiles only");
-    static_assert(!BS || (FR > 0 && !SH), "block-specialised: a fused step over the per-instance partition");
-    __shared__ int sm_last, sm_lastv[SH ? kMaxSharedUsers : (BS ? kBlockFusedMaxBatch : (FR > 0 ? kFusedMaxBatch : 1))];
+    __shared__ int sm_last, sm_lastv[SH ? kMaxSharedUsers : (FR > 0 ? kFusedMaxBatch : 1)];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -257,27 +247,8 @@ __global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS =
     const int kvh = blockIdx.y, tile = blockIdx.z;
     const int m0 = tile * ROWS;
 
-    if constexpr (BS) {
-        if ((int)blockIdx.x < f.n_proj) {               // a projection workgroup (they are dispatched first)
-            if (!(f.dbg & 1)) projection_tasks<FR>(a, f, insts, kvh, (int)blockIdx.x * NW + wave, f.n_proj * NW, lane);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            if (tid < f.batch) {
-                const int prev = __hip_atomic_fetch_add(&a.counters[counter_index(a, tid, kvh, 0)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                sm_lastv[tid] = (prev == insts[tid].n_dunits + f.n_proj - 1);
-            }
-            __syncthreads();
-            for (int b = 0; b < f.batch; ++b) {         // hardly ever: the attention units finish later
-                if (!sm_lastv[b]) continue;             // uniform
-                merge_decode_step<G, NT>(a, insts[b], b, kvh);
-                reset_counter(a, counter_index(a, b, kvh, 0));
-            }
-            return;
-        }
-    }
     const SUnit* const su = reinterpret_cast<const SUnit*>(units) + blockIdx.x;     // SH only
-    const Unit unit = SH ? su->u : units[BS ? blockIdx.x - f.n_proj : blockIdx.x];
+    const Unit unit = SH ? su->u : units[blockIdx.x];
 
     int n_m, q_row0, tail_len = 0, tail_visible;
     if (SH) {
@@ -321,8 +292,8 @@ __global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS =
         sm_users[tid] = make_int4(inst, su->users[tid].slot, insts[inst].sslot0, insts[inst].n_sslots);
     }
 
-    if (FR > 0 && !BS && wave >= NW) {
-        if constexpr (FR > 0 && !BS)
+    if (FR > 0 && wave >= NW) {
+        if constexpr (FR > 0)
             projection_tasks<FR>(a, f, insts, kvh, (int)blockIdx.x * NW + (wave - NW), (int)gridDim.x * NW, lane);
     } else {
     // Q in operand layout: lane (c16, g4) holds, for sub-tile j and chunk c of the head
@@ -500,7 +471,7 @@ __global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS =
     };
     if constexpr (!F8) {
         Walker<T, D, NW, BLK, 8> walk(a, unit, items, kvh, tail_visible, wave);
-        if (!(BS && (f.dbg & 2))) stream(walk, PlainBuf{}, issue_plain, consume_plain);
+        stream(walk, PlainBuf{}, issue_plain, consume_plain);
     } else {
         // Compressed pages first, then the (plain) tail, each in a loop of its own: one loop
         // over both kinds would put the two load patterns under a branch.
@@ -547,7 +518,6 @@ __global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS =
         rm.head = kvh * G + g;
         rm.q_row = prefill ? q_row0 + r : q_row0;
         if (SH) { const int4 us = sm_users[r]; rm.q_row = us.x; rm.unit_slot = us.y; }
-        if (BS) rm.unit_slot = (int)blockIdx.x - f.n_proj;      // partial slots are numbered by unit
         return rm;
     };
     if constexpr (SH) {
@@ -568,12 +538,6 @@ __global__ __launch_bounds__((FR > 0 && !BS ? 2 : 1) * NW * 64, (FR > 0 || (MS =
         merge_shared<G, NT>(a, sm_users, sm_lastv, n_users, kvh);
     } else if constexpr (FR == 0) {
         finish_unit<T, D, NW, NW, ROWS, ACCS>(a, unit, kvh, tile, sm_acc, sm_m, sm_l, &sm_last, min(ROWS, n_m - m0), map);
-    } else if constexpr (BS) {
-        const int cidx = counter_index(a, unit.inst, kvh, 0);
-        if (publish_unit<T, D, NW, NW, ROWS, ACCS>(a, cidx, unit.n_units_inst + f.n_proj, sm_acc, sm_m, sm_l, &sm_last, G, map)) {
-            merge_decode_step<G, NT>(a, insts[unit.inst], unit.inst, kvh);
-            reset_counter(a, cidx);
-        }
     } else {
         publish_partial<T, D, NT, NW, ROWS, ACCS>(a, sm_acc, sm_m, sm_l, G, map);
         // arrival at every instance's counter of this KV head
@@ -607,7 +571,7 @@ hipError_t launch_v(const AttnArgs& a, int tiles, hipStream_t s) {
 template <int G, int NW, int FR>
 hipError_t launch_step_v(const AttnArgs& a, const MaterializeArgs& m, hipStream_t s) {
     const KernelArgs k = make_kernel_args(a);
-    StepArgs f{};
+    StepArgs f;
     f.hidden = m.hidden; f.w_k = m.w_k; f.w_v = m.w_v; f.rope = m.rope;
     f.Hd = m.Hd; f.batch = a.batch;
     dim3 grid(a.n_units, a.Hkv, 1), block(2 * NW * 64);
@@ -619,31 +583,8 @@ hipError_t launch_step_v(const AttnArgs& a, const MaterializeArgs& m, hipStream_
     return hipGetLastError();
 }
 
-// Block-specialised form: attention units first, then n_proj projection workgroups per KV head.
-template <int G>
-hipError_t launch_step_blocks(const AttnArgs& a, const MaterializeArgs& m, hipStream_t s) {
-    const KernelArgs k = make_kernel_args(a);
-    StepArgs f{};
-    f.hidden = m.hidden; f.w_k = m.w_k; f.w_v = m.w_v; f.rope = m.rope;
-    f.Hd = m.Hd; f.batch = a.batch;
-    // one task = one rotary pair of K or of V for four instances; about four tasks per wave
-    const int tasks = ((a.batch + 3) / 4) * D;
-    f.n_proj = std::max(4, std::min(64, tasks / 16));
-    if (getenv("MATKV_DBG_NPROJ")) f.n_proj = atoi(getenv("MATKV_DBG_NPROJ"));
-    f.dbg = getenv("MATKV_DBG_BS") ? atoi(getenv("MATKV_DBG_BS")) : 0;
-    dim3 grid(a.n_units + f.n_proj, a.Hkv, 1), block(4 * 64);
-    auto kern = a.kv_fmt == MATKV_PAGE_E4M3 ? attn_mfma_kernel<G, 4, 1, 2, 4, true, false, true>
-                                             : attn_mfma_kernel<G, 4, 1, 2, 4, false, false, true>;
-    hipLaunchKernelGGL(kern, grid, block, 0, s, k, f,
-                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
-                       reinterpret_cast<const Item*>(a.table + a.off_items),
-                       reinterpret_cast<const Unit*>(a.table + a.off_units));
-    return hipGetLastError();
-}
-
 template <int G>
 hipError_t launch_step_g(const AttnArgs& a, const MaterializeArgs& m, hipStream_t s) {
-    if (decode_step_form(a, m, MATKV_BF16) == 2) return launch_step_blocks<G>(a, m, s);
     if constexpr (G <= 4) return a.batch == 1 ? launch_step_v<G, 4, 1>(a, m, s) : launch_step_v<G, 4, 4>(a, m, s);
     return hipErrorInvalidValue;
 }
@@ -699,20 +640,19 @@ hipError_t launch_attn_mfma(const AttnArgs& a, int dtype, hipStream_t s) {
 
 
 // Fused decode step: K/V projection of every instance's newest token and the decode attention
-// in one launch (default kernel shape only).  0 = not covered (two launches); 1 = projection
-// waves inside every attention workgroup; 2 = projection workgroups beside the attention
-// workgroups.
-int decode_step_form(const AttnArgs& a, const MaterializeArgs& m, int dtype) {
-    if (!attn_mfma_supported(a, dtype) || a.prefill || a.shared || a.variant != 0) return 0;
-    if ((m.Hd % 4096) != 0 && (m.Hd % 3072) != 0) return 0;
-    // Form 1, measured: ahead while every projection wave has one task (up to four instances) at
-    // the 8B shape; at group size 8 with hidden 8192 (config 4) 3 % behind the two launches (it
-    // halves the attention waves per compute unit), where form 2 takes over.
-    if (a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4) return 1;
-    if (a.batch >= 1 && a.batch <= kBlockFusedMaxBatch) return 2;
-    return 0;
+// in one launch (default kernel shape only).
+bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype) {
+    // Measured: the single launch wins while every projection wave has one task (up to four
+    // instances) at the 8B shape; at group size 8 with hidden 8192 (config 4) it is 3 % behind
+    // the two launches (it halves the attention waves per compute unit), so it stops at group
+    // size 4.  Projection workgroups of their own beside the attention workgroups (for larger
+    // batches) lose outright: the decode kernel wants exactly one attention workgroup per
+    // compute unit - a second resident workgroup of any kind on a compute unit stretches the
+    // launch by a third (batch 16: 57 us with 256 workgroups, 83 us with 264).
+    return attn_mfma_supported(a, dtype) && !a.prefill && !a.shared && a.variant == 0 &&
+           ((m.Hd % 4096) == 0 || (m.Hd % 3072) == 0) &&
+           a.batch >= 1 && a.batch <= kFusedMaxBatch && a.Hq / a.Hkv <= 4;
 }
-bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype) { return decode_step_form(a, m, dtype) != 0; }
 
 hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int dtype, hipStream_t s) {
     if (a.n_units <= 0 || !decode_step_supported(a, m, dtype)) return hipErrorInvalidValue;

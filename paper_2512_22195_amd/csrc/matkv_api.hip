@@ -154,13 +154,15 @@ matkv_status check_config(const matkv_config* c, const char** why) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Decode workgroups per (instance, KV head) when the configuration does not fix it: about one
-// workgroup per compute unit over the whole batch, each with at least 128 tokens to stream.
+// Decode workgroups per (instance, KV head) when the configuration does not fix it: one
+// workgroup per compute unit over the whole batch and never more than there are compute units
+// (a compute unit that holds two runs a third longer, and the launch ends with it: batch 3,
+// 8 KV heads: 240 workgroups 19.7 us, 264 workgroups 24.9 us), each with at least 128 tokens.
 int choose_decode_units(const matkv_config& c, int batch, long inst_tokens) {
     int u = c.decode_units;
     if (u <= 0) {
         const int per_head = batch * c.n_kv_heads;
-        u = (256 + per_head - 1) / per_head;
+        u = 256 / per_head;
         const long cap = inst_tokens / 128;
         if (u > cap) u = (int)cap;
     }
