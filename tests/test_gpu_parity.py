@@ -988,3 +988,30 @@ def test_decode_step_over_shared_pages(use_graph):
                 chunk_lens={0: 400, 1: 90}, retrieved=[[0, 1], [0], [1, 0], [0]], q_lens=[4, 9, 1, 17],
                 steps=3, rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
     _chain_parity(case, fused=True, use_graph=use_graph)
+
+
+# ------------------------------------------------------------- seeded random small chains ---
+@pytest.mark.parametrize("seed", list(range(14)))
+def test_random_small_chain(seed):
+    """A net under the hand-picked cases: the full chain on a seeded random draw of the shape
+    parameters (grouping, head_dim, dtype, hidden size, batch, chunk and question lengths,
+    decode steps, page reuse, compressed blobs, fused step, explicit partition)."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "bf16" if rng.random() < 0.75 else "f32"
+    D = 128 if (dtype == "bf16" and rng.random() < 0.8) else 64
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    hidden = int(rng.choice([64, 256, 512, 3072, 4096])) if dtype == "bf16" else int(rng.choice([64, 192]))
+    batch = int(rng.integers(1, 7))
+    n_chunks = int(rng.integers(1, 5))
+    lens = {c: int(rng.integers(1, 260)) for c in range(n_chunks)}
+    retrieved = [sorted(rng.choice(n_chunks, size=int(rng.integers(0, n_chunks + 1)), replace=False).tolist()) for _ in range(batch)]
+    q_lens = [int(rng.integers(1, 41)) for _ in range(batch)]
+    steps = int(rng.integers(0, 4))
+    compressed = bool(dtype == "bf16" and D == 128 and rng.random() < 0.4)
+    case = Case(f"rand-{seed}", n_layers=int(rng.integers(1, 3)), Hq=G * Hkv, Hkv=Hkv, D=D, hidden=hidden, dtype=dtype,
+                chunk_lens=lens, retrieved=retrieved, q_lens=q_lens, steps=steps, rope_base=float(rng.choice([10000.0, 500000.0])),
+                scale=1.0 / np.sqrt(hidden) * 2.0, q_scale=1.0, compressed=compressed,
+                decode_units=int(rng.choice([0, 0, 0, 1, 3])), max_tail=None)
+    print(case)
+    _chain_parity(case, fused=bool(rng.random() < 0.5))
