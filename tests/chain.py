@@ -378,7 +378,7 @@ def compare_chunk_prefill(case: Case, outs, ref):
         # the relative gate is per row: the first rows average a handful of values and are an
         # order of magnitude larger than rows that average hundreds
         rms = np.sqrt((r ** 2).mean(axis=(1, 2), keepdims=True))
-        assert err.max() <= atol, f"chunk {cid} layer {l}: max abs {err.max():.3e} > {atol}"
+        assert (err <= atol + store_slack(case.dtype, r)).all(), f"chunk {cid} layer {l}: max abs {err.max():.3e} > {atol}"
         bad = err > rtol * rms + store_slack(case.dtype, r)
         assert not bad.any(), f"chunk {cid} layer {l}: max abs {err.max():.3e} at rows {np.unique(np.nonzero(bad)[0])[:8]}"
         worst = max(worst, err.max())
@@ -479,7 +479,9 @@ def tolerances(dtype: str):
     1e-2 bf16 inputs with fp32 accumulation) plus a relative gate, because with near-uniform
     softmax the outputs are far smaller than the absolute bar.  For bf16 the relative gate is
     applied per element with half an ulp of the stored output (2^-8 |ref|) added: an output
-    several times the rms is rounded by more than the rms gate alone allows."""
+    several times the rms is rounded by more than the rms gate alone allows.  The same half ulp
+    is added to the absolute bar: an output beyond 2.56 is stored with an error of up to more
+    than 1e-2 whatever was computed (4.1381 is stored as 4.125)."""
     return (1e-5, 1e-4) if dtype == "f32" else (1e-2, 2e-2)
 
 
@@ -499,7 +501,7 @@ def compare_attention(case: Case, o_pre, o_dec, pre, dec):
         assert np.isfinite(got).all(), f"prefill layer {l} instance {b}: non-finite output"
         err = np.abs(got - ref).max()
         rms = np.sqrt((ref ** 2).mean())
-        assert err <= atol, f"prefill layer {l} inst {b}: max abs {err:.3e} > {atol}"
+        assert (np.abs(got - ref) <= atol + store_slack(case.dtype, ref)).all(), f"prefill layer {l} inst {b}: max abs {err:.3e} > {atol}"
         assert (np.abs(got - ref) <= rtol * rms + store_slack(case.dtype, ref)).all(), \
             f"prefill layer {l} inst {b}: max abs {err:.3e} vs rms {rms:.3e}"
         worst = max(worst, err)
@@ -508,7 +510,7 @@ def compare_attention(case: Case, o_pre, o_dec, pre, dec):
         assert np.isfinite(got).all(), f"decode step {t} layer {l} instance {b}: non-finite output"
         err = np.abs(got - ref).max()
         rms = np.sqrt((ref ** 2).mean())
-        assert err <= atol, f"decode step {t} layer {l} inst {b}: max abs {err:.3e} > {atol}"
+        assert (np.abs(got - ref) <= atol + store_slack(case.dtype, ref)).all(), f"decode step {t} layer {l} inst {b}: max abs {err:.3e} > {atol}"
         assert (np.abs(got - ref) <= rtol * rms + store_slack(case.dtype, ref)).all(), \
             f"decode step {t} layer {l} inst {b}: max abs {err:.3e} vs rms {rms:.3e}"
         worst = max(worst, err)
