@@ -244,6 +244,18 @@ matkv_status matkv_assemble(matkv_ctx* ctx, const matkv_page* pages_host,
 int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tokens_host,
                                 int32_t n_pages, int32_t batch, int32_t q_len,
                                 int32_t* unit_tokens_out, int32_t* unit_items_out, int32_t cap);
+/* Host-only preview of the shared decode partition (see matkv_table_shared_units) that
+ * matkv_assemble would build for a batch (no GPU is touched).  page_ids_host /
+ * page_tokens_host: [batch][max_pages], instance b uses its first n_pages_host[b] entries;
+ * equal ids mean the same slot.  Unit u is written to units_out[u * 36 ..]: id of its first
+ * page (-1: only a tail), page tokens it streams, 1 if it ends with its user's tail, number
+ * of users, then 16 pairs (instance, partial slot), -1 where unused.  slots_out (may be NULL):
+ * [batch][2] = first partial slot and number of slots of each instance.  Returns the number
+ * of units (at most cap), 0 if no shared partition would be built, -1 on a bad argument. */
+int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids_host,
+                                const int32_t* page_tokens_host, const int32_t* n_pages_host,
+                                const int32_t* q_len_host, int32_t batch, int32_t* units_out,
+                                int32_t cap, int32_t* slots_out);
 /* Decode work units of the table's shared partition, 0 if matkv_assemble built none, -1 if the
  * table is unknown.  When two or more instances of a batch point at the same slot (the same
  * chunk, retrieved by several requests), matkv_assemble cuts the DISTINCT pages into pieces

@@ -28,7 +28,7 @@ EXPORTS = [
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
-    "matkv_table_shared_units",
+    "matkv_table_shared_units", "matkv_plan_shared_units",
 ]
 
 
@@ -106,6 +106,8 @@ def _load_library():
     lib.matkv_plan_decode_units.argtypes = [cfgp, POINTER(c_int32), c_int32, c_int32, c_int32,
                                             POINTER(c_int32), POINTER(c_int32), c_int32]
     lib.matkv_plan_decode_units.restype = c_int32
+    lib.matkv_plan_shared_units.argtypes = [cfgp] + [POINTER(c_int32)] * 4 + [c_int32, POINTER(c_int32), c_int32, POINTER(c_int32)]
+    lib.matkv_plan_shared_units.restype = c_int32
     lib.matkv_probe_read.argtypes = [c_void_p, c_void_p, c_size_t]; lib.matkv_probe_read.restype = c_int32
     lib.matkv_graph_begin.argtypes = [c_void_p]; lib.matkv_graph_begin.restype = c_int32
     lib.matkv_graph_end.argtypes = [c_void_p, POINTER(c_void_p)]; lib.matkv_graph_end.restype = c_int32
@@ -156,6 +158,27 @@ def table_bytes(cfg: Config) -> int:
 
 def config_check(cfg: Config) -> int:
     return int(_lib.matkv_config_check(byref(cfg)))
+
+
+def plan_shared_units(cfg: Config, pages, q_lens):
+    """Shared decode partition matkv_assemble would build.  pages: per instance a list of
+    (page id, tokens).  Returns (units, slots) with units = list of dicts {page, tokens, tail,
+    users: [(instance, slot)]} and slots = [(first, count)] per instance; ([], None) if none is built."""
+    batch, mp = len(pages), max(cfg.max_pages, 1)
+    ids, toks = (c_int32 * (batch * mp))(), (c_int32 * (batch * mp))()
+    for b, plist in enumerate(pages):
+        for i, (pid, n) in enumerate(plist):
+            ids[b * mp + i], toks[b * mp + i] = pid, n
+    npg = (c_int32 * batch)(*[len(p) for p in pages])
+    ql = (c_int32 * batch)(*q_lens)
+    cap, w = 4096, 36
+    out, slots = (c_int32 * (cap * w))(), (c_int32 * (2 * batch))()
+    n = _lib.matkv_plan_shared_units(byref(cfg), ids, toks, npg, ql, batch, out, cap, slots)
+    if n < 0:
+        raise MatKVError(EINVAL, "matkv_plan_shared_units")
+    units = [dict(page=out[u * w], tokens=out[u * w + 1], tail=bool(out[u * w + 2]),
+                  users=[(out[u * w + 4 + 2 * k], out[u * w + 5 + 2 * k]) for k in range(out[u * w + 3])]) for u in range(n)]
+    return units, ([(slots[2 * b], slots[2 * b + 1]) for b in range(batch)] if n else None)
 
 
 def plan_decode_units(cfg: Config, page_tokens, batch: int, q_len: int):

@@ -1126,6 +1126,56 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
     return made < cap ? made : cap;
 }
 
+int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids, const int32_t* page_tokens,
+                                const int32_t* n_pages, const int32_t* q_len, int32_t batch,
+                                int32_t* units_out, int32_t cap, int32_t* slots_out) {
+    const char* why;
+    if (check_config(cfg, &why) != MATKV_OK) return -1;
+    if (!n_pages || !q_len || batch < 1 || batch > cfg->max_batch || cap < 0 || (cap > 0 && !units_out)) return -1;
+    const int grp = cfg->n_q_heads / cfg->n_kv_heads;
+    std::vector<matkv_page> pages((size_t)batch * std::max(cfg->max_pages, 1));
+    std::vector<InstanceInfo> insts((size_t)batch);
+    for (int b = 0; b < batch; ++b) {
+        if (n_pages[b] < 0 || n_pages[b] > cfg->max_pages || q_len[b] < 1 || q_len[b] > cfg->max_tail_tokens) return -1;
+        if (n_pages[b] > 0 && (!page_ids || !page_tokens)) return -1;
+        memset(&insts[b], 0, sizeof(InstanceInfo));
+        insts[b].q_len = q_len[b];
+        for (int p = 0; p < n_pages[b]; ++p) {
+            const size_t i = (size_t)b * cfg->max_pages + p;
+            if (page_ids[i] < 0 || page_tokens[i] < 1) return -1;
+            pages[i].slot = reinterpret_cast<const void*>(((uintptr_t)page_ids[i] + 1) * 4096);   // never dereferenced
+            pages[i].n_tokens = page_tokens[i];
+            pages[i].format = MATKV_PAGE_PLAIN;
+        }
+    }
+    // the conditions of matkv_assemble
+    if (batch < 2 || cfg->decode_units != 0 || cfg->decode_variant != 0 || cfg->dtype != MATKV_BF16 ||
+        cfg->head_dim != 128 || !group_size_built(grp))
+        return 0;
+    const TableLayout tl = table_layout(*cfg);
+    std::vector<Item> items((size_t)tl.max_items);
+    std::vector<SUnit> sunits((size_t)tl.max_sunits);
+    int n_items = 0;
+    const int n = build_shared_units(*cfg, pages.data(), n_pages, batch, tl.max_sunits, tl.max_items, insts.data(),
+                                     items.data(), &n_items, sunits.data());
+    for (int u = 0; u < n && u < cap; ++u) {
+        const SUnit& su = sunits[u];
+        int32_t* o = units_out + (size_t)u * (4 + 2 * kMaxSharedUsers);
+        const uintptr_t base = (uintptr_t)su.u.first.base;
+        o[0] = base ? (int32_t)(base / 4096 - 1) : -1;     // id of the unit's first page; -1: only a tail
+        o[1] = su.u.page_tokens;                            // page tokens the unit streams (all its items)
+        o[2] = su.u.has_tail;
+        o[3] = su.n_users;
+        for (int k = 0; k < kMaxSharedUsers; ++k) {
+            o[4 + 2 * k] = k < su.n_users ? su.users[k].inst : -1;
+            o[5 + 2 * k] = k < su.n_users ? su.users[k].slot : -1;
+        }
+    }
+    if (slots_out && n > 0)
+        for (int b = 0; b < batch; ++b) { slots_out[2 * b] = insts[b].sslot0; slots_out[2 * b + 1] = insts[b].n_sslots; }
+    return n < cap ? n : cap;
+}
+
 int32_t matkv_table_shared_units(matkv_ctx* c, const void* table) {
     if (!c) return -1;
     TableHost* th = find_table(c, table);

@@ -98,3 +98,70 @@ def test_decode_partition_covers_every_token_once_and_is_balanced(mk):
     assert toks == [0] and items == [0]
     with pytest.raises(mk.MatKVError):
         mk.plan_decode_units(cfg, [0, 5], batch=1, q_len=10)
+
+
+def test_decode_partition_never_exceeds_the_compute_units(mk):
+    """Workgroups of a decode launch = units x KV heads over the batch: at most 256, so that no
+    compute unit holds two (batch 3 x 8 KV heads: 10 units each, not 11)."""
+    for batch in (1, 2, 3, 5, 7, 16):
+        cfg = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, batch, 10, 192)
+        toks, _ = mk.plan_decode_units(cfg, [1000] * 10, batch=batch, q_len=64)
+        assert len(toks) * batch * 8 <= 256 and len(toks) == 256 // (batch * 8)
+        assert sum(toks) == 10000
+
+
+def test_shared_partition_covers_every_instance_once(mk):
+    """Host logic of the shared decode partition: built only under heavy page reuse; every
+    (instance, page token) is streamed by exactly one unit that lists the instance; a unit has at
+    most 16 / G users; every instance owns one tail unit and a run of distinct partial slots
+    that its units' entries use up exactly; the launch stays within 512 workgroups."""
+    rng = np.random.default_rng(7)
+    for G, Hkv in ((4, 8), (1, 2), (3, 8), (8, 8), (2, 4)):
+        for trial in range(6):
+            batch = int(rng.integers(2, 17))
+            n_chunks = int(rng.integers(1, 7))
+            lens = [int(rng.integers(1, 1500)) for _ in range(n_chunks)]
+            pages = []
+            for _ in range(batch):
+                k = int(rng.integers(0, n_chunks + 1))
+                ids = sorted(rng.choice(n_chunks, size=k, replace=False).tolist())
+                if 0 not in ids and rng.random() < 0.8:
+                    ids = [0] + ids                         # a hot chunk
+                pages.append([(i, lens[i]) for i in ids])
+            q_lens = [int(rng.integers(1, 100)) for _ in range(batch)]
+            cfg = mk.make_config(2, G * Hkv, Hkv, 128, 4096, "bf16", 500000.0, batch, 6, 128)
+            units, slots = mk.plan_shared_units(cfg, pages, q_lens)
+            all_tokens = sum(n for p in pages for _, n in p)
+            distinct = sum(lens[i] for i in {i for p in pages for i, _ in p})
+            shared_any = any(sum(1 for p in pages if any(i == c for i, _ in p)) >= 2 for c in range(n_chunks))
+            if not shared_any or 2 * distinct > all_tokens:
+                assert units == [] and slots is None
+                continue
+            assert units and len(units) * Hkv <= 512 + batch * Hkv   # (the tails of very small batches may add a few)
+            streamed = [0] * batch
+            used = [set() for _ in range(batch)]
+            tails = [0] * batch
+            for u in units:
+                assert 1 <= len(u["users"]) <= 16 // G
+                assert u["tokens"] >= 0 and (u["tokens"] > 0 or u["tail"])
+                if u["tail"]:
+                    assert len(u["users"]) == 1
+                    tails[u["users"][0][0]] += 1
+                for inst, slot in u["users"]:
+                    streamed[inst] += u["tokens"]
+                    first, count = slots[inst]
+                    assert first <= slot < first + count and slot not in used[inst]
+                    used[inst].add(slot)
+            assert tails == [1] * batch
+            assert streamed == [sum(n for _, n in p) for p in pages]
+            assert [len(s) for s in used] == [c for _, c in slots]
+            ends = sorted((f, f + c) for f, c in slots)
+            assert all(a[1] == b[0] for a, b in zip(ends, ends[1:])) and ends[0][0] == 0     # the runs tile 0 .. total
+    # not built: explicit unit count, fp32, a batch of one
+    pages = [[(0, 500)], [(0, 500)], [(0, 500)]]
+    assert mk.plan_shared_units(mk.make_config(2, 8, 2, 128, 512, "bf16", 500000.0, 3, 2, 64, decode_units=2), pages, [3, 3, 3])[0] == []
+    assert mk.plan_shared_units(mk.make_config(2, 8, 2, 64, 512, "f32", 10000.0, 3, 2, 64), pages, [3, 3, 3])[0] == []
+    assert mk.plan_shared_units(mk.make_config(2, 8, 2, 128, 512, "bf16", 500000.0, 3, 2, 64), pages[:1], [3])[0] == []
+    assert len(mk.plan_shared_units(mk.make_config(2, 8, 2, 128, 512, "bf16", 500000.0, 3, 2, 64), pages, [3, 3, 3])[0]) == 3 + 2      # three tails, the page in two pieces
+    with pytest.raises(mk.MatKVError):
+        mk.plan_shared_units(mk.make_config(2, 8, 2, 128, 512, "bf16", 500000.0, 3, 2, 64), [[(0, 0)], [(0, 5)]], [3, 3])
