@@ -137,8 +137,6 @@ __global__ __launch_bounds__(NW * 64) void attn_rows_kernel(
     constexpr int LPT = D / EPL;                        // lanes that share one token row
     constexpr int TPW = 64 / LPT;                       // token rows per wave-wide load
     constexpr int BLK = TPW * U;                        // token rows one wave handles per step
-    constexpr int NT = NW * 64;
-    constexpr int PSTRIDE = D + 4;                      // floats of one partial row
     typedef RowMath<T> RM;
 
     const int tid = threadIdx.x;
