@@ -24,8 +24,9 @@
  *     the workspace and cache tables belong to the caller.
  *   - All compute entry points enqueue on the compute stream given at creation
  *     and return without waiting; matkv_load enqueues on the load stream.
- *   - Every entry point returns a matkv_status; nothing aborts or prints.  After
- *     a failure matkv_last_error() holds a one-line reason.  Arguments are
+ *   - Every entry point returns a matkv_status; nothing aborts or prints, and no C++
+ *     exception leaves the library (host allocation failures become MATKV_ENOMEM).
+ *     After a failure matkv_last_error() holds a one-line reason.  Arguments are
  *     validated before anything is enqueued.
  *   - Element type (config.dtype): MATKV_BF16 (bf16 storage, fp32 arithmetic,
  *     one round-to-nearest-even on store) or MATKV_F32.
@@ -39,10 +40,9 @@
  *   Q, O decode   [batch][Hq][D]
  *   hidden        [tokens][hidden]   weights [Hkv*D][hidden] (row = output feature)
  *
- * Positions: a chunk is materialized with pos0 = 0 whatever its place in the
- * prompt (Section III-B: documents always start at the first input position);
- * tail token j of instance b sits at position pos_base[b] + j.  Attention takes
- * Q already rotated.
+ * Positions: every chunk is rotated from position 0, whatever place it later takes
+ * in a prompt (Section III-B), so a chunk is materialized with pos0 = 0; tail token j
+ * of instance b sits at position pos_base[b] + j.  Attention takes Q already rotated.
  */
 #ifndef MATKV_H
 #define MATKV_H
@@ -145,8 +145,8 @@ matkv_status matkv_materialize(matkv_ctx* ctx, const void* hidden, const void* w
                                const void* w_v, int32_t n_tokens, int64_t pos0,
                                void* k_out, void* v_out, int64_t token_stride);
 
-/* The attention a chunk performs on itself while it is materialized (Section III-B: the chunk
- * runs through the model's prefill alone, starting at the first input position): row i, head h
+/* The attention a chunk performs on itself while it is materialized (Section III-B: each chunk
+ * is prefilled on its own, its tokens at positions 0, 1, ...): row i, head h
  * (KV head h / (Hq/Hkv)) = softmax over the chunk's own tokens j <= i of scale * q.k, times V.
  * Together with matkv_materialize this is the part of a chunk's forward pass that reads and
  * writes K/V; the rest of the layer (norms, output projection, MLP) is the caller's.
@@ -192,8 +192,11 @@ matkv_status matkv_materialize_tail(matkv_ctx* ctx, const void* hidden, const vo
  * table still points into the slot, the copy is ordered after all compute work enqueued so
  * far; if that table has since been re-assembled onto other slots, only after the work that
  * was enqueued up to that re-assembly (so the next instance's load runs beside the current
- * instance's kernels whichever of the two is enqueued first).  Errors: EINVAL (null, size mismatch, not pinned, slot too small),
- * EBUSY (more than 4096 tickets outstanding), EHIP. */
+ * instance's kernels whichever of the two is enqueued first).  A table that still points
+ * into the slot cannot be read again (attention, graph replay) until the new copy has been
+ * waited for or has finished: such a call returns MATKV_ENOTREADY instead of racing with
+ * the copy.  Errors: EINVAL (null, size mismatch, not pinned, slot too small), EBUSY (more than
+ * 4096 tickets outstanding; a graph is being recorded), EHIP. */
 matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int32_t n_tokens,
                         void* device_slot, size_t slot_bytes, matkv_ticket* out);
 /* The storage half of load_KV (Section IV: materialized KVs live as raw bytes on flash storage):
@@ -208,7 +211,9 @@ matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int
  * do direct I/O into pinned GPU-visible memory the pieces pass through one more host copy
  * (read by a helper thread of this call, so that reading and copying overlap).  On MATKV_EIO (read
  * error, file shorter than the blob) no ticket is issued and part of the slot may have been
- * overwritten.  Other errors as matkv_load. */
+ * overwritten; the slot then counts as the target of an unfinished load until the pieces already
+ * enqueued have landed, so a table over it is refused or ordered behind them like any other.
+ * Other errors as matkv_load. */
 matkv_status matkv_load_file(matkv_ctx* ctx, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
                              void* device_slot, size_t slot_bytes, matkv_ticket* out);
 /* The storage half of store_KV (Section IV): writes `bytes` of device memory (a materialized blob
@@ -231,8 +236,11 @@ matkv_status matkv_sync(matkv_ctx* ctx, matkv_ticket t);
  * q_len_host [batch] are host arrays; pos_base_host [batch] may be NULL (then the first
  * question token of instance b takes position sum of its pages' n_tokens).  The table's
  * tail_len starts at q_len.  Every page whose slot was a matkv_load target must have been
- * waited for or completed, else MATKV_ENOTREADY.  table: device buffer of
- * matkv_table_bytes(cfg), written on the compute stream. */
+ * waited for or completed, else MATKV_ENOTREADY (the attention entry points and
+ * matkv_graph_launch make the same check for loads issued after the table was built).
+ * A slot that a live table points into may be the target of a new load at any time: the copy
+ * is ordered behind the work already enqueued instead of being refused.  table: device buffer
+ * of matkv_table_bytes(cfg), written on the compute stream. */
 matkv_status matkv_assemble(matkv_ctx* ctx, const matkv_page* pages_host,
                             const int32_t* n_pages_host, const int32_t* q_len_host,
                             const int64_t* pos_base_host, int32_t batch, void* table);

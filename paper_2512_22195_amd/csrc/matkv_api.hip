@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <condition_variable>
 #include <mutex>
+#include <exception>
 #include <new>
 #include <thread>
 #include <unordered_map>
@@ -52,6 +53,7 @@ struct TableHost {
     uint64_t sig_decode = 0, sig_prefill = 0;   // of what a recorded decode / prefill launch bakes in
     int max_tail_len = 0;     // largest tail_len of any instance (host mirror)
     int min_tail_len = 0;
+    int n_decode_slots = 0;   // partial slots a decode launch writes (units, or (unit, user) pairs when shared)
     std::vector<const void*> slots;   // distinct slots its pages point into
 };
 
@@ -126,6 +128,23 @@ matkv_status hip_fail(matkv_ctx* c, hipError_t e, const char* what) {
         hipError_t e_ = (call);                                \
         if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
     } while (0)
+
+// No C++ exception crosses the boundary: host containers and std::thread can throw
+// (allocation failure, no thread to be had); every entry point that reaches them runs between
+// these two and turns the exception into a status.
+#define MATKV_TRY try {
+#define MATKV_CATCH(ctx, name)                                                                     \
+    } catch (const std::bad_alloc&) {                                                              \
+        return fail(ctx, MATKV_ENOMEM, "%s: out of host memory", name);                            \
+    } catch (const std::exception& ex_) {                                                          \
+        return fail(ctx, MATKV_ENOMEM, "%s: %s", name, ex_.what());                                \
+    } catch (...) {                                                                                \
+        return fail(ctx, MATKV_ENOMEM, "%s: unexpected C++ exception", name);                      \
+    }
+#define MATKV_CATCH_INT                                                                            \
+    } catch (...) {                                                                                \
+        return -1;                                                                                 \
+    }
 
 int elem_bytes(const matkv_config& c) { return c.dtype == MATKV_F32 ? 4 : 2; }
 
@@ -509,7 +528,12 @@ matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t works
     c->tl = table_layout(*cfg);
     const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
     c->scale_log2e = scale * 1.4426950408889634f;
-    c->tickets.resize(kTicketRing);
+    try {
+        c->tickets.resize(kTicketRing);
+    } catch (...) {
+        delete c;
+        return MATKV_ENOMEM;
+    }
 
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fence_ev, hipEventDisableTiming);
@@ -615,6 +639,7 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
                                     void* tail_v) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;
+    MATKV_TRY
     if (!hidden || !w_k || !w_v || !table || !tail_k || !tail_v)
         return fail(c, MATKV_EINVAL, "materialize_tail: null pointer");
     if (!aligned16(hidden) || !aligned16(w_k) || !aligned16(w_v) || !aligned16(tail_k) || !aligned16(tail_v))
@@ -636,6 +661,7 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
     a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim; a.Hd = c->cfg.hidden;
     HIP_TRY(c, launch_materialize(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
+    MATKV_CATCH(c, "materialize_tail")
 }
 
 // ------------------------------------------------------------------------------------ L ----
@@ -644,6 +670,9 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
 // the load stream has been ordered after compute work that may still read the slot.
 static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, int32_t n_tokens,
                                  void* device_slot, size_t slot_bytes, Ticket** t_out) {
+    // a copy ordered behind the compute stream would pull the load stream and the ticket's event
+    // into the recording
+    if (c->capturing) return fail(c, MATKV_EBUSY, "%s: not allowed while a graph is being captured", name);
     if (n_tokens < 1) return fail(c, MATKV_EINVAL, "%s: n_tokens=%d", name, n_tokens);
     const size_t want = matkv_blob_bytes(&c->cfg, n_tokens), want_c = matkv_compressed_blob_bytes(&c->cfg, n_tokens);
     if (bytes != want && bytes != want_c)
@@ -696,6 +725,7 @@ matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32
                         void* device_slot, size_t slot_bytes, matkv_ticket* out) {
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;
+    MATKV_TRY
     if (!host_blob || !device_slot || !out) return fail(c, MATKV_EINVAL, "load: null pointer");
     if (!aligned16(host_blob)) return fail(c, MATKV_EINVAL, "load: pointers must be 16-byte aligned");
     hipPointerAttribute_t attr;
@@ -707,6 +737,7 @@ matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32
     if (st != MATKV_OK) return st;
     HIP_TRY(c, hipMemcpyAsync(device_slot, host_blob, bytes, hipMemcpyHostToDevice, c->load));
     return load_finish(c, t, device_slot, out);
+    MATKV_CATCH(c, "load")
 }
 
 // File -> two plain page-aligned buffers (a reader thread, one pread per piece) -> pinned bounce
@@ -786,28 +817,26 @@ static matkv_status load_file_via_plain(matkv_ctx* c, int fd, uint64_t offset, s
     return st;
 }
 
-matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
-                             void* device_slot, size_t slot_bytes, matkv_ticket* out) {
-    matkv_status st = precheck(c);
-    if (st != MATKV_OK) return st;
-    if (fd < 0 || !device_slot || !out) return fail(c, MATKV_EINVAL, "load_file: bad descriptor or null pointer");
-    if (c->capturing) return fail(c, MATKV_EBUSY, "load_file: not allowed while a graph is being captured");
-    Ticket* t;
-    st = load_prepare(c, "load_file", bytes, n_tokens, device_slot, slot_bytes, &t);
-    if (st != MATKV_OK) return st;
-    for (int i = 0; i < kBounceRing; ++i) {
-        if (c->bounce[i].host) continue;
-        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
-    }
+// After a failed file load some pieces may already be on the load stream: the slot is marked as
+// the target of a load that nobody has waited for (a ticket of its own, never handed out), so
+// that a later matkv_assemble orders the compute stream behind those copies instead of
+// reading a slot that is still being written.
+static void load_abandon(matkv_ctx* c, Ticket* t, void* device_slot) {
+    if (hipEventRecord(t->ev, c->load) != hipSuccess) { (void)hipGetLastError(); return; }
+    t->id = c->next_ticket++;
+    t->slot = device_slot;
+    t->done = false;
+    SlotState& s = c->slots[device_slot];
+    s.pending = t->id;
+    s.waited = false;
+}
+
+static matkv_status load_file_pieces(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, void* device_slot) {
     // piece k+1 is read from the file while the copies of the pieces before it are in flight
     size_t done = 0;
     while (done < bytes) {
-        if (c->read_via_plain) {
-            st = load_file_via_plain(c, fd, offset + done, bytes - done, static_cast<char*>(device_slot) + done);
-            if (st != MATKV_OK) return st;
-            break;
-        }
+        if (c->read_via_plain)
+            return load_file_via_plain(c, fd, offset + done, bytes - done, static_cast<char*>(device_slot) + done);
         Staging& b = c->bounce[c->bounce_next];
         c->bounce_next = (c->bounce_next + 1) % kBounceRing;
         if (b.used) HIP_TRY(c, hipEventSynchronize(b.ev));
@@ -838,7 +867,30 @@ matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes
         b.used = true;
         done += piece;
     }
+    return MATKV_OK;
+}
+
+matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
+                             void* device_slot, size_t slot_bytes, matkv_ticket* out) {
+    matkv_status st = precheck(c);
+    if (st != MATKV_OK) return st;
+    MATKV_TRY
+    if (fd < 0 || !device_slot || !out) return fail(c, MATKV_EINVAL, "load_file: bad descriptor or null pointer");
+    Ticket* t;
+    st = load_prepare(c, "load_file", bytes, n_tokens, device_slot, slot_bytes, &t);
+    if (st != MATKV_OK) return st;
+    for (int i = 0; i < kBounceRing; ++i) {
+        if (c->bounce[i].host) continue;
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
+    }
+    st = load_file_pieces(c, fd, offset, bytes, device_slot);
+    if (st != MATKV_OK) {
+        if (!c->sticky_hip) load_abandon(c, t, device_slot);
+        return st;
+    }
     return load_finish(c, t, device_slot, out);
+    MATKV_CATCH(c, "load_file")
 }
 
 matkv_status matkv_store_file(matkv_ctx* c, int fd, uint64_t offset, const void* device_blob, size_t bytes) {
@@ -947,6 +999,36 @@ matkv_status matkv_sync(matkv_ctx* c, matkv_ticket tk) {
     return MATKV_OK;
 }
 
+// A slot that was the target of a load nobody has waited for: if the copy has finished, the
+// compute stream is ordered behind it (while a graph is being recorded nothing is ordered: a
+// finished copy needs no edge) and the slot counts as waited for; if not, MATKV_ENOTREADY.
+static matkv_status slot_ready(matkv_ctx* c, const void* slot, const char* name) {
+    auto it = c->slots.find(slot);
+    if (it == c->slots.end() || !it->second.pending || it->second.waited) return MATKV_OK;
+    Ticket& t = c->tickets[it->second.pending % kTicketRing];
+    bool done = (t.id != it->second.pending) || t.done;
+    if (!done) {
+        hipError_t q = hipEventQuery(t.ev);
+        if (q == hipSuccess) { t.done = true; done = true; }
+        else if (q == hipErrorNotReady) (void)hipGetLastError();
+        else return hip_fail(c, q, "hipEventQuery");
+    }
+    if (!done) return fail(c, MATKV_ENOTREADY, "%s: a page's load has neither finished nor been waited for", name);
+    if (t.id == it->second.pending && !c->capturing) HIP_TRY(c, hipStreamWaitEvent(c->compute, t.ev, 0));
+    it->second.waited = true;
+    return MATKV_OK;
+}
+
+// Every slot a table points into, before work that reads the table is enqueued: a load into one
+// of them after the table was assembled must not race with that work.
+static matkv_status table_pages_ready(matkv_ctx* c, const TableHost& th, const char* name) {
+    for (const void* sl : th.slots) {
+        matkv_status st = slot_ready(c, sl, name);
+        if (st != MATKV_OK) return st;
+    }
+    return MATKV_OK;
+}
+
 // ------------------------------------------------------------------------------------ A ----
 
 matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t* n_pages,
@@ -954,6 +1036,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     matkv_status st = precheck(c);
     if (st != MATKV_OK) return st;
     if (c->capturing) return fail(c, MATKV_EBUSY, "assemble: not allowed while a graph is being captured");
+    MATKV_TRY
     if (!n_pages || !q_len || !table) return fail(c, MATKV_EINVAL, "assemble: null pointer");
     if (!aligned16(table)) return fail(c, MATKV_EINVAL, "assemble: table must be 16-byte aligned");
     if (batch < 1 || batch > c->cfg.max_batch) return fail(c, MATKV_EINVAL, "assemble: batch=%d, max_batch=%d", batch, c->cfg.max_batch);
@@ -973,21 +1056,9 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
                 return fail(c, MATKV_EINVAL, "assemble: instance %d page %d has unknown format %d", b, p, pg.format);
             if (kv_fmt < 0) kv_fmt = pg.format;
             if (pg.format != kv_fmt) return fail(c, MATKV_EUNSUPPORTED, "assemble: plain and compressed pages in one table");
-            auto it = c->slots.find(pg.slot);
-            if (it != c->slots.end() && it->second.pending && !it->second.waited) {
-                Ticket& t = c->tickets[it->second.pending % kTicketRing];
-                bool done = (t.id != it->second.pending) || t.done;
-                if (!done) {
-                    hipError_t q = hipEventQuery(t.ev);
-                    if (q == hipSuccess) { t.done = true; done = true; }
-                    else if (q == hipErrorNotReady) (void)hipGetLastError();
-                    else return hip_fail(c, q, "hipEventQuery");
-                }
-                if (!done) return fail(c, MATKV_ENOTREADY, "assemble: instance %d page %d: load neither finished nor waited for", b, p);
-                // finished on the load stream: still order the compute stream after it
-                if (t.id == it->second.pending) HIP_TRY(c, hipStreamWaitEvent(c->compute, t.ev, 0));
-                it->second.waited = true;
-            }
+            st = slot_ready(c, pg.slot, "assemble");
+            if (st == MATKV_ENOTREADY) return fail(c, MATKV_ENOTREADY, "assemble: instance %d page %d: load neither finished nor waited for", b, p);
+            if (st != MATKV_OK) return st;
             total_tokens += pg.n_tokens;
         }
     }
@@ -1070,6 +1141,11 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
 
     th.batch = batch; th.n_items = n_items; th.n_dunits = n_dunits; th.n_punits = n_punits;
     th.total_q = cu; th.max_q = max_q; th.kv_fmt = kv_fmt; th.n_sunits = n_sunits;
+    th.n_decode_slots = n_dunits;
+    if (n_sunits > 0) {
+        th.n_decode_slots = 0;
+        for (int b = 0; b < batch; ++b) th.n_decode_slots = std::max(th.n_decode_slots, insts[b].sslot0 + insts[b].n_sslots);
+    }
     sign_partition(th);
     // Slot bookkeeping: the table's old contents are dead from here on in stream order, so the
     // slots only they pointed into may be overwritten once the work enqueued so far is done.
@@ -1093,6 +1169,7 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     for (const void* sl : th.slots) ++c->slots[sl].refs;
     c->tables[table] = th;
     return MATKV_OK;
+    MATKV_CATCH(c, "assemble")
 }
 
 int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tokens, int32_t n_pages,
@@ -1100,6 +1177,7 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
                                 int32_t* unit_items_out, int32_t cap) {
     const char* why;
     if (check_config(cfg, &why) != MATKV_OK) return -1;
+    MATKV_TRY
     if (n_pages < 0 || n_pages > cfg->max_pages || (n_pages > 0 && !page_tokens) || batch < 1 ||
         batch > cfg->max_batch || q_len < 1 || q_len > cfg->max_tail_tokens || cap < 0)
         return -1;
@@ -1124,6 +1202,7 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
         if (unit_items_out) unit_items_out[u] = units[u].n_items - units[u].has_tail;
     }
     return made < cap ? made : cap;
+    MATKV_CATCH_INT
 }
 
 int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids, const int32_t* page_tokens,
@@ -1132,6 +1211,7 @@ int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids
     const char* why;
     if (check_config(cfg, &why) != MATKV_OK) return -1;
     if (!n_pages || !q_len || batch < 1 || batch > cfg->max_batch || cap < 0 || (cap > 0 && !units_out)) return -1;
+    MATKV_TRY
     const int grp = cfg->n_q_heads / cfg->n_kv_heads;
     std::vector<matkv_page> pages((size_t)batch * std::max(cfg->max_pages, 1));
     std::vector<InstanceInfo> insts((size_t)batch);
@@ -1174,6 +1254,7 @@ int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids
     if (slots_out && n > 0)
         for (int b = 0; b < batch; ++b) { slots_out[2 * b] = insts[b].sslot0; slots_out[2 * b + 1] = insts[b].n_sslots; }
     return n < cap ? n : cap;
+    MATKV_CATCH_INT
 }
 
 int32_t matkv_table_shared_units(matkv_ctx* c, const void* table) {
@@ -1188,6 +1269,7 @@ matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
     TableHost* th = find_table(c, table);
     if (!th) return fail(c, MATKV_EINVAL, "advance: table was not built by matkv_assemble");
     if (n < 1) return fail(c, MATKV_EINVAL, "advance: n=%d", n);
+    MATKV_TRY
     note_table_use(c, table, *th, false);
     if (c->capturing) {
         c->cap->advances.emplace_back(table, n);
@@ -1198,6 +1280,7 @@ matkv_status matkv_advance(matkv_ctx* c, void* table, int32_t n) {
     }
     HIP_TRY(c, launch_advance(reinterpret_cast<char*>(table), c->tl.off_inst, th->batch, n, c->cfg.max_tail_tokens, c->compute));
     return MATKV_OK;
+    MATKV_CATCH(c, "advance")
 }
 
 // -------------------------------------------------------------------------------- P / D ----
@@ -1212,7 +1295,11 @@ static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32
     if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MATKV_EINVAL, "%s: layer %d outside 0..%d", name, layer, c->cfg.n_layers - 1);
     TableHost* th = find_table(c, table);
     if (!th) return fail(c, MATKV_EINVAL, "%s: table was not built by matkv_assemble", name);
+    MATKV_TRY
+    st = table_pages_ready(c, *th, name);
+    if (st != MATKV_OK) return st;
     note_table_use(c, table, *th, prefill != 0);
+    MATKV_CATCH(c, name)
     AttnArgs a{};
     a.q = q; a.out = out; a.tail_k = tail_k; a.tail_v = tail_v;
     a.table = reinterpret_cast<const char*>(table);
@@ -1367,7 +1454,14 @@ matkv_status matkv_graph_end(matkv_ctx* c, matkv_graph** out) {
         delete g;
         return hip_fail(c, e, "graph_end");
     }
-    c->graphs.push_back(g);
+    try {
+        c->graphs.push_back(g);
+    } catch (...) {
+        (void)hipGraphExecDestroy(g->exec);
+        (void)hipGraphDestroy(g->graph);
+        delete g;
+        return fail(c, MATKV_ENOMEM, "graph_end: out of host memory");
+    }
     *out = g;
     return MATKV_OK;
 }
@@ -1383,6 +1477,9 @@ matkv_status matkv_graph_launch(matkv_ctx* c, matkv_graph* g) {
         if (!th) return fail(c, MATKV_EINVAL, "graph_launch: a recorded table no longer exists");
         if ((e.decode && th->sig_decode != e.sig_decode) || (e.prefill && th->sig_prefill != e.sig_prefill))
             return fail(c, MATKV_EINVAL, "graph_launch: a table has been re-assembled into a different partition since the recording");
+        // a load into one of its slots since the recording: the replay must not race with the copy
+        st = table_pages_ready(c, *th, "graph_launch");
+        if (st != MATKV_OK) return st;
     }
     // the recorded tail advances must still fit
     for (auto& adv : g->advances) {

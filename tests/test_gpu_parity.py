@@ -632,11 +632,65 @@ def test_assemble_refuses_pages_still_loading():
         with pytest.raises(mk.MatKVError) as e:
             ctx.assemble([[(slots[-1], 1000)]], [4], table)
         assert e.value.status == mk.ENOTREADY
-        assert not ctx.query(tickets[-1]) or True              # may have finished by now; never blocks
+        # the last ticket cannot be complete before the first: copies on one stream finish in order
+        first_done, last_done = ctx.query(tickets[0]), ctx.query(tickets[-1])    # never blocks
+        assert first_done or not last_done
         ctx.wait(tickets[-1])
         ctx.assemble([[(slots[-1], 1000)]], [4], table)
         ctx.sync(tickets[-1])
         assert ctx.query(tickets[-1])
+    finally:
+        ctx.close()
+
+
+def test_attention_refuses_a_table_whose_slot_is_being_reloaded():
+    """A load into a slot that a live table points into: attention over that table is refused
+    (ENOTREADY) while the copy is neither finished nor waited for - never a silent race - and
+    after matkv_wait it reads the new bytes."""
+    from paper_2512_22195_amd import binding as mk
+    case = Case("reload", n_layers=32, Hq=32, Hkv=8, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 1000}, retrieved=[[0]], q_lens=[4], steps=1, scale=1.0)
+    inp = chain.make_attention_inputs(case)
+    inp2 = chain.make_attention_inputs(Case("reload-2", n_layers=32, Hq=32, Hkv=8, D=128, hidden=64, dtype="bf16",
+                                            chunk_lens={0: 1000}, retrieved=[[0]], q_lens=[4], steps=1, scale=1.0))
+    ctx = chain.make_context(case)
+    try:
+        host_a = inp["blobs"][0].contiguous().view(torch.uint8).reshape(-1).pin_memory()
+        host_b = inp2["blobs"][0].contiguous().view(torch.uint8).reshape(-1).pin_memory()
+        slot = ctx.new_slot(1000)
+        spare = [ctx.new_slot(1000) for _ in range(10)]       # 1.3 GB queued ahead of the reload
+        cs = ctx.compute_stream
+        with torch.cuda.stream(cs):
+            tail = inp["tail"].to("cuda:0")
+            q = inp["q_dec"][0].to("cuda:0")
+            o = torch.full_like(q, float("nan"))
+            table = ctx.new_table()
+            ctx.wait(ctx.load(host_a, 1000, slot))
+            ctx.assemble([[(slot, 1000)]], case.q_lens, table)
+            ctx.advance(table, 1)
+            ctx.decode_attn(0, q[0], table, tail[0, 0], tail[0, 1], o[0])
+            q_pre = inp["q_pre"][0].to("cuda:0")
+            o_pre = torch.empty_like(q_pre)
+            cs.synchronize()
+            for s in spare:
+                ctx.load(host_a, 1000, s)
+            tk = ctx.load(host_b, 1000, slot)                 # the table still points into `slot`
+            # nothing between the load and these calls allocates or synchronises: 1.4 GB of copies are queued
+            for fn in (lambda: ctx.decode_attn(0, q[0], table, tail[0, 0], tail[0, 1], o[0]),
+                       lambda: ctx.prefill_attn(0, q_pre, table, tail[0, 0], tail[0, 1], o_pre)):
+                with pytest.raises(mk.MatKVError) as e:
+                    fn()
+                assert e.value.status == mk.ENOTREADY
+            ctx.wait(tk)
+            for l in range(case.n_layers):
+                ctx.decode_attn(l, q[l], table, tail[l, 0], tail[l, 1], o[l])
+            cs.synchronize()
+        # the outputs are those of the second blob
+        case2 = Case("reload-2", n_layers=32, Hq=32, Hkv=8, D=128, hidden=64, dtype="bf16",
+                     chunk_lens={0: 1000}, retrieved=[[0]], q_lens=[4], steps=1, scale=1.0)
+        mixed = dict(blobs=inp2["blobs"], tail=inp["tail"], q_pre=inp["q_pre"], q_dec=inp["q_dec"])
+        _, dec = chain.run_oracle_attention(case2, mixed, layers=[0, 17, 31])
+        chain.compare_attention(case2, None, o.cpu()[None], {}, dec)
     finally:
         ctx.close()
 
