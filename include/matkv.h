@@ -288,6 +288,20 @@ matkv_status matkv_prefill_attn(matkv_ctx* ctx, int32_t layer, const void* q, co
  * q/out: [batch][Hq][D]. */
 matkv_status matkv_decode_attn(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
                                const void* tail_k, const void* tail_v, void* out);
+/* matkv_decode_attn for callers that cannot allocate device memory or hand the library a
+ * scratch buffer of their own choosing at this point: code under stream capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, same result.  The split partial
+ * results and arrival counters that matkv_decode_attn keeps in the context's workspace live
+ * here in an 8 MiB array inside the library's device image (1 MiB of counters: at most 8192
+ * (instance, KV head) pairs; 7 MiB of partial results: decode units of the batch x Hq x
+ * (D + 4) floats), which every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing (no hipMalloc, hipFree, hipHostMalloc), clears the counters it
+ * uses with a fill kernel and can be recorded by matkv_graph_begin / end.  A batch that needs
+ * more than the array holds is refused with MATKV_ENOMEM before anything is enqueued.  All
+ * calls on one GPU share the array: two calls that overlap in time (other streams, other
+ * contexts) race; calls on one compute stream are ordered and safe. */
+matkv_status matkv_decode_attn_static(matkv_ctx* ctx, int32_t layer, const void* q, const void* table,
+                                      const void* tail_k, const void* tail_v, void* out);
 /* One decode step of one layer in a single launch (Section III-B steps 2-3 for the new token,
  * then Section V-A's decode attention): the same result as
  *   matkv_materialize_tail(hidden, w_k, w_v, table, 1, tail_k, tail_v) followed by

@@ -28,7 +28,7 @@ EXPORTS = [
     "matkv_wait", "matkv_query", "matkv_sync", "matkv_assemble", "matkv_advance",
     "matkv_prefill_attn", "matkv_decode_attn", "matkv_decode_step", "matkv_graph_begin", "matkv_graph_end",
     "matkv_graph_launch", "matkv_graph_destroy", "matkv_plan_decode_units", "matkv_probe_read",
-    "matkv_table_shared_units", "matkv_plan_shared_units",
+    "matkv_table_shared_units", "matkv_plan_shared_units", "matkv_decode_attn_static",
 ]
 
 
@@ -90,7 +90,7 @@ def _load_library():
                                    POINTER(c_int64), c_int32, c_void_p]
     lib.matkv_assemble.restype = c_int32
     lib.matkv_advance.argtypes = [c_void_p, c_void_p, c_int32]; lib.matkv_advance.restype = c_int32
-    for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn):
+    for fn in (lib.matkv_prefill_attn, lib.matkv_decode_attn, lib.matkv_decode_attn_static):
         fn.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         fn.restype = c_int32
     lib.matkv_compressed_blob_bytes.argtypes = [POINTER(Config), c_int32]
@@ -327,6 +327,10 @@ class Context:
     def decode_attn(self, layer, q, table, tail_k, tail_v, out):
         self._check(_lib.matkv_decode_attn(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
                                            _ptr(out)), "matkv_decode_attn")
+
+    def decode_attn_static(self, layer, q, table, tail_k, tail_v, out):
+        self._check(_lib.matkv_decode_attn_static(self._h, layer, _ptr(q), _ptr(table), _ptr(tail_k), _ptr(tail_v),
+                                                  _ptr(out)), "matkv_decode_attn_static")
 
     def decode_step(self, layer, hidden, w_k, w_v, q, table, tail_k, tail_v, out):
         self._check(_lib.matkv_decode_step(self._h, layer, _ptr(hidden), _ptr(w_k), _ptr(w_v), _ptr(q), _ptr(table),

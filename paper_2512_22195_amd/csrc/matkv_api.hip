@@ -65,6 +65,41 @@ struct Staging {
 
 }  // namespace
 
+// Scratch of matkv_decode_attn_static (the decode attention for callers that cannot allocate or
+// pass a workspace): arrival counters, 128 bytes apart, then the units' partial results.  Every
+// device the library runs on holds its own copy until the process ends.
+constexpr size_t kStaticCounterBytes = 1u << 20;    // 8192 (instance, KV head) pairs
+constexpr size_t kStaticPartialBytes = 7u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticCounterBytes + kStaticPartialBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.  In host code the
+// array's name is only a handle; the address comes from the runtime, once per device.
+hipError_t scratch_address(int device, char** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
+__global__ void zero_ints_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+}  // namespace
+
 struct matkv_graph {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
@@ -78,6 +113,7 @@ struct matkv_ctx {
     int device = 0;
     hipStream_t compute = nullptr, load = nullptr;
     char* workspace = nullptr;
+    char* static_scratch = nullptr;           // this device's copy of `scratch`
     WorkspaceLayout wl;
     TableLayout tl;
     float scale_log2e = 0.f;
@@ -536,6 +572,7 @@ matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t works
     }
 
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = scratch_address(c->device, &c->static_scratch);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fence_ev, hipEventDisableTiming);
     // rotary table: inv_freq in double, and inv_freq / 2pi split into two floats
     RopeEntry rope[64];
@@ -1324,10 +1361,26 @@ static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32
 }
 
 static matkv_status attn_common(matkv_ctx* c, const char* name, int prefill, int32_t layer, const void* q,
-                                const void* table, const void* tail_k, const void* tail_v, void* out) {
+                                const void* table, const void* tail_k, const void* tail_v, void* out,
+                                bool static_scratch = false) {
     AttnArgs a;
     matkv_status st = attn_args(c, name, prefill, layer, q, table, tail_k, tail_v, out, &a);
     if (st != MATKV_OK) return st;
+    if (static_scratch) {
+        const TableHost* th = find_table(c, table);
+        const size_t need_p = (size_t)th->n_decode_slots * a.Hq * (a.D + 4) * sizeof(float);
+        const size_t need_c = (size_t)a.batch * a.Hkv * kDecodeCounterStride * sizeof(int32_t);
+        if (need_p > kStaticPartialBytes || need_c > kStaticCounterBytes)
+            return fail(c, MATKV_ENOMEM, "%s: this batch needs %zu bytes of partial results and %zu bytes of counters, the static scratch holds %zu and %zu",
+                        name, need_p, need_c, kStaticPartialBytes, kStaticCounterBytes);
+        a.counters = reinterpret_cast<int32_t*>(c->static_scratch);
+        a.partials = reinterpret_cast<float*>(c->static_scratch + kStaticCounterBytes);
+        // the array keeps whatever the last call on this device left: the counters start at zero
+        // (a fill kernel, so that the call can be recorded into a graph)
+        const int n_ints = (int)(need_c / sizeof(int32_t));
+        hipLaunchKernelGGL(zero_ints_kernel, dim3((n_ints + 255) / 256), dim3(256), 0, c->compute, a.counters, n_ints);
+        HIP_TRY(c, hipGetLastError());
+    }
     const bool want_mfma = prefill || a.variant == 0 || a.variant >= 9000;
     if (attn_prefill_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_prefill(a, c->cfg.dtype, c->compute));
     else if (want_mfma && attn_mfma_supported(a, c->cfg.dtype)) HIP_TRY(c, launch_attn_mfma(a, c->cfg.dtype, c->compute));
@@ -1344,6 +1397,11 @@ matkv_status matkv_prefill_attn(matkv_ctx* c, int32_t layer, const void* q, cons
 matkv_status matkv_decode_attn(matkv_ctx* c, int32_t layer, const void* q, const void* table,
                                const void* tail_k, const void* tail_v, void* out) {
     return attn_common(c, "decode_attn", 0, layer, q, table, tail_k, tail_v, out);
+}
+
+matkv_status matkv_decode_attn_static(matkv_ctx* c, int32_t layer, const void* q, const void* table,
+                                      const void* tail_k, const void* tail_v, void* out) {
+    return attn_common(c, "decode_attn_static", 0, layer, q, table, tail_k, tail_v, out, true);
 }
 
 matkv_status matkv_decode_step(matkv_ctx* c, int32_t layer, const void* hidden, const void* w_k, const void* w_v,
