@@ -169,30 +169,48 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_rows_kernel(M
 // ---- bf16 GEMV form: a handful of token rows (a decode step), hidden a multiple of 4096 ------
 // (NL = 8) or of 3072 (NL = 6: Llama-3.2-3B).
 // One wave per rotary pair, as above, but shaped for latency (see gemv_common.h).
-template <int R, int NL>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void materialize_gemv_kernel(MaterializeArgs a) {
+// KS = 2: the hidden axis is cut in two and a pair is the work of two waves of the workgroup
+// (eight waves, two per SIMD), each with one pass of 512 * NL columns - all weight loads of the
+// launch are then requested at once instead of in two dependent rounds (hidden 8192, four
+// rows: 11.3 -> see the design notes); the odd wave hands its sums over through LDS.
+template <int R, int NL, int KS>
+__global__ __launch_bounds__(kWavesPerBlock * KS * 64) void materialize_gemv_kernel(MaterializeArgs a) {
     typedef uint16_t T;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int half = a.D / 2;
-    const int task = blockIdx.x * kWavesPerBlock + wave;     // (kv, head, pair)
-    if (task >= 2 * a.Hkv * half) return;
+    const int task = blockIdx.x * kWavesPerBlock + wave / KS;     // (kv, head, pair)
+    const int part = wave % KS;                                   // which slice of the hidden axis
+    const bool live = task < 2 * a.Hkv * half;
     const int kv = task / (a.Hkv * half);
     const int head = (task / half) % a.Hkv;
     const int j = task % half;
     const int row0 = blockIdx.y * R;
+    const int Hd_part = a.Hd / KS;
 
-    const T* w = reinterpret_cast<const T*>(kv == 0 ? a.w_k : a.w_v);
-    const T* w0 = w + ((size_t)head * a.D + j) * a.Hd;
-    const T* w1 = w0 + (size_t)half * a.Hd;
-    const T* x = reinterpret_cast<const T*>(a.hidden) + (size_t)row0 * a.Hd;
-
+    __shared__ float sm_part[KS > 1 ? kWavesPerBlock : 1][2][R];
     float acc0[R], acc1[R];
-    gemv::pair_dots<R, NL>(w0, w1, x, (size_t)a.Hd, a.n_tokens - row0, a.Hd, lane, acc0, acc1);
+    if (live) {
+        const T* w = reinterpret_cast<const T*>(kv == 0 ? a.w_k : a.w_v);
+        const T* w0 = w + ((size_t)head * a.D + j) * a.Hd + (size_t)part * Hd_part;
+        const T* w1 = w0 + (size_t)half * a.Hd;
+        const T* x = reinterpret_cast<const T*>(a.hidden) + (size_t)row0 * a.Hd + (size_t)part * Hd_part;
+        gemv::pair_dots<R, NL>(w0, w1, x, (size_t)a.Hd, a.n_tokens - row0, Hd_part, lane, acc0, acc1);
+    }
+    if constexpr (KS > 1) {
+        if (live && part == 1 && lane < R) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) if (lane == r) { sm_part[wave / KS][0][r] = acc0[r]; sm_part[wave / KS][1][r] = acc1[r]; }
+        }
+        __syncthreads();
+        if (part != 0) return;
+    }
+    if (!live) return;
 
     if (lane < R) {
         float r0 = 0.f, r1 = 0.f;
 #pragma unroll
         for (int r = 0; r < R; ++r) if (lane == r) { r0 = acc0[r]; r1 = acc1[r]; }
+        if constexpr (KS > 1) { r0 += sm_part[wave / KS][0][lane]; r1 += sm_part[wave / KS][1][lane]; }
         const RowDest d = resolve_row(a, row0 + lane);
         if (d.valid) {
             if (kv == 0) gemv::rotate_pair(a.rope[j], (float)d.pos, r0, r1);
@@ -211,18 +229,21 @@ bool gemv_supported(const MaterializeArgs& a, int dtype) {
     return dtype == MATKV_BF16 && ((a.Hd % 4096) == 0 || (a.Hd % 3072) == 0);
 }
 
-template <int NL>
+template <int NL, int KS>
 hipError_t launch_gemv_nl(const MaterializeArgs& a, int total_rows, hipStream_t s) {
     const int n_tasks = 2 * a.Hkv * (a.D / 2);
     const int bx = (n_tasks + kWavesPerBlock - 1) / kWavesPerBlock;
-    const dim3 block(kWavesPerBlock * 64);
-    if (total_rows == 1) hipLaunchKernelGGL((materialize_gemv_kernel<1, NL>), dim3(bx, 1), block, 0, s, a);
-    else if (total_rows == 2) hipLaunchKernelGGL((materialize_gemv_kernel<2, NL>), dim3(bx, 1), block, 0, s, a);
-    else hipLaunchKernelGGL((materialize_gemv_kernel<4, NL>), dim3(bx, (total_rows + 3) / 4), block, 0, s, a);
+    const dim3 block(kWavesPerBlock * KS * 64);
+    if (total_rows == 1) hipLaunchKernelGGL((materialize_gemv_kernel<1, NL, KS>), dim3(bx, 1), block, 0, s, a);
+    else if (total_rows == 2) hipLaunchKernelGGL((materialize_gemv_kernel<2, NL, KS>), dim3(bx, 1), block, 0, s, a);
+    else hipLaunchKernelGGL((materialize_gemv_kernel<4, NL, KS>), dim3(bx, (total_rows + 3) / 4), block, 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gemv(const MaterializeArgs& a, int total_rows, hipStream_t s) {
-    return (a.Hd % 4096) == 0 ? launch_gemv_nl<8>(a, total_rows, s) : launch_gemv_nl<6>(a, total_rows, s);
+    // two passes of columns per wave become one pass in each of two waves
+    if (a.Hd == 8192) return launch_gemv_nl<8, 2>(a, total_rows, s);
+    if (a.Hd == 6144) return launch_gemv_nl<6, 2>(a, total_rows, s);
+    return (a.Hd % 4096) == 0 ? launch_gemv_nl<8, 1>(a, total_rows, s) : launch_gemv_nl<6, 1>(a, total_rows, s);
 }
 
 __global__ void advance_kernel(char* table, size_t off_inst, int batch, int n, int max_tail) {

@@ -209,6 +209,170 @@ __global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a
     }
 }
 
+// ---- the same tile on eight waves ------------------------------------------------------------
+// One wave per SIMD leaves every latency of a step in the open: the operand reads from LDS, the
+// matrix instructions that wait for them, the stores of the next tile and the barrier follow
+// one another (measured: about 980 cycles per 64-column step around 256 cycles of matrix work).
+// Here the workgroup has two wave groups of 2 x 2 waves each; a step covers 128 hidden columns
+// and group g multiplies columns 64g .. 64g+63 of it, so every SIMD holds two waves whose
+// reads and matrix instructions overlap, and there is one barrier per 128 columns.  Rows of the
+// LDS tiles are 256 + 16 bytes: 16 lanes store one whole row at a time and 16 lanes read 16
+// bytes of 16 different rows without a bank conflict.  The two groups' partial sums meet in LDS
+// once, at the end: each group hands over the token blocks the other one finishes, so all eight
+// waves share the rotary epilogue.  (128-row tiles in this form - 238 registers, 139 KB of LDS -
+// measured 167 us for a 1000-token chunk against 37 us: not built.)
+constexpr int BK8 = 128;
+constexpr int STR8 = BK8 + 8;
+
+template <int BM>
+__global__ __launch_bounds__(512, 2) void materialize_mfma8_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int MI = BM / 32;              // 16-row token blocks per wave
+    constexpr int LRA = BM / 32;             // 16-byte pieces per thread and step: token tile
+    constexpr int LRB = D / 32;              //                                    weight tile
+    constexpr int A_ELEMS = BM * STR8, B_ELEMS = D * STR8;
+    __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * (A_ELEMS + B_ELEMS)];
+    static_assert(MI == 2, "the two wave groups split the token blocks of a wave in the epilogue");
+    static_assert(sizeof(float) * 8 * (MI / 2) * 4 * 64 * 4 <= sizeof(uint16_t) * 2 * (A_ELEMS + B_ELEMS), "exchange buffer");
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int kg = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
+    const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
+    const int row0 = blockIdx.y * BM;
+
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden);
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd;
+
+    // global -> LDS staging: thread t moves 16 bytes of rows t/16 + 32i, columns 8*(t%16)
+    const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
+    const uint16_t* xg[LRA];
+    const uint16_t* wg[LRB];
+#pragma unroll
+    for (int i = 0; i < LRA; ++i) {
+        const int r = min(row0 + ld_row + 32 * i, total_rows - 1);       // rows past the end repeat the last
+        xg[i] = X + (size_t)r * a.Hd + ld_col;
+    }
+#pragma unroll
+    for (int i = 0; i < LRB; ++i) wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
+
+    constexpr int NS = 4;
+    struct Stage { uint4 x[LRA], w[LRB]; };
+    Stage st[NS];
+    const int nk = a.Hd / BK8;
+    auto load_global = [&](Stage& g, int ks) {
+        const int k0 = min(ks, nk - 1) * BK8;
+#pragma unroll
+        for (int i = 0; i < LRA; ++i) g.x[i] = ldg16(xg[i] + k0);
+#pragma unroll
+        for (int i = 0; i < LRB; ++i) g.w[i] = ldg16(wg[i] + k0);
+    };
+    auto a_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS); };
+    auto b_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS) + A_ELEMS; };
+    auto store_lds = [&](int buf, const Stage& g) {
+#pragma unroll
+        for (int i = 0; i < LRA; ++i)
+            *reinterpret_cast<uint4*>(a_tile(buf) + (ld_row + 32 * i) * STR8 + ld_col) = g.x[i];
+#pragma unroll
+        for (int i = 0; i < LRB; ++i)
+            *reinterpret_cast<uint4*>(b_tile(buf) + (ld_row + 32 * i) * STR8 + ld_col) = g.w[i];
+    };
+
+    f32x4 acc[MI][4];           // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int buf) {
+        const uint16_t* At = a_tile(buf) + (16 * MI * wm + c16) * STR8 + 64 * kg + 8 * g4;
+        const uint16_t* Bt = b_tile(buf) + c16 * STR8 + 64 * kg + 8 * g4;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            bf16x8 av[MI], bv[4];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                av[mi] = *reinterpret_cast<const bf16x8*>(At + 16 * mi * STR8 + 32 * k2);
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+                const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
+                bv[ni] = *reinterpret_cast<const bf16x8*>(Bt + 16 * tn * STR8 + 32 * k2);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) load_global(st[i], i);
+    store_lds(0, st[0]);
+    lds_barrier();
+    int ks = 0;
+    auto step = [&](auto stage_tag) {
+        constexpr int S = decltype(stage_tag)::value;
+        load_global(st[(S + NS - 1) % NS], ks + NS - 1);
+        if (ks < nk) compute(ks & 1);
+        store_lds((ks + 1) & 1, st[(S + 1) % NS]);
+        lds_barrier();
+        ++ks;
+    };
+    do {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+    } while (ks < nk);
+
+    // the two groups' sums meet: group g keeps token blocks [g * MI/2, (g+1) * MI/2) and hands
+    // the others to its partner wave (same wm, wn; the tiles are dead after the last barrier)
+    constexpr int MH = MI / 2;
+    float4* xch = reinterpret_cast<float4*>(tiles);
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < MH; ++m)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const f32x4 v = acc[(1 - kg) * MH + m][ni];
+            xch[((wave * MH + m) * 4 + ni) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    __syncthreads();
+    // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16
+    uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+#pragma unroll
+    for (int m = 0; m < MH; ++m) {
+        const int mi = kg * MH + m;
+        f32x4 sum[4];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const float4 o = xch[(((wave ^ 4) * MH + m) * 4 + ni) * 64 + lane];
+            sum[ni] = acc[mi][ni];
+            sum[ni][0] += o.x; sum[ni][1] += o.y; sum[ni][2] += o.z; sum[ni][3] += o.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const RowDest d = resolve_row(a, row0 + 16 * MI * wm + 16 * mi + 4 * g4 + i);
+            if (!d.valid) continue;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int j = 16 * (2 * wn + p) + c16;           // rotary pair index, features j and j + 64
+                float lo = sum[p][i], hi = sum[p + 2][i];
+                if (kv == 0) {
+                    float c, s;
+                    rope_cs(a.rope[j], d.pos, c, s);
+                    const float k0 = lo * c - hi * s;
+                    const float k1 = lo * s + hi * c;
+                    lo = k0; hi = k1;
+                }
+                out[d.elem_off + j] = f32_to_bf16_rne(lo);
+                out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
+            }
+        }
+    }
+}
+
 // ---- skinny form: 16 .. 255 token rows (a question, a decode step of a large batch) ----------
 // Too few rows for the tiled GEMM to fill the chip (64 rows make 16 tiles).  Here a workgroup owns
 // up to 64 rows x 16 rotary pairs (features 16g .. 16g+15 and their partners 64 further) of one
@@ -342,12 +506,24 @@ hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hip
         else                   hipLaunchKernelGGL(materialize_skinny_kernel<2>, dim3(gx, (total_rows + 31) / 32), block, 0, s, a, total_rows);
         return hipGetLastError();
     }
-    const dim3 block(256);
-    if (2 * a.Hkv * ((total_rows + 127) / 128) >= 256) {
-        hipLaunchKernelGGL(materialize_mfma_kernel<128>, dim3(2 * a.Hkv, (total_rows + 127) / 128), block, 0, s, a, total_rows);
-    } else {
-        hipLaunchKernelGGL(materialize_mfma_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), block, 0, s, a, total_rows);
+    // Measured (8 KV heads, TFLOP/s at hidden 4096 / 8192): the launch is bound by what the L2 can
+    // hand to the compute units (64 x 128 tiles re-read every operand 16 times: 454 MB for a
+    // 1000-token chunk at hidden 4096, 81 % of it L2 hits, about 12 TB/s), so larger tiles win as
+    // soon as there are enough of them: 128-row tiles 715 / 765 at 4096 rows and 721 / 817 at 8192,
+    // against 549 / 610 and 585 / 666 with 64-row tiles.  While 64-row tiles make no more
+    // workgroups than there are compute units, the eight-wave form of the same tile is ahead
+    // (1000 rows: 444 / 519 against 394 / 440); with more, it holds one workgroup per compute unit
+    // where the four-wave form holds two or three, and falls behind (1206 rows: 295 against 335).
+    const int wgs64 = 2 * a.Hkv * ((total_rows + 63) / 64);
+    if ((a.Hd % BK8) == 0 && wgs64 <= 256) {
+        hipLaunchKernelGGL(materialize_mfma8_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), dim3(512), 0, s, a, total_rows);
+        return hipGetLastError();
     }
+    const dim3 block(256);
+    if (2 * a.Hkv * ((total_rows + 127) / 128) >= 256)
+        hipLaunchKernelGGL(materialize_mfma_kernel<128>, dim3(2 * a.Hkv, (total_rows + 127) / 128), block, 0, s, a, total_rows);
+    else
+        hipLaunchKernelGGL(materialize_mfma_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), block, 0, s, a, total_rows);
     return hipGetLastError();
 }
 

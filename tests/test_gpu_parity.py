@@ -167,11 +167,13 @@ def test_materialize_row_count_forms_bf16(T):
         ctx.close()
 
 
-@pytest.mark.parametrize("hidden,T", [(3072, 1), (3072, 3), (3072, 9), (6144, 2), (3072, 40), (3072, 300), (4096, 7)])
+@pytest.mark.parametrize("hidden,T", [(3072, 1), (3072, 3), (3072, 9), (6144, 2), (6144, 5), (3072, 40), (3072, 300), (4096, 7),
+                                      (8192, 1), (8192, 2), (8192, 4), (8192, 9)])
 def test_materialize_hidden_sizes_bf16(hidden, T):
-    """Hidden sizes of the paper's models beside 4096 and 8192: 3072 (the 3B model; passes of
-    six loads in the GEMV form) and a multiple of it, at row counts that take the GEMV form, the
-    skinny form and the tiled GEMM."""
+    """Hidden sizes of the paper's models: 3072 (the 3B model; passes of six loads in the GEMV
+    form) and a multiple of it, 4096, and 8192 (the 70B model: in the GEMV form two waves share
+    a rotary pair, each with half of the hidden axis), at row counts that take the GEMV form,
+    the skinny form and the tiled GEMM."""
     case = Case(f"bf16-hidden-{hidden}", n_layers=1, Hq=6, Hkv=2, D=128, hidden=hidden, dtype="bf16",
                 chunk_lens={0: 8}, retrieved=[[0]], q_lens=[1], steps=0, rope_base=500000.0, scale=1.0 / 8.0)
     from workload import normal, to_f64
