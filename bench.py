@@ -67,6 +67,21 @@ def ev():
     return torch.cuda.Event(enable_timing=True)
 
 
+_STREAMS = None
+
+
+def streams():
+    """One compute stream and one load stream for every context of this run.  The box gives a
+    process four hardware queues and the runtime deals streams onto them in creation order: with
+    a fresh pair of streams per context, a later context's two streams can land on one queue,
+    and its loads then run behind its kernels instead of beside them."""
+    global _STREAMS
+    if _STREAMS is None:
+        import torch
+        _STREAMS = (torch.cuda.Stream(device="cuda:0"), torch.cuda.Stream(device="cuda:0"))
+    return _STREAMS
+
+
 class Workload:
     """One BASELINE configuration resident on the GPU: context, synthetic inputs, captured graphs."""
 
@@ -89,7 +104,7 @@ class Workload:
         self.cfg = mk.make_config(self.nl, self.Hq, self.Hkv, self.D, self.Hd, s.dtype, s.rope_base, max_batch=self.B,
                                   max_pages=s.n_chunks, max_tail_tokens=self.max_tail, decode_units=units,
                                   decode_variant=variant)
-        self.ctx = ctx = mk.Context(self.cfg, device=dev)
+        self.ctx = ctx = mk.Context(self.cfg, *streams(), device=dev)
         self.cs = cs = ctx.compute_stream
         tdt, vs = s.torch_dtype, s.value_scale
         self.blob_bytes = mk.blob_bytes(self.cfg, self.L)
@@ -510,7 +525,8 @@ def file_leg(ctx, host, dst, L, nbytes, with_fd=None):
                 t0 = time.perf_counter()
                 tickets = [ctx.load_file(fd, i * nbytes, nbytes, L, d) for i, d in enumerate(dst)]
                 t_call = time.perf_counter() - t0
-                ctx.sync(tickets[-1])
+                for t in tickets:
+                    ctx.sync(t)
                 dt = time.perf_counter() - t0
                 if best is None or dt < best[0]:
                     best = (dt, t_call)
@@ -587,12 +603,16 @@ def load_leg(args, steps, warmup):
                 if marks is not None:
                     marks.append(ev()); marks[-1].record(cs)
 
+            def sync_all(tickets):
+                for t in tickets:
+                    ctx.sync(t)
+
             def run_stream(load_fn, n, n_serial):
                 with torch.cuda.stream(cs):
                     torch.cuda.synchronize()
                     # compute alone: every instance's blobs already in place
-                    tk = load_fn(0); ctx.sync(tk[-1])
-                    tk = load_fn(1); ctx.sync(tk[-1])
+                    tk = load_fn(0); sync_all(tk)
+                    tk = load_fn(1); sync_all(tk)
                     t0 = time.perf_counter()
                     for i in range(n_serial):
                         enqueue_compute(i, None)
@@ -600,21 +620,24 @@ def load_leg(args, steps, warmup):
                     t_comp = (time.perf_counter() - t0) / n_serial
                     # loads alone
                     t0 = time.perf_counter()
+                    hist = []
                     for i in range(n_serial):
-                        tk = load_fn(i)
-                    ctx.sync(tk[-1])
+                        if i >= 2:
+                            sync_all(hist[i - 2])     # the slot set is loaded into again
+                        hist.append(load_fn(i))
+                    sync_all(hist[-1])
                     t_ld = (time.perf_counter() - t0) / n_serial
                     # serial: load, wait for it, compute, wait for it
                     t0 = time.perf_counter()
                     for i in range(n_serial):
                         tk = load_fn(i)
-                        ctx.sync(tk[-1])
+                        sync_all(tk)
                         enqueue_compute(i, tk)
                         cs.synchronize()
                     t_ser = (time.perf_counter() - t0) / n_serial
                     # pipelined: the compute of i is enqueued, then the load of i+1 is issued
                     tk = load_fn(0)                   # steady state: the first load is already there
-                    ctx.sync(tk[-1])
+                    sync_all(tk)
                     torch.cuda.synchronize()
                     base = ev(); base.record(cs)
                     marks, lmarks = [], []
@@ -697,7 +720,7 @@ def batch16_compressed_leg(reps=10, nl=8):
     max_tail = (max(q_lens) + shape.decode_steps + 7) // 8 * 8
     cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B, max_pages=shape.n_chunks,
                          max_tail_tokens=max_tail)
-    ctx = mk.Context(cfg, device=dev)
+    ctx = mk.Context(cfg, *streams(), device=dev)
     cs = ctx.compute_stream
     try:
         with torch.cuda.stream(cs):
@@ -753,7 +776,7 @@ def compressed_leg(config_id, reps=5):
     max_tail = (max(q_lens) + shape.decode_steps + 7) // 8 * 8
     cfg = mk.make_config(nl, Hq, Hkv, D, Hd, shape.dtype, shape.rope_base, max_batch=B, max_pages=shape.n_chunks,
                          max_tail_tokens=max_tail)
-    ctx = mk.Context(cfg, device=dev)
+    ctx = mk.Context(cfg, *streams(), device=dev)
     cs = ctx.compute_stream
     try:
         cbytes, pbytes = mk.compressed_blob_bytes(cfg, L), mk.blob_bytes(cfg, L)

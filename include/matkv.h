@@ -126,7 +126,9 @@ const char* matkv_status_string(matkv_status s);
  * matkv_workspace_bytes(cfg), 256-byte aligned, zeroed by this call (on the compute
  * stream) and owned by the caller for the context's lifetime.  compute_stream and
  * load_stream are hipStream_t handles (0 = the null stream); they must differ for loads
- * to overlap compute and must both have default priority. */
+ * to overlap compute and must both have default priority.  The runtime deals a process's
+ * streams onto a few hardware queues (four by default) in creation order: two streams that
+ * land on one queue run one behind the other, so create the pair early and keep it. */
 matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t workspace_bytes,
                           void* compute_stream, void* load_stream, matkv_ctx** out);
 /* Waits for both streams, destroys events and open graphs, frees host bookkeeping. */
@@ -200,26 +202,30 @@ matkv_status matkv_materialize_tail(matkv_ctx* ctx, const void* hidden, const vo
 matkv_status matkv_load(matkv_ctx* ctx, const void* host_blob, size_t bytes, int32_t n_tokens,
                         void* device_slot, size_t slot_bytes, matkv_ticket* out);
 /* The storage half of load_KV (Section IV: materialized KVs live as raw bytes on flash storage):
- * the blob is `bytes` bytes at `offset` of the open file descriptor fd.  The call reads the
- * file in pieces into pinned bounce buffers owned by the context (4 x 8 MiB, allocated on the
- * first call) and enqueues each piece's copy on the load stream, reading the next piece while
- * the earlier copies are in flight.  It returns once the LAST piece is enqueued, i.e. it blocks
- * the calling thread for about the file-read time while work already enqueued on the compute
- * stream keeps running; the ticket then behaves as matkv_load's.  A descriptor opened with
- * O_DIRECT needs offset and bytes to be multiples of the device's block size (4096 is safe; a
- * blob of a multiple of 8 tokens is a multiple of 4096 at head_dim 128); where the system cannot
- * do direct I/O into pinned GPU-visible memory the pieces pass through one more host copy
- * (read by a helper thread of this call, so that reading and copying overlap).  On MATKV_EIO (read
- * error, file shorter than the blob) no ticket is issued and part of the slot may have been
- * overwritten; the slot then counts as the target of an unfinished load until the pieces already
- * enqueued have landed, so a table over it is refused or ordered behind them like any other.
- * Other errors as matkv_load. */
+ * the blob is `bytes` bytes at `offset` of the open file descriptor fd.  The call validates its
+ * arguments, queues the request and returns; it does not read.  Reader threads owned by the
+ * context (started at the first call) take the queued requests in order, piece by piece (8 MiB,
+ * three preads in flight at different offsets), each piece into a pinned bounce buffer and from
+ * there onto the load stream; the ticket completes when the last piece's copy does.  fd must
+ * stay open, and the file unchanged, until then.  matkv_query never blocks (MATKV_ENOTREADY
+ * while pieces are still being read); matkv_wait and matkv_sync block the host until the last
+ * piece has been enqueued (matkv_sync: until it has landed) - work already enqueued on the compute
+ * stream keeps running meanwhile.  A descriptor opened with O_DIRECT needs offset and bytes to
+ * be multiples of the device's block size (4096 is safe; a blob of a multiple of 8 tokens is a
+ * multiple of 4096 at head_dim 128); where the system cannot do direct I/O into pinned
+ * GPU-visible memory the pieces pass through one more host copy in the reader thread.  A read
+ * error or a file shorter than the blob makes the TICKET fail: matkv_wait / matkv_query /
+ * matkv_sync on it return MATKV_EIO (reason in matkv_last_error), part of the slot may have been
+ * overwritten, and a table over the slot is refused with MATKV_EIO until another load into it
+ * succeeds.  One load per slot at a time: a load (of either kind) into a slot whose file load is
+ * still being read returns MATKV_EBUSY.  Requests still queued when the context is destroyed are
+ * dropped.  Other errors as matkv_load. */
 matkv_status matkv_load_file(matkv_ctx* ctx, int fd, uint64_t offset, size_t bytes, int32_t n_tokens,
                              void* device_slot, size_t slot_bytes, matkv_ticket* out);
 /* The storage half of store_KV (Section IV): writes `bytes` of device memory (a materialized blob
  * or any part of one) to the open file descriptor at `offset`, through the same pinned bounce
- * buffers, after all work enqueued on the compute stream so far.  Synchronous: returns when the
- * last byte has been handed to pwrite (no fsync).  O_DIRECT descriptors: as for matkv_load_file.
+ * buffers, after all work enqueued on the compute stream so far and after every queued file load
+ * has been read.  Synchronous: returns when the last byte has been handed to pwrite (no fsync).  O_DIRECT descriptors: as for matkv_load_file.
  * Errors: EINVAL, EIO, EHIP, ENOMEM. */
 matkv_status matkv_store_file(matkv_ctx* ctx, int fd, uint64_t offset, const void* device_blob, size_t bytes);
 /* Makes the compute stream wait for the ticket's copy (does not block the host). */

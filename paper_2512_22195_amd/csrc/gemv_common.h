@@ -77,6 +77,9 @@ __device__ __forceinline__ void pair_dots(const uint16_t* w0, const uint16_t* w1
 // Rotation of the pair (r0, r1) by pos * theta_j: hi/lo split product in turns, whole turns
 // dropped exactly, then the hardware sine / cosine (which take turns).
 __device__ __forceinline__ void rotate_pair(const RopeEntry& e, float pos, float& r0, float& r1) {
+    // no contraction: pos * turns_hi - rint(t) as one multiply-add would take the product exactly
+    // and the rounding error of t, added back below, would count twice
+#pragma clang fp contract(off)
     const float t = pos * e.turns_hi;
     const float err = fmaf(pos, e.turns_hi, -t);
     float fr = t - rintf(t);

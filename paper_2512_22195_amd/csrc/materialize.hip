@@ -85,7 +85,9 @@ __device__ __forceinline__ void rope_cs(const RopeEntry& e, int64_t pos, float& 
         sincos((double)pos * e.inv_freq, &sd, &cd);
         c = (float)cd; s = (float)sd;
     } else {
-        // bf16 path: the angle in turns, hi/lo split product, whole turns dropped exactly
+        // bf16 path: the angle in turns, hi/lo split product, whole turns dropped exactly (no
+        // contraction: p * turns_hi - rint(t) as one multiply-add would count t's rounding error twice)
+#pragma clang fp contract(off)
         const float p = (float)pos;
         const float t = p * e.turns_hi;
         const float err = fmaf(p, e.turns_hi, -t);

@@ -73,6 +73,10 @@ __device__ __forceinline__ RowDest resolve_row(const MaterializeArgs& a, int r) 
 // cos / sin of pos * theta_j with the angle kept in turns: hi/lo split product, whole turns
 // dropped exactly, then the hardware sine / cosine (which take turns).
 __device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, float& s) {
+    // no contraction here: were p * turns_hi - rint(t) fused into one multiply-add, the product
+    // would enter exactly and the rounding error of t, added back below, would count twice
+    // (half an ulp of t: 1e-4 turns at position 20 000)
+#pragma clang fp contract(off)
     const float t = p * e.turns_hi;
     const float err = fmaf(p, e.turns_hi, -t);
     float fr = t - rintf(t);

@@ -10,7 +10,9 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <atomic>
 #include <condition_variable>
+#include <list>
 #include <mutex>
 #include <exception>
 #include <new>
@@ -27,7 +29,7 @@ namespace {
 constexpr int kTicketRing = 4096;
 constexpr int kStagingRing = 4;
 constexpr int kReleaseRing = 8;                // events marking "work on a table's old contents is enqueued"
-constexpr int kBounceRing = 4;                 // pinned pieces between a file and the load stream
+constexpr int kBounceRing = 6;                 // pinned pieces between a file and the load stream
 constexpr size_t kBounceBytes = 8u << 20;
 
 struct Ticket {
@@ -35,6 +37,10 @@ struct Ticket {
     uint64_t id = 0;          // 0 = never used
     void* slot = nullptr;
     bool done = true;         // observed complete
+    // loads from a file: the event is recorded by a reader thread once the last piece's copy is on
+    // the load stream.  Guarded by the context's io mutex.
+    bool queued = false;      // pieces still to be read or enqueued: the event is not recorded yet
+    bool failed = false;      // a read failed (the reason is in io_err)
 };
 
 struct SlotState {
@@ -125,11 +131,21 @@ struct matkv_ctx {
     std::unordered_map<const void*, TableHost> tables;
     Staging staging[kStagingRing];
     int staging_next = 0;
-    Staging bounce[kBounceRing];              // allocated at the first matkv_load_file
+    Staging bounce[kBounceRing];              // allocated at the first matkv_load_file / matkv_store_file
     int bounce_next = 0;
-    char* plain_buf = nullptr;                // see matkv_load_file: direct reads that cannot target pinned memory
-    char* plain_buf2 = nullptr;               // second one: a reader thread fills one while the other is copied out
-    bool read_via_plain = false;
+    char* plain_buf = nullptr;                // matkv_store_file: direct writes that cannot come from pinned memory
+    std::atomic<bool> read_via_plain{false};  // direct I/O cannot target the pinned buffers on this system
+    // file loads: requests wait in a queue, reader threads take them piece by piece
+    struct FileReq {
+        int fd; uint64_t offset; size_t bytes; char* dst; Ticket* ticket;
+        size_t n_pieces, next_piece, pieces_done;
+    };
+    std::mutex io_mu;
+    std::condition_variable io_work, io_done;
+    std::list<FileReq> io_queue;              // front = the oldest request (a list: readers keep pointers into it)
+    std::vector<std::thread> io_readers;
+    bool io_stop = false;
+    char io_err[256] = {0};                   // reason of the last failed read
     hipEvent_t fence_ev = nullptr;
     hipEvent_t release_ev[kReleaseRing] = {};
     int release_next = 0;
@@ -601,6 +617,12 @@ matkv_status matkv_create(const matkv_config* cfg, void* workspace, size_t works
 
 matkv_status matkv_destroy(matkv_ctx* c) {
     if (!c) return MATKV_EINVAL;
+    {
+        std::lock_guard<std::mutex> lk(c->io_mu);
+        c->io_stop = true;                   // requests still queued are dropped with the context
+    }
+    c->io_work.notify_all();
+    for (std::thread& th : c->io_readers) th.join();
     (void)hipStreamSynchronize(c->load);
     (void)hipStreamSynchronize(c->compute);
     for (matkv_graph* g : c->graphs) {
@@ -619,7 +641,6 @@ matkv_status matkv_destroy(matkv_ctx* c) {
         if (c->bounce[i].host) (void)hipHostFree(c->bounce[i].host);
     }
     free(c->plain_buf);
-    free(c->plain_buf2);
     for (int i = 0; i < kReleaseRing; ++i)
         if (c->release_ev[i]) (void)hipEventDestroy(c->release_ev[i]);
     if (c->fence_ev) (void)hipEventDestroy(c->fence_ev);
@@ -703,6 +724,19 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
 
 // ------------------------------------------------------------------------------------ L ----
 
+// Where a file load stands: 0 = all its copies are on the load stream (or it is no file load),
+// 1 = pieces still to be read, 2 = a read failed.  block: wait until it is not 1.
+static int file_state(matkv_ctx* c, Ticket* t, bool block) {
+    std::unique_lock<std::mutex> lk(c->io_mu);
+    if (block) c->io_done.wait(lk, [&] { return !t->queued; });
+    if (t->queued) return 1;
+    return t->failed ? 2 : 0;
+}
+static matkv_status file_failed(matkv_ctx* c) {
+    std::lock_guard<std::mutex> lk(c->io_mu);
+    return fail(c, MATKV_EIO, "%s", c->io_err);
+}
+
 // Checks shared by both load entry points; on success *t_out is the ticket record to fill and
 // the load stream has been ordered after compute work that may still read the slot.
 static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, int32_t n_tokens,
@@ -724,6 +758,7 @@ static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, i
     }
     Ticket& t = c->tickets[c->next_ticket % kTicketRing];
     if (t.id != 0 && !t.done) {
+        if (file_state(c, &t, false) == 1) return fail(c, MATKV_EBUSY, "%s: %d tickets outstanding", name, kTicketRing);
         hipError_t q = hipEventQuery(t.ev);
         if (q == hipErrorNotReady) { (void)hipGetLastError(); return fail(c, MATKV_EBUSY, "%s: %d tickets outstanding", name, kTicketRing); }
         if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
@@ -731,6 +766,13 @@ static matkv_status load_prepare(matkv_ctx* c, const char* name, size_t bytes, i
     }
     if (!t.ev) HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
     SlotState& s = c->slots[device_slot];
+    if (s.pending) {
+        // a file load into this slot whose pieces are still being read: a second load would mix
+        // its copies with theirs on the load stream
+        Ticket& prev = c->tickets[s.pending % kTicketRing];
+        if (prev.id == s.pending && file_state(c, &prev, false) == 1)
+            return fail(c, MATKV_EBUSY, "%s: a load from a file into this slot is still being read", name);
+    }
     if (s.refs > 0) {
         // a live table still points into the slot: order the copy after all compute work so far
         HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
@@ -750,7 +792,7 @@ static matkv_status load_finish(matkv_ctx* c, Ticket* t, void* device_slot, matk
     HIP_TRY(c, hipEventRecord(t->ev, c->load));
     t->id = c->next_ticket++;
     t->slot = device_slot;
-    t->done = false;
+    t->done = false; t->queued = false; t->failed = false;
     SlotState& s = c->slots[device_slot];
     s.pending = t->id;
     s.waited = false;
@@ -777,132 +819,106 @@ matkv_status matkv_load(matkv_ctx* c, const void* host_blob, size_t bytes, int32
     MATKV_CATCH(c, "load")
 }
 
-// File -> two plain page-aligned buffers (a reader thread, one pread per piece) -> pinned bounce
-// ring (this thread's memcpy) -> load stream.  Used where direct I/O cannot target the pinned
-// buffers: the file read of piece k+1 then overlaps the host copy and the enqueue of piece k.
-static matkv_status load_file_via_plain(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, char* device_dst) {
-    if (!c->plain_buf2 && posix_memalign(reinterpret_cast<void**>(&c->plain_buf2), 4096, kBounceBytes) != 0) {
-        c->plain_buf2 = nullptr;
-        return fail(c, MATKV_ENOMEM, "load_file: out of host memory");
-    }
-    char* plain[2] = {c->plain_buf, c->plain_buf2};
-    const size_t n_pieces = (bytes + kBounceBytes - 1) / kBounceBytes;
-    auto piece_bytes = [&](size_t k) { return std::min(kBounceBytes, bytes - k * kBounceBytes); };
-    std::mutex mu;
-    std::condition_variable cv;
-    bool full[2] = {false, false};
-    bool stop = false;
-    int read_errno = 0;            // > 0: pread failed; -1: file ended early
-    uint64_t bad_at = 0;
-    std::thread reader([&] {
-        for (size_t k = 0; k < n_pieces; ++k) {
-            {
-                std::unique_lock<std::mutex> lk(mu);
-                cv.wait(lk, [&] { return !full[k & 1] || stop; });
-                if (stop) return;
-            }
-            const size_t piece = piece_bytes(k);
+// ---- loads from a file: reader threads owned by the context -------------------------------
+// matkv_load_file queues a request and returns.  kIoReaders threads take the queued requests
+// piece by piece (8 MiB, several preads in flight at different offsets), each into one of its own
+// two pinned bounce buffers - through a plain page-aligned buffer of its own where direct I/O
+// cannot target pinned memory - and enqueue the piece's copy on the load stream.  The thread
+// that finishes a request's last piece records the ticket's event behind all its copies.
+constexpr int kIoReaders = 3;
+static_assert(kBounceRing >= 2 * kIoReaders, "two bounce buffers per reader");
+
+static void io_reader_main(matkv_ctx* c, int reader) {
+    (void)hipSetDevice(c->device);
+    char* plain = nullptr;
+    int flip = 0;
+    std::unique_lock<std::mutex> lk(c->io_mu);
+    for (;;) {
+        matkv_ctx::FileReq* rq = nullptr;
+        c->io_work.wait(lk, [&] {
+            if (c->io_stop) return true;
+            for (auto& r : c->io_queue) if (r.next_piece < r.n_pieces) { rq = &r; return true; }
+            return false;
+        });
+        if (c->io_stop) break;
+        const size_t k = rq->next_piece++;
+        const bool skip = rq->ticket->failed;           // an earlier piece failed: nothing more is read
+        lk.unlock();
+
+        char why[200] = {0};
+        if (!skip) {
+            Staging& b = c->bounce[2 * reader + flip];
+            flip ^= 1;
+            hipError_t he = b.used ? hipEventSynchronize(b.ev) : hipSuccess;     // its last copy has left the buffer
+            const size_t piece = std::min(kBounceBytes, rq->bytes - k * kBounceBytes);
+            const uint64_t at = rq->offset + k * kBounceBytes;
             size_t got = 0;
-            int err = 0;
-            while (got < piece) {
-                ssize_t r = pread(fd, plain[k & 1] + got, piece - got, (off_t)(offset + k * kBounceBytes + got));
-                if (r < 0 && errno == EINTR) continue;
-                if (r <= 0) { err = r < 0 ? errno : -1; break; }
-                got += (size_t)r;
-            }
-            std::lock_guard<std::mutex> lk(mu);
-            if (err) { read_errno = err; bad_at = offset + k * kBounceBytes + got; stop = true; cv.notify_all(); return; }
-            full[k & 1] = true;
-            cv.notify_all();
-        }
-    });
-    matkv_status st = MATKV_OK;
-    hipError_t he = hipSuccess;
-    for (size_t k = 0; k < n_pieces && st == MATKV_OK; ++k) {
-        {
-            std::unique_lock<std::mutex> lk(mu);
-            cv.wait(lk, [&] { return full[k & 1] || stop; });
-            if (!full[k & 1]) break;                   // the reader gave up
-        }
-        Staging& b = c->bounce[c->bounce_next];
-        c->bounce_next = (c->bounce_next + 1) % kBounceRing;
-        if (b.used) he = hipEventSynchronize(b.ev);
-        const size_t piece = piece_bytes(k);
-        if (he == hipSuccess) {
-            memcpy(b.host, plain[k & 1], piece);
-            he = hipMemcpyAsync(device_dst + k * kBounceBytes, b.host, piece, hipMemcpyHostToDevice, c->load);
-        }
-        if (he == hipSuccess) he = hipEventRecord(b.ev, c->load);
-        {
-            std::lock_guard<std::mutex> lk(mu);
-            full[k & 1] = false;
-            if (he != hipSuccess) stop = true;
-            cv.notify_all();
-        }
-        if (he != hipSuccess) break;
-        b.used = true;
-    }
-    {
-        std::lock_guard<std::mutex> lk(mu);
-        stop = true;
-        cv.notify_all();
-    }
-    reader.join();
-    if (he != hipSuccess) return hip_fail(c, he, "load_file: copy of a piece");
-    if (read_errno > 0) return fail(c, MATKV_EIO, "load_file: pread at %llu: %s", (unsigned long long)bad_at, strerror(read_errno));
-    if (read_errno < 0) return fail(c, MATKV_EIO, "load_file: file ends %llu bytes short of the blob", (unsigned long long)(offset + bytes - bad_at));
-    return st;
-}
-
-// After a failed file load some pieces may already be on the load stream: the slot is marked as
-// the target of a load that nobody has waited for (a ticket of its own, never handed out), so
-// that a later matkv_assemble orders the compute stream behind those copies instead of
-// reading a slot that is still being written.
-static void load_abandon(matkv_ctx* c, Ticket* t, void* device_slot) {
-    if (hipEventRecord(t->ev, c->load) != hipSuccess) { (void)hipGetLastError(); return; }
-    t->id = c->next_ticket++;
-    t->slot = device_slot;
-    t->done = false;
-    SlotState& s = c->slots[device_slot];
-    s.pending = t->id;
-    s.waited = false;
-}
-
-static matkv_status load_file_pieces(matkv_ctx* c, int fd, uint64_t offset, size_t bytes, void* device_slot) {
-    // piece k+1 is read from the file while the copies of the pieces before it are in flight
-    size_t done = 0;
-    while (done < bytes) {
-        if (c->read_via_plain)
-            return load_file_via_plain(c, fd, offset + done, bytes - done, static_cast<char*>(device_slot) + done);
-        Staging& b = c->bounce[c->bounce_next];
-        c->bounce_next = (c->bounce_next + 1) % kBounceRing;
-        if (b.used) HIP_TRY(c, hipEventSynchronize(b.ev));
-        const size_t piece = std::min(kBounceBytes, bytes - done);
-        size_t got = 0;
-        while (got < piece) {
-            char* dest = c->read_via_plain ? c->plain_buf : b.host;
-            ssize_t r = pread(fd, dest + got, piece - got, (off_t)(offset + done + got));
-            if (r < 0 && errno == EINTR) continue;
-            if (r < 0 && errno == EFAULT && !c->read_via_plain) {
-                // direct I/O cannot pin the device-mapped bounce buffer on this system: from now
-                // on read into plain page-aligned memory and copy into the bounce buffer
-                if (!c->plain_buf && posix_memalign(reinterpret_cast<void**>(&c->plain_buf), 4096, kBounceBytes) != 0) {
-                    c->plain_buf = nullptr;
-                    return fail(c, MATKV_ENOMEM, "load_file: out of host memory");
+            while (he == hipSuccess && !why[0] && got < piece) {
+                const bool via_plain = c->read_via_plain.load();
+                if (via_plain && !plain && posix_memalign(reinterpret_cast<void**>(&plain), 4096, kBounceBytes) != 0) {
+                    plain = nullptr;
+                    snprintf(why, sizeof(why), "out of host memory");
+                    break;
                 }
-                c->read_via_plain = true;
-                if (got) memcpy(c->plain_buf, b.host, got);
-                continue;
+                char* dest = via_plain ? plain : b.host;
+                const ssize_t r = pread(rq->fd, dest + got, piece - got, (off_t)(at + got));
+                if (r < 0 && errno == EINTR) continue;
+                if (r < 0 && errno == EFAULT && !via_plain) {
+                    // direct I/O cannot pin the device-mapped bounce buffer on this system: from now
+                    // on read into plain page-aligned memory and copy into the bounce buffer
+                    c->read_via_plain.store(true);
+                    got = 0;
+                    continue;
+                }
+                if (r < 0) snprintf(why, sizeof(why), "pread at %llu: %s", (unsigned long long)(at + got), strerror(errno));
+                else if (r == 0) snprintf(why, sizeof(why), "file ends %llu bytes short of the blob",
+                                          (unsigned long long)(rq->offset + rq->bytes - (at + got)));
+                else got += (size_t)r;
             }
-            if (r < 0) return fail(c, MATKV_EIO, "load_file: pread at %llu: %s", (unsigned long long)(offset + done + got), strerror(errno));
-            if (r == 0) return fail(c, MATKV_EIO, "load_file: file ends %zu bytes short of the blob", bytes - done - got);
-            got += (size_t)r;
+            if (he == hipSuccess && !why[0]) {
+                if (c->read_via_plain.load()) memcpy(b.host, plain, piece);
+                he = hipMemcpyAsync(rq->dst + k * kBounceBytes, b.host, piece, hipMemcpyHostToDevice, c->load);
+                if (he == hipSuccess) he = hipEventRecord(b.ev, c->load);
+                b.used = true;
+            }
+            if (he != hipSuccess) {
+                (void)hipGetLastError();
+                snprintf(why, sizeof(why), "copy of a piece: %s", hipGetErrorString(he));
+            }
         }
-        if (c->read_via_plain) memcpy(b.host, c->plain_buf, piece);
-        HIP_TRY(c, hipMemcpyAsync(static_cast<char*>(device_slot) + done, b.host, piece, hipMemcpyHostToDevice, c->load));
-        HIP_TRY(c, hipEventRecord(b.ev, c->load));
-        b.used = true;
-        done += piece;
+
+        lk.lock();
+        if (why[0] && !rq->ticket->failed) {
+            rq->ticket->failed = true;
+            snprintf(c->io_err, sizeof(c->io_err), "load_file: %s", why);
+        }
+        if (++rq->pieces_done == rq->n_pieces) {
+            // every copy of this request is on the load stream (or the request was given up)
+            if (hipEventRecord(rq->ticket->ev, c->load) != hipSuccess) {
+                (void)hipGetLastError();
+                rq->ticket->failed = true;
+            }
+            rq->ticket->queued = false;
+            for (auto it = c->io_queue.begin(); it != c->io_queue.end(); ++it)
+                if (&*it == rq) { c->io_queue.erase(it); break; }
+            c->io_done.notify_all();
+        }
+    }
+    free(plain);
+}
+
+// Blocks until no file load is queued or being read (the store path and the destructor share
+// the bounce buffers with the readers).
+static void io_drain(matkv_ctx* c) {
+    std::unique_lock<std::mutex> lk(c->io_mu);
+    c->io_done.wait(lk, [&] { return c->io_queue.empty(); });
+}
+
+static matkv_status bounce_buffers(matkv_ctx* c) {
+    for (int i = 0; i < kBounceRing; ++i) {
+        if (c->bounce[i].host) continue;
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
     }
     return MATKV_OK;
 }
@@ -916,17 +932,28 @@ matkv_status matkv_load_file(matkv_ctx* c, int fd, uint64_t offset, size_t bytes
     Ticket* t;
     st = load_prepare(c, "load_file", bytes, n_tokens, device_slot, slot_bytes, &t);
     if (st != MATKV_OK) return st;
-    for (int i = 0; i < kBounceRing; ++i) {
-        if (c->bounce[i].host) continue;
-        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
+    st = bounce_buffers(c);
+    if (st != MATKV_OK) return st;
+    if (c->io_readers.empty()) {
+        c->io_readers.reserve(kIoReaders);
+        for (int r = 0; r < kIoReaders; ++r) c->io_readers.emplace_back(io_reader_main, c, r);
     }
-    st = load_file_pieces(c, fd, offset, bytes, device_slot);
-    if (st != MATKV_OK) {
-        if (!c->sticky_hip) load_abandon(c, t, device_slot);
-        return st;
+    {
+        std::lock_guard<std::mutex> lk(c->io_mu);
+        t->id = c->next_ticket++;
+        t->slot = device_slot;
+        t->done = false; t->queued = true; t->failed = false;
+        matkv_ctx::FileReq rq{};
+        rq.fd = fd; rq.offset = offset; rq.bytes = bytes; rq.dst = static_cast<char*>(device_slot); rq.ticket = t;
+        rq.n_pieces = (bytes + kBounceBytes - 1) / kBounceBytes; rq.next_piece = 0; rq.pieces_done = 0;
+        c->io_queue.push_back(rq);
     }
-    return load_finish(c, t, device_slot, out);
+    c->io_work.notify_all();
+    SlotState& s = c->slots[device_slot];
+    s.pending = t->id;
+    s.waited = false;
+    out->id = t->id;
+    return MATKV_OK;
     MATKV_CATCH(c, "load_file")
 }
 
@@ -941,11 +968,9 @@ matkv_status matkv_store_file(matkv_ctx* c, int fd, uint64_t offset, const void*
         (void)hipGetLastError();
         return fail(c, MATKV_EINVAL, "store_file: blob is not device memory");
     }
-    for (int i = 0; i < kBounceRing; ++i) {
-        if (c->bounce[i].host) continue;
-        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->bounce[i].host), kBounceBytes, hipHostMallocDefault));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->bounce[i].ev, hipEventDisableTiming));
-    }
+    st = bounce_buffers(c);
+    if (st != MATKV_OK) return st;
+    io_drain(c);                             // the reader threads use the same bounce buffers
     // the blob was produced on the compute stream: the copies out follow what is enqueued there
     HIP_TRY(c, hipEventRecord(c->fence_ev, c->compute));
     HIP_TRY(c, hipStreamWaitEvent(c->load, c->fence_ev, 0));
@@ -968,18 +993,25 @@ matkv_status matkv_store_file(matkv_ctx* c, int fd, uint64_t offset, const void*
         HIP_TRY(c, hipEventSynchronize(b.ev));
         const char* src = b.host;
         const size_t piece = piece_bytes(k);
-        if (c->read_via_plain) { memcpy(c->plain_buf, b.host, piece); src = c->plain_buf; }
+        if (c->read_via_plain.load()) {
+            if (!c->plain_buf && posix_memalign(reinterpret_cast<void**>(&c->plain_buf), 4096, kBounceBytes) != 0) {
+                c->plain_buf = nullptr;
+                return fail(c, MATKV_ENOMEM, "store_file: out of host memory");
+            }
+            memcpy(c->plain_buf, b.host, piece);
+            src = c->plain_buf;
+        }
         size_t put = 0;
         while (put < piece) {
             ssize_t r = pwrite(fd, src + put, piece - put, (off_t)(offset + k * kBounceBytes + put));
             if (r < 0 && errno == EINTR) continue;
-            if (r < 0 && errno == EFAULT && !c->read_via_plain) {
-                // direct I/O cannot pin the device-mapped bounce buffer on this system (see load_file)
+            if (r < 0 && errno == EFAULT && !c->read_via_plain.load()) {
+                // direct I/O cannot pin the device-mapped bounce buffer on this system (see the reader threads)
                 if (!c->plain_buf && posix_memalign(reinterpret_cast<void**>(&c->plain_buf), 4096, kBounceBytes) != 0) {
                     c->plain_buf = nullptr;
                     return fail(c, MATKV_ENOMEM, "store_file: out of host memory");
                 }
-                c->read_via_plain = true;
+                c->read_via_plain.store(true);
                 memcpy(c->plain_buf, b.host, piece);
                 src = c->plain_buf;
                 continue;
@@ -1006,6 +1038,9 @@ matkv_status matkv_wait(matkv_ctx* c, matkv_ticket tk) {
     Ticket* t;
     st = ticket_lookup(c, tk, &t);
     if (st != MATKV_OK || !t) return st;
+    // a file load still being read: the event is not recorded yet, so the host waits here until
+    // the last piece's copy is on the load stream (the copies themselves are not waited for)
+    if (!t->done && file_state(c, t, true) == 2) return file_failed(c);
     if (!t->done) HIP_TRY(c, hipStreamWaitEvent(c->compute, t->ev, 0));
     auto it = c->slots.find(t->slot);
     if (it != c->slots.end() && it->second.pending == tk.id) it->second.waited = true;
@@ -1019,6 +1054,9 @@ matkv_status matkv_query(matkv_ctx* c, matkv_ticket tk) {
     st = ticket_lookup(c, tk, &t);
     if (st != MATKV_OK || !t) return st;
     if (t->done) return MATKV_OK;
+    const int fs = file_state(c, t, false);
+    if (fs == 1) return MATKV_ENOTREADY;
+    if (fs == 2) return file_failed(c);
     hipError_t q = hipEventQuery(t->ev);
     if (q == hipErrorNotReady) { (void)hipGetLastError(); return MATKV_ENOTREADY; }
     if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
@@ -1032,6 +1070,10 @@ matkv_status matkv_sync(matkv_ctx* c, matkv_ticket tk) {
     Ticket* t;
     st = ticket_lookup(c, tk, &t);
     if (st != MATKV_OK || !t) return st;
+    if (!t->done && file_state(c, t, true) == 2) {
+        (void)hipEventSynchronize(t->ev);     // the pieces that did get enqueued
+        return file_failed(c);
+    }
     if (!t->done) { HIP_TRY(c, hipEventSynchronize(t->ev)); t->done = true; }
     return MATKV_OK;
 }
@@ -1045,6 +1087,9 @@ static matkv_status slot_ready(matkv_ctx* c, const void* slot, const char* name)
     Ticket& t = c->tickets[it->second.pending % kTicketRing];
     bool done = (t.id != it->second.pending) || t.done;
     if (!done) {
+        const int fs = file_state(c, &t, false);
+        if (fs == 1) return fail(c, MATKV_ENOTREADY, "%s: a page's load from a file is still being read", name);
+        if (fs == 2) return fail(c, MATKV_EIO, "%s: a page's load from a file failed", name);
         hipError_t q = hipEventQuery(t.ev);
         if (q == hipSuccess) { t.done = true; done = true; }
         else if (q == hipErrorNotReady) (void)hipGetLastError();

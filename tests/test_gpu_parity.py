@@ -425,6 +425,86 @@ def test_config4_70b_shape_sampled():
     assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
 
 
+def _full_size_resident(config_id, layers, instances, steps, prefill_rows):
+    """A BASELINE configuration at its stated size with EVERY layer resident in HBM, inputs drawn
+    on the GPU (the bench's recipe), pushed through the launch configuration bench.py times:
+    question projection + prefill attention per layer, then decode steps replayed from one
+    recorded graph of matkv_decode_step calls.  The oracle reads back and checks the sampled
+    (layer, instance, step / question row) outputs."""
+    from workload import normal
+    case = chain.case_from_config(config_id)
+    case.steps = max(steps) + 1
+    c, dev = case, "cuda:0"
+    ctx = chain.make_context(case)
+    cs = ctx.compute_stream
+    try:
+        with torch.cuda.stream(cs):
+            blobs = {cid: normal((c.name, "blob", cid), (c.n_layers, 2, c.Hkv, n, c.D), c.scale, c.tdtype, dev)
+                     for cid, n in c.chunk_lens.items()}
+            total_q = sum(c.q_lens)
+            w = normal((c.name, "w"), (c.n_layers, 2, c.Hkv * c.D, c.hidden), c.scale, c.tdtype, dev)
+            x_q = normal((c.name, "x_q"), (c.n_layers, total_q, c.hidden), c.scale, c.tdtype, dev)
+            x_dec = normal((c.name, "x_dec"), (c.steps, c.n_layers, c.batch, c.hidden), c.scale, c.tdtype, dev)
+            q_pre = normal((c.name, "q_pre"), (c.n_layers, total_q, c.Hq, c.D), c.scale, c.tdtype, dev)
+            q_dec = normal((c.name, "q_dec"), (c.steps, c.n_layers, c.batch, c.Hq, c.D), c.scale, c.tdtype, dev)
+            tail = ctx.new_tail()
+            table = ctx.new_table()
+            ctx.assemble([[(blobs[cid], c.chunk_lens[cid]) for cid in r] for r in c.retrieved], c.q_lens, table)
+            o_pre = torch.full_like(q_pre, float("nan"))
+            o_dec = torch.full_like(q_dec, float("nan"))
+            for l in range(c.n_layers):
+                ctx.materialize_tail(x_q[l], w[l, 0], w[l, 1], table, -1, tail[l, 0], tail[l, 1])
+                ctx.prefill_attn(l, q_pre[l], table, tail[l, 0], tail[l, 1], o_pre[l])
+            x_cur, q_cur, o_cur = torch.empty_like(x_dec[0]), torch.empty_like(q_dec[0]), torch.empty_like(o_dec[0])
+            ctx.graph_begin()
+            ctx.advance(table, 1)
+            for l in range(c.n_layers):
+                ctx.decode_step(l, x_cur[l], w[l, 0], w[l, 1], q_cur[l], table, tail[l, 0], tail[l, 1], o_cur[l])
+            g = ctx.graph_end()
+            for t in range(c.steps):
+                x_cur.copy_(x_dec[t]); q_cur.copy_(q_dec[t])
+                ctx.graph_launch(g)
+                o_dec[t].copy_(o_cur)
+            cs.synchronize()
+            ctx.graph_destroy(g)
+        assert torch.isfinite(o_pre.float()).all() and torch.isfinite(o_dec.float()).all()
+        # the oracle's tail rows: the question rows as the GPU projected them are checked against
+        # the oracle's own projection first (sampled layers), then both sides attend over the
+        # oracle's rounded rows
+        import oracle
+        from workload import to_f64
+        from oracle.matkv_oracle import store_round
+        cu = chain.cu_q(c)
+        tail_ref = torch.zeros_like(tail)
+        for l in layers:
+            for b in instances:
+                p0 = float(sum(c.chunk_lens[cid] for cid in c.retrieved[b]))
+                K, V = oracle.materialize(to_f64(x_q[l, cu[b]:cu[b + 1]]), to_f64(w[l, 0]), to_f64(w[l, 1]), c.Hkv, c.D, p0, c.rope_base)
+                lq = c.q_lens[b]
+                chain.compare_materialized(c, tail[l, 0, b, :, :lq].cpu(), K, f"question K layer {l} inst {b}")
+                chain.compare_materialized(c, tail[l, 1, b, :, :lq].cpu(), V, f"question V layer {l} inst {b}")
+                tail_ref[l, 0, b, :, :lq] = torch.from_numpy(store_round(K, c.dtype)).to(tail.dtype)
+                tail_ref[l, 1, b, :, :lq] = torch.from_numpy(store_round(V, c.dtype)).to(tail.dtype)
+        inp = dict(blobs=blobs, tail=tail_ref, q_pre=q_pre, q_dec=q_dec)
+        pre, dec = chain.run_oracle_attention(c, inp, layers=layers, steps=steps, instances=instances,
+                                              prefill_rows=prefill_rows, proj=dict(w=w, x_dec=x_dec))
+        return chain.compare_attention(c, o_pre.cpu(), o_dec.cpu(), pre, dec)
+    finally:
+        ctx.close()
+
+
+def test_config3_full_size_all_layers_resident():
+    """Config 3 as stated: batch 16, five 1000-token chunks each out of a pool of 200 (shared
+    pages), questions of 32..128 tokens, all 32 layers resident (8.5 GB of chunk KV)."""
+    _full_size_resident(3, layers=[0, 15, 31], instances=[0, 9, 15], steps=[0, 3], prefill_rows=[0, 17, 127])
+
+
+def test_config4_full_size_all_layers_resident():
+    """Config 4 as stated: 70B layer shape (64 / 8 heads, hidden 8192), batch 4, twenty 1000-token
+    chunks each, 128-token questions, all 80 layers resident (26 GB of chunk KV)."""
+    _full_size_resident(4, layers=[0, 41, 79], instances=[0, 3], steps=[0, 2], prefill_rows=[0, 64, 127])
+
+
 # ------------------------------------------------------------------ boundary behaviour ------
 def test_load_is_byte_exact_and_validates():
     from paper_2512_22195_amd import binding as mk
@@ -473,10 +553,12 @@ def test_chain_through_files(tmp_path):
 
 
 def test_load_file_is_byte_exact(tmp_path):
-    """matkv_load_file: blobs read from a file at nonzero offsets, through the bounce buffers
-    (a blob of several 8 MiB pieces with a ragged last one, and a small one), land byte-exact in
-    their slots; the loaded pages then serve an attention call; a file that ends early gives
-    MATKV_EIO and no ticket; O_DIRECT is used when the filesystem allows it."""
+    """matkv_load_file: blobs read from a file at nonzero offsets by the context's reader threads,
+    through the bounce buffers (a blob of several 8 MiB pieces with a ragged last one, and a small
+    one), land byte-exact in their slots; the call returns once the request is queued and the
+    ticket completes when the last piece's copy does; the loaded pages then serve an attention
+    call; a file that ends early makes the ticket fail with MATKV_EIO, and a table over that slot
+    is refused; O_DIRECT is used when the filesystem allows it."""
     import os
     from paper_2512_22195_amd import binding as mk
     case = Case("load-file", n_layers=3, Hq=8, Hkv=4, D=128, hidden=64, dtype="bf16",
@@ -494,6 +576,7 @@ def test_load_file_is_byte_exact(tmp_path):
             f.write(b"\0" * off0); f.write(b0.numpy().tobytes())
             f.write(b"\0" * 8192); f.write(b1.numpy().tobytes())
             f.flush(); os.fsync(f.fileno())
+        ran = 0
         for flags in (os.O_RDONLY | getattr(os, "O_DIRECT", 0), os.O_RDONLY):
             try:
                 fd = os.open(path, flags)
@@ -501,28 +584,79 @@ def test_load_file_is_byte_exact(tmp_path):
                 continue                                    # no O_DIRECT on this filesystem
             try:
                 s0, s1 = ctx.new_slot(3000), ctx.new_slot(40)
+                t0 = ctx.load_file(fd, off0, n0, 3000, s0)
+                t1 = ctx.load_file(fd, off1, n1, 40, s1)
                 try:
-                    t0 = ctx.load_file(fd, off0, n0, 3000, s0)
+                    ctx.sync(t0)
                 except mk.MatKVError as e:
                     if flags & getattr(os, "O_DIRECT", 0) and e.status == mk.EIO:
                         continue                            # direct reads refused by this filesystem
                     raise
-                t1 = ctx.load_file(fd, off1, n1, 40, s1)
                 ctx.sync(t1)
                 assert ctx.query(t0) and ctx.query(t1)
                 assert torch.equal(s0.cpu(), b0) and torch.equal(s1.cpu(), b1)
-                with pytest.raises(mk.MatKVError) as e:     # the file ends inside the blob
-                    ctx.load_file(fd, off1 + 4096, n1, 40, s1)
+                ran += 1
+                # the file ends inside the blob: the request is accepted, its ticket fails
+                t_bad = ctx.load_file(fd, off1 + 4096, n1, 40, s1)
+                for fn in (ctx.sync, ctx.wait, ctx.query):
+                    with pytest.raises(mk.MatKVError) as e:
+                        fn(t_bad)
+                    assert e.value.status == mk.EIO
+                table = ctx.new_table()
+                with pytest.raises(mk.MatKVError) as e:     # a table over a slot whose load failed
+                    ctx.assemble([[(s0, 3000), (s1, 40)]], [2], table)
                 assert e.value.status == mk.EIO
-                with pytest.raises(mk.MatKVError) as e:     # wrong byte count
+                with pytest.raises(mk.MatKVError) as e:     # wrong byte count: refused before anything is queued
                     ctx.load_file(fd, off1, n1 - 4096, 40, s1)
                 assert e.value.status == mk.EINVAL
-                # pages loaded from the file are ordinary pages
-                ctx.wait(t0); ctx.wait(t1)
-                table = ctx.new_table()
+                # a good load into the same slot puts it right; pages loaded from the file are ordinary pages
+                t1 = ctx.load_file(fd, off1, n1, 40, s1)
+                ctx.wait(t0); ctx.wait(t1)                  # wait() blocks the host until the pieces are enqueued
                 ctx.assemble([[(s0, 3000), (s1, 40)]], [2], table)
+                ctx.sync(t1)
+                assert torch.equal(s1.cpu(), b1)
             finally:
                 os.close(fd)
+        assert ran >= 1
+    finally:
+        ctx.close()
+
+
+def test_load_file_returns_before_the_read_is_done(tmp_path):
+    """Ten 8 MiB-piece blobs queued back to back: the calls return without reading (far less time
+    than the reads take), the first ticket completes before the last, and everything is
+    byte-exact at the end."""
+    import os, time
+    from paper_2512_22195_amd import binding as mk
+    case = Case("load-file-async", n_layers=8, Hq=8, Hkv=8, D=128, hidden=64, dtype="bf16",
+                chunk_lens={0: 2048}, retrieved=[[0]], q_lens=[2], steps=0)
+    ctx = chain.make_context(case)
+    path = str(tmp_path / "many.bin")
+    try:
+        n = mk.blob_bytes(ctx.cfg, 2048)                    # 67 MB
+        g = torch.Generator().manual_seed(11)
+        blobs = [torch.randint(0, 256, (n,), dtype=torch.uint8, generator=g) for _ in range(10)]
+        with open(path, "wb") as f:
+            for b in blobs:
+                f.write(b.numpy().tobytes())
+            f.flush(); os.fsync(f.fileno())
+        fd = os.open(path, os.O_RDONLY)
+        try:
+            slots = [ctx.new_slot(2048) for _ in blobs]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            tickets = [ctx.load_file(fd, i * n, n, 2048, s) for i, s in enumerate(slots)]
+            t_calls = time.perf_counter() - t0
+            ctx.sync(tickets[0])
+            last_done_early = ctx.query(tickets[-1])
+            ctx.sync(tickets[-1])
+            t_all = time.perf_counter() - t0
+            assert t_calls < 0.5 * t_all, f"calls took {t_calls:.3f} s of {t_all:.3f} s"
+            assert not last_done_early or t_all < 0.05      # 600 MB do not arrive with the first 67
+            for s, b in zip(slots, blobs):
+                assert torch.equal(s.cpu(), b)
+        finally:
+            os.close(fd)
     finally:
         ctx.close()
 
