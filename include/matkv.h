@@ -86,6 +86,9 @@ typedef struct {
     int32_t decode_variant;   /* decode kernel shape; 0 = default.  9000 + 10 * (blocks of loads in flight)
                                * + waves = matrix-core kernel (9024, 9034, 9028, 9022 are built);
                                * 100 * waves + loads in flight = plain-ALU kernel (402 .. 108) */
+    int32_t out_f32;          /* 1: the attention entry points of a bf16 configuration write `out` as float
+                               * ([..][Hq][D] floats, unrounded; Q, K and V stay bf16); 0: out has the
+                               * configuration's element type.  Ignored for MATKV_F32. */
 } matkv_config;
 
 /* One loaded chunk: the device slot that holds its blob and its token count (host struct). */

@@ -37,7 +37,7 @@ class Config(Structure):
                 ("head_dim", c_int32), ("hidden", c_int32), ("dtype", c_int32),
                 ("rope_base", c_float), ("softmax_scale", c_float),
                 ("max_batch", c_int32), ("max_pages", c_int32), ("max_tail_tokens", c_int32),
-                ("decode_units", c_int32), ("decode_variant", c_int32)]
+                ("decode_units", c_int32), ("decode_variant", c_int32), ("out_f32", c_int32)]
 
 
 class Page(Structure):
@@ -127,13 +127,13 @@ def lib():
 
 def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, hidden, dtype, rope_base,
                 max_batch, max_pages, max_tail_tokens, softmax_scale=0.0, decode_units=0,
-                decode_variant=0) -> Config:
+                decode_variant=0, out_f32=0) -> Config:
     if isinstance(dtype, torch.dtype):
         dtype = F32 if dtype == torch.float32 else BF16
     elif isinstance(dtype, str):
         dtype = F32 if dtype == "f32" else BF16
     return Config(n_layers, n_q_heads, n_kv_heads, head_dim, hidden, dtype, rope_base,
-                  softmax_scale, max_batch, max_pages, max_tail_tokens, decode_units, decode_variant)
+                  softmax_scale, max_batch, max_pages, max_tail_tokens, decode_units, decode_variant, int(out_f32))
 
 
 def blob_bytes(cfg: Config, n_tokens: int) -> int:

@@ -77,6 +77,10 @@ __device__ __forceinline__ float lane_xor(float v, int off, int lane) {
     return __shfl_xor(v, off);
 }
 
+// One pair of output elements of a bf16 launch: rounded to bf16, or as they are when the
+// configuration asks for float outputs.
+__device__ __forceinline__ void store_out2(void* out, bool f32, size_t idx, float x, float y);
+
 struct KernelArgs {
     const void* __restrict__ q;
     void* __restrict__ out;
@@ -86,8 +90,14 @@ struct KernelArgs {
     int32_t* __restrict__ counters;
     int32_t layer, Hq, Hkv, max_tail, rows, prefill;
     int32_t cstride;             // ints between two arrival counters
+    int32_t out_f32;             // bf16 path: outputs leave as float, unrounded
     float scale_log2e;
 };
+
+__device__ __forceinline__ void store_out2(void* out, bool f32, size_t idx, float x, float y) {
+    if (f32) *reinterpret_cast<float2*>(reinterpret_cast<float*>(out) + idx) = make_float2(x, y);
+    else *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(out) + idx) = (uint32_t)f32_to_bf16_rne(x) | ((uint32_t)f32_to_bf16_rne(y) << 16);
+}
 
 // Arrival counter of (instance, KV head, row z).  Decode launches keep every counter on a
 // 128-byte line of its own: agent-scope atomics on one line are served one after the other, and
@@ -103,6 +113,7 @@ inline KernelArgs make_kernel_args(const AttnArgs& a) {
     k.layer = a.layer; k.Hq = a.Hq; k.Hkv = a.Hkv; k.max_tail = a.max_tail; k.rows = a.rows;
     k.prefill = a.prefill; k.scale_log2e = a.scale_log2e;
     k.cstride = a.prefill ? 1 : kDecodeCounterStride;
+    k.out_f32 = a.out_f32;
     return k;
 }
 
@@ -289,9 +300,12 @@ __device__ __forceinline__ void merge_units(const KernelArgs& a, int unit0, int 
         for (int cb = 0; cb < CB; ++cb) {
             if (!live[cb]) continue;
             const float inv = 1.0f / Lsum[cb];
-            T* op = reinterpret_cast<T*>(a.out) + ((size_t)rms[cb].q_row * a.Hq + rms[cb].head) * D + dd[cb];
+            const size_t oidx = ((size_t)rms[cb].q_row * a.Hq + rms[cb].head) * D + dd[cb];
+            T* op = reinterpret_cast<T*>(a.out) + oidx;
             if constexpr (sizeof(T) == 4) {
                 *reinterpret_cast<float2*>(op) = make_float2(ox[cb] * inv, oy[cb] * inv);
+            } else if (a.out_f32) {
+                *reinterpret_cast<float2*>(reinterpret_cast<float*>(a.out) + oidx) = make_float2(ox[cb] * inv, oy[cb] * inv);
             } else {
                 *reinterpret_cast<uint32_t*>(op) =
                     (uint32_t)f32_to_bf16_rne(ox[cb] * inv) | ((uint32_t)f32_to_bf16_rne(oy[cb] * inv) << 16);

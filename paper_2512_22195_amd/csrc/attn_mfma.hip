@@ -109,8 +109,7 @@ __device__ __forceinline__ void merge_decode_step(const KernelArgs& a, const Ins
     ox = fmaf(ox, cold, __uint_as_float(vw << 16) * cx);
     oy = fmaf(oy, cold, __uint_as_float(vw & 0xffff0000u) * cx);
     const float inv = 1.0f / L;
-    *reinterpret_cast<uint32_t*>(reinterpret_cast<T*>(a.out) + ((size_t)b * a.Hq + head) * D + d) =
-        (uint32_t)f32_to_bf16_rne(ox * inv) | ((uint32_t)f32_to_bf16_rne(oy * inv) << 16);
+    store_out2(a.out, a.out_f32, ((size_t)b * a.Hq + head) * D + d, ox * inv, oy * inv);
     }
 }
 
@@ -209,8 +208,7 @@ __device__ __forceinline__ void merge_shared(const KernelArgs& a, const int4* us
         for (int cb = 0; cb < CB; ++cb) {
             if (n[cb] == 0) continue;
             const float inv = 1.0f / L[cb];
-            *reinterpret_cast<uint32_t*>(reinterpret_cast<T*>(a.out) + ((size_t)inst[cb] * a.Hq + head[cb]) * D + dd[cb]) =
-                (uint32_t)f32_to_bf16_rne(ox[cb] * inv) | ((uint32_t)f32_to_bf16_rne(oy[cb] * inv) << 16);
+            store_out2(a.out, a.out_f32, ((size_t)inst[cb] * a.Hq + head[cb]) * D + dd[cb], ox[cb] * inv, oy[cb] * inv);
         }
     }
 }

@@ -356,13 +356,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
         const int r = m / G, head = kvh * G + m % G;
         if (single) {
             const float inv = 1.0f / ol[j][0];
-            T* op = reinterpret_cast<T*>(a.out) + ((size_t)(inst.cu_q + r) * a.Hq + head) * D + 4 * g4;
+            const size_t oidx = ((size_t)(inst.cu_q + r) * a.Hq + head) * D + 4 * g4;
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                uint2 w;
-                w.x = (uint32_t)f32_to_bf16_rne(ot[j][s][0] * inv) | ((uint32_t)f32_to_bf16_rne(ot[j][s][1] * inv) << 16);
-                w.y = (uint32_t)f32_to_bf16_rne(ot[j][s][2] * inv) | ((uint32_t)f32_to_bf16_rne(ot[j][s][3] * inv) << 16);
-                *reinterpret_cast<uint2*>(op + 16 * s) = w;
+                store_out2(a.out, a.out_f32, oidx + 16 * s, ot[j][s][0] * inv, ot[j][s][1] * inv);
+                store_out2(a.out, a.out_f32, oidx + 16 * s + 2, ot[j][s][2] * inv, ot[j][s][3] * inv);
             }
         } else {
             float* prow = a.partials + (((size_t)blockIdx.x * a.rows + r) * a.Hq + head) * kPartialStride(D);
@@ -428,10 +426,9 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     }
     if (n_units == 0) return;
     const float inv = 1.0f / L;
-    uint2 o;
-    o.x = (uint32_t)f32_to_bf16_rne(acc.x * inv) | ((uint32_t)f32_to_bf16_rne(acc.y * inv) << 16);
-    o.y = (uint32_t)f32_to_bf16_rne(acc.z * inv) | ((uint32_t)f32_to_bf16_rne(acc.w * inv) << 16);
-    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + ((size_t)q_row * a.Hq + head) * D + 4 * hl) = o;
+    const size_t oidx = ((size_t)q_row * a.Hq + head) * D + 4 * hl;
+    store_out2(a.out, a.out_f32, oidx, acc.x * inv, acc.y * inv);
+    store_out2(a.out, a.out_f32, oidx + 2, acc.z * inv, acc.w * inv);
 }
 
 template <int G, int MS, int TB, bool F8, int NW = 4>

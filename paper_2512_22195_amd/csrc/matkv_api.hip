@@ -216,6 +216,7 @@ matkv_status check_config(const matkv_config* c, const char** why) {
     if (c->max_tail_tokens % 8) { *why = "max_tail_tokens must be a multiple of 8"; return MATKV_EINVAL; }
     if (c->decode_units < 0 || c->decode_units > kMaxDecodeUnitsPerInstance) { *why = "decode_units outside 0..256"; return MATKV_EINVAL; }
     if (c->decode_variant < 0) { *why = "decode_variant negative"; return MATKV_EINVAL; }
+    if (c->out_f32 != 0 && c->out_f32 != 1) { *why = "out_f32 must be 0 or 1"; return MATKV_EINVAL; }
     if (c->max_batch > 1024 || c->max_pages > 4096) { *why = "max_batch <= 1024, max_pages <= 4096"; return MATKV_EINVAL; }
     if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return MATKV_EUNSUPPORTED; }
     const int g = c->n_q_heads / c->n_kv_heads;
@@ -1399,6 +1400,7 @@ static matkv_status attn_args(matkv_ctx* c, const char* name, int prefill, int32
     a.batch = th->batch; a.total_q = th->total_q; a.kv_fmt = th->kv_fmt;
     a.max_unit_items = prefill ? th->max_punit_items : 0;
     a.scale_log2e = c->scale_log2e;
+    a.out_f32 = c->cfg.dtype == MATKV_BF16 && c->cfg.out_f32;
     a.off_inst = c->tl.off_inst; a.off_items = c->tl.off_items;
     a.off_units = prefill ? c->tl.off_punits : (a.shared ? c->tl.off_sunits : c->tl.off_dunits);
     *out_args = a;
@@ -1504,6 +1506,7 @@ matkv_status matkv_chunk_attn(matkv_ctx* c, int32_t layer, const void* q, const 
     a.prefill = 2; a.rows = n_tokens; a.n_units = 1; a.max_units_inst = 1;
     a.batch = 1; a.total_q = n_tokens; a.max_unit_items = 1;
     a.scale_log2e = c->scale_log2e;
+    a.out_f32 = cfg.dtype == MATKV_BF16 && cfg.out_f32;
     const bool tiles = attn_prefill_supported(a, cfg.dtype);
     if (!tiles) {
         // the row-per-workgroup kernel leaves a partial and a counter per (row, head) in the workspace

@@ -168,6 +168,7 @@ struct AttnArgs {
     float scale_log2e;
     int32_t kv_fmt;            // matkv_page_format of every page of the table
     int32_t shared;            // decode over the shared partition (units = SUnit records)
+    int32_t out_f32;           // bf16 configurations: q / out of the attention calls: out is float
     int32_t variant;           // kernel shape: 0 = default; 9000 + waves = matrix-core kernel;
                                // waves * 100 + loads in flight = plain-ALU kernel
     size_t off_inst, off_items, off_units;
