@@ -373,7 +373,7 @@ int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const i
         distinct_tokens += pu.n_tokens;
         all_tokens += (long)pu.n_tokens * (long)pu.users.size();
     }
-    if (distinct_tokens * 2 > all_tokens) return 0;
+    if (distinct_tokens * 2 > all_tokens && !getenv("MATKV_SHARED_ALWAYS")) return 0;
 
     const int group = kMaxSharedUsers / (cfg.n_q_heads / cfg.n_kv_heads);
     auto groups_of = [&](const PageUse& pu) { return ((long)pu.users.size() + group - 1) / group; };
