@@ -264,23 +264,24 @@ int32_t matkv_plan_decode_units(const matkv_config* cfg, const int32_t* page_tok
 /* Host-only preview of the shared decode partition (see matkv_table_shared_units) that
  * matkv_assemble would build for a batch (no GPU is touched).  page_ids_host /
  * page_tokens_host: [batch][max_pages], instance b uses its first n_pages_host[b] entries;
- * equal ids mean the same slot.  Unit u is written to units_out[u * 36 ..]: id of its first
- * page (-1: only a tail), page tokens it streams, 1 if it ends with its user's tail, number
- * of users, then 16 pairs (instance, partial slot), -1 where unused.  slots_out (may be NULL):
- * [batch][2] = first partial slot and number of slots of each instance.  Returns the number
- * of units (at most cap), 0 if no shared partition would be built, -1 on a bad argument. */
+ * equal ids mean the same slot.  Unit u is written to units_out[u * 52 ..]: id of its first
+ * page (-1: it starts with a tail), page tokens it streams, the instance whose tail it holds
+ * (-1: none), number of users, then 16 triples (instance, partial slot, page tokens of the
+ * unit that this user sees), -1 / -1 / 0 where unused.  slots_out (may be NULL): [batch][2] =
+ * first partial slot and number of slots of each instance.  Returns the number of units (at
+ * most cap), 0 if no shared partition would be built, -1 on a bad argument. */
 int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids_host,
                                 const int32_t* page_tokens_host, const int32_t* n_pages_host,
                                 const int32_t* q_len_host, int32_t batch, int32_t* units_out,
                                 int32_t cap, int32_t* slots_out);
 /* Decode work units of the table's shared partition, 0 if matkv_assemble built none, -1 if the
  * table is unknown.  When two or more instances of a batch point at the same slot (the same
- * chunk, retrieved by several requests), matkv_assemble cuts the DISTINCT pages into pieces
- * and lists with each piece the instances that use it: the decode attention then reads a
- * shared chunk once for up to 16 / (Hq/Hkv) instances at a time instead of once per
- * instance.  Built only when at most half of the batch's page tokens are distinct (below that
- * the cache hierarchy serves the repeated reads well enough), for plain pages, bf16,
- * head_dim 128, decode_units = 0 and decode_variant = 0; results are the same as without it (every instance still gets exact
+ * chunk, retrieved by several requests), matkv_assemble cuts the batch's DISTINCT pages and its
+ * tails into equal work units and notes with every piece the instances that use it: the decode
+ * attention then reads a shared chunk once for up to 16 / (Hq/Hkv) instances at a time instead
+ * of once per instance.  Built when the distinct pages are at least a twentieth fewer tokens
+ * than all uses together, for plain pages, bf16, head_dim 128, decode_units = 0 and
+ * decode_variant = 0; results are the same as without it (every instance still gets exact
  * attention over its own cache). */
 int32_t matkv_table_shared_units(matkv_ctx* ctx, const void* table);
 /* tail_len[b] += n for every instance of the table (a one-wave kernel; capturable). */

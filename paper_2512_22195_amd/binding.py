@@ -162,8 +162,9 @@ def config_check(cfg: Config) -> int:
 
 def plan_shared_units(cfg: Config, pages, q_lens):
     """Shared decode partition matkv_assemble would build.  pages: per instance a list of
-    (page id, tokens).  Returns (units, slots) with units = list of dicts {page, tokens, tail,
-    users: [(instance, slot)]} and slots = [(first, count)] per instance; ([], None) if none is built."""
+    (page id, tokens).  Returns (units, slots) with units = list of dicts {page, tokens, tail
+    (the instance whose tail the unit holds, or None), users: [(instance, slot, page tokens of
+    the unit this user sees)]} and slots = [(first, count)] per instance; ([], None) if none is built."""
     batch, mp = len(pages), max(cfg.max_pages, 1)
     ids, toks = (c_int32 * (batch * mp))(), (c_int32 * (batch * mp))()
     for b, plist in enumerate(pages):
@@ -171,13 +172,14 @@ def plan_shared_units(cfg: Config, pages, q_lens):
             ids[b * mp + i], toks[b * mp + i] = pid, n
     npg = (c_int32 * batch)(*[len(p) for p in pages])
     ql = (c_int32 * batch)(*q_lens)
-    cap, w = 4096, 36
+    cap, w = 4096, 52
     out, slots = (c_int32 * (cap * w))(), (c_int32 * (2 * batch))()
     n = _lib.matkv_plan_shared_units(byref(cfg), ids, toks, npg, ql, batch, out, cap, slots)
     if n < 0:
         raise MatKVError(EINVAL, "matkv_plan_shared_units")
-    units = [dict(page=out[u * w], tokens=out[u * w + 1], tail=bool(out[u * w + 2]),
-                  users=[(out[u * w + 4 + 2 * k], out[u * w + 5 + 2 * k]) for k in range(out[u * w + 3])]) for u in range(n)]
+    units = [dict(page=out[u * w], tokens=out[u * w + 1], tail=(out[u * w + 2] if out[u * w + 2] >= 0 else None),
+                  users=[(out[u * w + 4 + 3 * k], out[u * w + 5 + 3 * k], out[u * w + 6 + 3 * k]) for k in range(out[u * w + 3])])
+             for u in range(n)]
     return units, ([(slots[2 * b], slots[2 * b + 1]) for b in range(batch)] if n else None)
 
 

@@ -127,6 +127,7 @@ struct BlockRef {
     bool is_tail;
     bool valid;
     float sk, sv;    // compressed page: scale of this head's K and V codes (else unused)
+    int umask;       // shared decode units: which of the unit's users see this block
 };
 
 // Scales of KV head kvh of a compressed page at `layer`: the blob's scale table is
@@ -184,7 +185,7 @@ struct Walker {
     }
     __device__ __forceinline__ BlockRef<T> next() {
         BlockRef<T> r;
-        r.valid = false; r.is_tail = false; r.k = nullptr; r.v = nullptr; r.t0 = 0; r.tok_end = 0;
+        r.valid = false; r.is_tail = false; r.k = nullptr; r.v = nullptr; r.t0 = 0; r.tok_end = 0; r.umask = 0;
         if (pos >= pos_end) return r;
         int rows = rows_of(item);
         while (pos >= item_pos0 + rows) {
@@ -198,6 +199,7 @@ struct Walker {
             }
         }
         r.sk = sk; r.sv = sv;
+        r.umask = item.umask;
         if (item.base) {
             page_heads(item, r);
         } else {

@@ -301,10 +301,12 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && 
     auto dim0 = [&](int c) { return F8 ? 16 * g4 + 8 * (c & 1) + 64 * (c >> 1) : 32 * c + 8 * g4; };
     bf16x8 bq[MS][4];
     int vis[MS];                                        // tail rows this lane's row may see
+    int row_user[MS];                                   // shared units: index of the row's user in the unit's list
 #pragma unroll
     for (int j = 0; j < MS; ++j) {
         const int m = min(m0 + 16 * j + c16, n_m - 1);
         const int r = m / G, g = m % G;
+        row_user[j] = r;
         int q_row = a.prefill ? q_row0 + r : q_row0;
         if (SH) {           // the record's user list comes through scalar loads; pick this lane's
 #pragma unroll
@@ -369,7 +371,8 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && 
                 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[1][c]), bq[j][c], s1, 0, 0, 0);
             }
             // lane holds tokens t0 + 4*g4 + i (s0) and t0 + 16 + 4*g4 + i (s1) of its row
-            const int limit = r.is_tail ? min(r.tok_end, vis[j]) : r.tok_end;
+            // (shared units: a row whose user does not use this piece sees none of it)
+            const int limit = (SH && !((r.umask >> row_user[j]) & 1)) ? 0 : (r.is_tail ? min(r.tok_end, vis[j]) : r.tok_end);
             const int tb = r.t0 + 4 * g4;
             float sv[8];
             bool ok[8];

@@ -320,7 +320,7 @@ __global__ void chunk_table_kernel(char* table, int n_tokens) {
     in.sslot0 = 0; in.n_sslots = 0; in.pad = 0;
     Item it;
     it.base = 0; it.page_tokens = n_tokens; it.tok0 = 0; it.ntok = n_tokens;
-    it.fmt = 0; it.scales16 = 0; it.pad = 0;
+    it.fmt = 0; it.scales16 = 0; it.umask = 0;
     Unit un;
     un.inst = 0; un.item0 = 0; un.n_items = 1; un.idx_in_inst = 0; un.n_units_inst = 1;
     un.unit0_inst = 0; un.has_tail = 1; un.page_tokens = 0; un.first = it;

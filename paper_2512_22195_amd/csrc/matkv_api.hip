@@ -335,144 +335,195 @@ int build_units(const matkv_page* pages, int n_pages, int inst, int n_units, int
 }
 
 // Shared decode partition (instances of a batch that retrieved the same chunk read it once).
-// Pages with one user stay with that user: an instance's private pages and its tail are cut
-// into multi-page units exactly as in the per-instance partition.  Every page with two or more
-// users is cut into pieces of about the same token count, its users into groups of at most
-// 16 / G instances (one matrix tile of rows), and every (piece, group) is one unit.  Each
-// (unit, user) pair gets one of that user's consecutive partial slots.  Returns the number of units, 0 if the batch shares no page or the partition
-// does not fit the table (then the per-instance partition is used).
+// The batch's DISTINCT pages and its tails form one stream of token rows - per instance its
+// private pages, then the shared pages it uses first, then its tail - which is cut into equal
+// runs, one workgroup (per KV head) each, never more workgroups than compute units.  A run is a
+// list of pieces like any decode unit; every piece carries the set of the unit's users that
+// may see it (Item::umask), the unit lists its users (at most 16 / G: the rows of its matrix
+// tile are (user, query head) pairs) and each (unit, user) pair gets one of that user's
+// consecutive partial slots.  A run ends early where one more piece would bring a user too many
+// or a second tail.  tokens_out (may be null): [unit][kMaxSharedUsers] page tokens each user sees.
+// Returns the number of units, 0 if the batch shares no page worth the trouble or the
+// partition does not fit the table (then the per-instance partition is used).
 int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const int32_t* n_pages, int batch,
-                       int max_sunits, int max_items, InstanceInfo* insts, Item* items, int* n_items, SUnit* sunits) {
+                       int max_sunits, int max_items, InstanceInfo* insts, Item* items, int* n_items, SUnit* sunits,
+                       int32_t* tokens_out = nullptr) {
     struct PageUse { const void* slot; int n_tokens; std::vector<int> users; };
     std::vector<PageUse> distinct;
     std::unordered_map<const void*, std::vector<int>> by_slot;   // slot -> indices into distinct
-    std::vector<std::vector<int>> page_of(batch);                // instance -> distinct index of each of its pages
-    bool any_shared = false;
     for (int b = 0; b < batch; ++b)
         for (int p = 0; p < n_pages[b]; ++p) {
             const matkv_page& pg = pages[(size_t)b * cfg.max_pages + p];
+            // (an instance that lists one page twice attends to it twice: the second occurrence is a
+            // page of its own)
             int found = -1;
-            for (int i : by_slot[pg.slot]) if (distinct[i].n_tokens == pg.n_tokens) found = i;
+            for (int i : by_slot[pg.slot])
+                if (distinct[i].n_tokens == pg.n_tokens &&
+                    std::find(distinct[i].users.begin(), distinct[i].users.end(), b) == distinct[i].users.end()) { found = i; break; }
             if (found < 0) {
                 found = (int)distinct.size();
                 distinct.push_back(PageUse{pg.slot, pg.n_tokens, {}});
                 by_slot[pg.slot].push_back(found);
-            } else {
-                any_shared = true;
             }
             distinct[found].users.push_back(b);
-            page_of[b].push_back(found);
         }
-    if (!any_shared) return 0;
-    // Worth it only under heavy sharing: the chip's last-level cache already serves most repeated
-    // reads of a page within one launch, and this partition's units are less even than the
-    // per-instance one's.  Measured at batch 16, five 1000-token chunks each: 81 % distinct page
-    // tokens 61.1 us against 59.0 us per-instance; 41 % 42.8 against 43.7; 6 % 30.5 against 33.8.
+    // Worth it when the distinct pages are at least a twentieth fewer bytes than all uses together
+    // (measured at batch 16, five 1000-token chunks each, per layer: 81 % distinct 57.5 us
+    // per-instance against see the design notes).
     long all_tokens = 0, distinct_tokens = 0;
     for (const PageUse& pu : distinct) {
         distinct_tokens += pu.n_tokens;
         all_tokens += (long)pu.n_tokens * (long)pu.users.size();
     }
-    if (distinct_tokens * 2 > all_tokens && !getenv("MATKV_SHARED_ALWAYS")) return 0;
+    if (distinct_tokens * 20 > all_tokens * 19) return 0;
 
-    const int group = kMaxSharedUsers / (cfg.n_q_heads / cfg.n_kv_heads);
-    auto groups_of = [&](const PageUse& pu) { return ((long)pu.users.size() + group - 1) / group; };
-    long work_tokens = 0;
-    for (const PageUse& pu : distinct) work_tokens += (long)pu.n_tokens * groups_of(pu);
-    // Unit size: the smallest (from 256 tokens up) with which the launch has at most 512
-    // workgroups - all resident at once, two per compute unit.  Measured at batch 16 with
-    // 8 KV heads: 256 or 512 equal workgroups 58-59 us, 384 of them 66 us, 528 of them 70 us.
-    std::vector<long> priv_tokens(batch, 0);
-    for (int b = 0; b < batch; ++b)
-        for (int p = 0; p < n_pages[b]; ++p)
-            if (distinct[page_of[b][p]].users.size() == 1) priv_tokens[b] += pages[(size_t)b * cfg.max_pages + p].n_tokens;
-    long per = std::max<long>(256, work_tokens * cfg.n_kv_heads / 512);
-    auto pieces_with = [](long n_tokens, long per_) { return (int)std::max<long>(1, (n_tokens + per_ / 2) / per_); };
-    auto units_with = [&](long per_) {
-        long n = 0;
-        for (int b = 0; b < batch; ++b) n += pieces_with(priv_tokens[b], per_);
+    const int G = cfg.n_q_heads / cfg.n_kv_heads;
+    const int cap_users = kMaxSharedUsers / G;
+    // a page with more users than a tile has rows for is streamed once per group of them: each
+    // group becomes a page of its own from here on
+    {
+        std::vector<PageUse> split;
         for (const PageUse& pu : distinct)
-            if (pu.users.size() >= 2) n += pieces_with(pu.n_tokens, per_) * groups_of(pu);
+            for (size_t u0 = 0; u0 < pu.users.size(); u0 += cap_users)
+                split.push_back(PageUse{pu.slot, pu.n_tokens,
+                                        std::vector<int>(pu.users.begin() + u0, pu.users.begin() + std::min(pu.users.size(), u0 + cap_users))});
+        distinct.swap(split);
+    }
+    // the stream: per instance the pages it is the first user of (private ones first), then its
+    // tail; an instance that is the first user of no page gets its tail behind a page it uses (one
+    // tail per page at most), so that tails stay apart: a unit holds at most one
+    struct Piece { int page; int inst; long gran; std::vector<int> users; };    // page < 0: the tail of inst
+    std::vector<Piece> stream;
+    std::vector<char> tail_placed(batch, 0), owns(batch, 0);
+    for (const PageUse& pu : distinct) owns[pu.users[0]] = 1;
+    long total_gran = 0;
+    auto push_tail = [&](int b) {
+        const int tail_est = insts[b].q_len + (cfg.max_tail_tokens - insts[b].q_len) / 2;
+        stream.push_back(Piece{-1, b, (tail_est + 7) / 8, {b}});
+        total_gran += stream.back().gran;
+        tail_placed[b] = 1;
+    };
+    for (int b = 0; b < batch; ++b) {
+        for (int pass = 0; pass < 2; ++pass)                     // private pages first
+            for (size_t di = 0; di < distinct.size(); ++di) {
+                const PageUse& pu = distinct[di];
+                if (pu.users[0] != b || (pass == 0) != (pu.users.size() == 1)) continue;
+                stream.push_back(Piece{(int)di, b, (pu.n_tokens + 7) / 8, pu.users});
+                total_gran += stream.back().gran;
+                for (int u : pu.users)
+                    if (!tail_placed[u] && !owns[u]) { push_tail(u); break; }
+            }
+        if (owns[b]) push_tail(b);
+    }
+    for (int b = 0; b < batch; ++b)
+        if (!tail_placed[b]) push_tail(b);
+    int n_target = 256 / cfg.n_kv_heads;
+    if (n_target > total_gran * 8 / 128) n_target = (int)(total_gran * 8 / 128);
+    if (n_target < 1) n_target = 1;
+
+    // Cuts the stream into units of `per` granules; returns the number of units, or -1 if they do
+    // not fit.  emit = false only counts.
+    std::vector<std::vector<int>> slot_of;                       // [unit][user index] -> partial slot (second pass)
+    auto cut = [&](long per, bool emit, int first_item) -> int {
+        int n = 0, n_it = first_item;
+        long room = 0;                                           // granules the open unit may still take
+        std::vector<int> users;                                  // of the open unit
+        bool open = false, has_tail = false;
+        SUnit* su = nullptr;
+        auto close_unit = [&]() {
+            if (!open) return;
+            if (emit) {
+                su->u.n_items = n_it - su->u.item0;
+                su->u.first = items[su->u.item0];
+                su->n_users = (int)users.size();
+                for (size_t k = 0; k < users.size(); ++k) su->users[k].inst = users[k];
+            }
+            ++n; open = false;
+        };
+        auto open_unit = [&]() {
+            if (emit) {
+                su = &sunits[n];
+                memset(su, 0, sizeof(*su));
+                su->u.item0 = n_it;
+            }
+            users.clear(); room = per; open = true; has_tail = false;
+        };
+        for (const Piece& pc : stream) {
+            const std::vector<int>& pusers = pc.users;
+            long g = 0;
+            while (g < pc.gran) {
+                if (open) {
+                    int fresh = 0;
+                    for (int u : pusers) if (std::find(users.begin(), users.end(), u) == users.end()) ++fresh;
+                    if ((int)users.size() + fresh > cap_users || (pc.page < 0 && has_tail) || room <= 0) close_unit();
+                }
+                if (!open) {
+                    if (n >= max_sunits) return -1;
+                    open_unit();
+                }
+                uint32_t mask = 0;
+                for (int u : pusers) {
+                    auto it = std::find(users.begin(), users.end(), u);
+                    if (it == users.end()) { users.push_back(u); it = users.end() - 1; }
+                    mask |= 1u << (int)(it - users.begin());
+                }
+                // a tail is never cut; a page piece takes what room there is
+                const long take = pc.page < 0 ? pc.gran : std::min(pc.gran - g, room);
+                if (emit) {
+                    if (n_it >= max_items) return -1;
+                    Item it;
+                    memset(&it, 0, sizeof(it));
+                    if (pc.page < 0) {
+                        it.base = 0; it.page_tokens = cfg.max_tail_tokens; it.tok0 = 0; it.ntok = cfg.max_tail_tokens;
+                        su->u.has_tail = 1; su->u.inst = pc.inst;
+                    } else {
+                        const PageUse& pu = distinct[pc.page];
+                        it.base = reinterpret_cast<uint64_t>(pu.slot);
+                        it.page_tokens = pu.n_tokens;
+                        it.tok0 = (int)(g * 8);
+                        it.ntok = (int)std::min<long>(pu.n_tokens, (g + take) * 8) - it.tok0;
+                        su->u.page_tokens += it.ntok;
+                        if (tokens_out)
+                            for (int k = 0; k < kMaxSharedUsers; ++k)
+                                if (mask >> k & 1) tokens_out[(size_t)n * kMaxSharedUsers + k] += it.ntok;
+                    }
+                    it.umask = (int32_t)mask;
+                    items[n_it] = it;
+                }
+                ++n_it;
+                if (pc.page < 0) has_tail = true;
+                g += take; room -= take;
+            }
+        }
+        close_unit();
+        if (emit) *n_items = n_it;
         return n;
     };
-    for (int it = 0; it < 64 && units_with(per) * cfg.n_kv_heads > 512; ++it) per += std::max<long>(8, per / 32);
-    auto pieces_of = [&](long n_tokens) { return pieces_with(n_tokens, per); };
-
-    // private runs: the instance's single-user pages in order, then its tail
-    std::vector<std::vector<matkv_page>> priv(batch);
-    std::vector<int> priv_units(batch), count(batch, 0);
-    long n_units = 0;
-    for (int b = 0; b < batch; ++b) {
-        long tokens = 0;
-        for (int p = 0; p < n_pages[b]; ++p)
-            if (distinct[page_of[b][p]].users.size() == 1) {
-                priv[b].push_back(pages[(size_t)b * cfg.max_pages + p]);
-                tokens += pages[(size_t)b * cfg.max_pages + p].n_tokens;
-            }
-        priv_units[b] = std::min(pieces_of(tokens), kMaxDecodeUnitsPerInstance / 2);
-        count[b] = priv_units[b];                       // build_units may make fewer; fixed below
-        n_units += priv_units[b];
+    // unit size: the smallest with which the launch has no more workgroups than compute units
+    long per = std::max<long>(16, (total_gran + n_target - 1) / n_target);
+    int n = cut(per, false, *n_items);
+    for (int it = 0; it < 64 && (n < 0 || n * cfg.n_kv_heads > 256); ++it) {
+        per += std::max<long>(1, per / 32);
+        n = cut(per, false, *n_items);
     }
-    for (const PageUse& pu : distinct) {
-        if (pu.users.size() < 2) continue;
-        const int np = pieces_of(pu.n_tokens);
-        for (int b : pu.users) count[b] += np;
-        n_units += (long)np * groups_of(pu);
-    }
-    if (n_units > max_sunits) return 0;
-    for (int b = 0; b < batch; ++b)
-        if (count[b] > kMaxDecodeUnitsPerInstance) return 0;
-    long need_items = *n_items;
-    for (int b = 0; b < batch; ++b) need_items += priv_units[b] + (long)priv[b].size() + 2;
-    if (need_items > max_items) return 0;
-
-    // private units first (they are the long ones), then the shared pieces
-    int n = 0;
-    std::vector<Unit> tmp((size_t)kMaxDecodeUnitsPerInstance);
-    std::vector<std::vector<int>> priv_index(batch);    // instance -> its private units' positions in sunits
-    for (int b = 0; b < batch; ++b) {
-        int n_tmp = 0;
-        const int tail_est = insts[b].q_len + (cfg.max_tail_tokens - insts[b].q_len) / 2;
-        const int made = build_units(priv[b].data(), (int)priv[b].size(), b, priv_units[b], tail_est, cfg.max_tail_tokens,
-                                     items, n_items, tmp.data(), &n_tmp, [](int) { return (size_t)0; });
-        count[b] -= priv_units[b] - made;
-        for (int k = 0; k < made; ++k) {
-            SUnit& su = sunits[n];
-            memset(&su, 0, sizeof(su));
-            su.u = tmp[k];
-            su.n_users = 1;
-            su.users[0].inst = b;
-            priv_index[b].push_back(n++);
-        }
-    }
+    if (n <= 0 || n > max_sunits || n * cfg.n_kv_heads > 256) return 0;
+    if (tokens_out) memset(tokens_out, 0, sizeof(int32_t) * (size_t)n * kMaxSharedUsers);
+    n = cut(per, true, *n_items);
+    if (n <= 0) return 0;
+    // partial slots: every (unit, user) pair one, an instance's slots consecutive
+    std::vector<int> count(batch, 0), next(batch, 0);
+    for (int u = 0; u < n; ++u)
+        for (int k = 0; k < sunits[u].n_users; ++k) ++count[sunits[u].users[k].inst];
     int slot0 = 0;
-    std::vector<int> next(batch);
     for (int b = 0; b < batch; ++b) {
+        if (count[b] > kMaxDecodeUnitsPerInstance) return 0;
         insts[b].sslot0 = slot0; insts[b].n_sslots = count[b];
         next[b] = slot0;
         slot0 += count[b];
-        for (int i : priv_index[b]) sunits[i].users[0].slot = next[b]++;
     }
-    for (const PageUse& pu : distinct) {
-        if (pu.users.size() < 2) continue;
-        const int np = pieces_of(pu.n_tokens);
-        const long gran = (pu.n_tokens + 7) / 8;
-        for (int i = 0; i < np; ++i) {
-            const int tok0 = (int)(gran * i / np) * 8;
-            const int tok1 = (int)std::min<long>(pu.n_tokens, (gran * (i + 1) / np) * 8);
-            for (size_t u0 = 0; u0 < pu.users.size(); u0 += group) {
-                SUnit& su = sunits[n++];
-                memset(&su, 0, sizeof(su));
-                su.u.inst = pu.users[u0]; su.u.n_items = 1; su.u.page_tokens = tok1 - tok0;
-                su.u.first.base = reinterpret_cast<uint64_t>(pu.slot);
-                su.u.first.page_tokens = pu.n_tokens; su.u.first.tok0 = tok0; su.u.first.ntok = tok1 - tok0;
-                su.n_users = (int)std::min<size_t>(group, pu.users.size() - u0);
-                for (int k = 0; k < su.n_users; ++k) {
-                    const int b = pu.users[u0 + k];
-                    su.users[k].inst = b; su.users[k].slot = next[b]++;
-                }
-            }
-        }
+    for (int u = 0; u < n; ++u) {
+        sunits[u].u.idx_in_inst = u;
+        for (int k = 0; k < sunits[u].n_users; ++k) sunits[u].users[k].slot = next[sunits[u].users[k].inst]++;
     }
     return n;
 }
@@ -1319,19 +1370,21 @@ int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids
     std::vector<Item> items((size_t)tl.max_items);
     std::vector<SUnit> sunits((size_t)tl.max_sunits);
     int n_items = 0;
+    std::vector<int32_t> user_tokens((size_t)tl.max_sunits * kMaxSharedUsers);
     const int n = build_shared_units(*cfg, pages.data(), n_pages, batch, tl.max_sunits, tl.max_items, insts.data(),
-                                     items.data(), &n_items, sunits.data());
+                                     items.data(), &n_items, sunits.data(), user_tokens.data());
     for (int u = 0; u < n && u < cap; ++u) {
         const SUnit& su = sunits[u];
-        int32_t* o = units_out + (size_t)u * (4 + 2 * kMaxSharedUsers);
+        int32_t* o = units_out + (size_t)u * (4 + 3 * kMaxSharedUsers);
         const uintptr_t base = (uintptr_t)su.u.first.base;
-        o[0] = base ? (int32_t)(base / 4096 - 1) : -1;     // id of the unit's first page; -1: only a tail
-        o[1] = su.u.page_tokens;                            // page tokens the unit streams (all its items)
-        o[2] = su.u.has_tail;
+        o[0] = base ? (int32_t)(base / 4096 - 1) : -1;     // id of the unit's first page; -1: it starts with a tail
+        o[1] = su.u.page_tokens;                            // page tokens the unit streams (all its pieces)
+        o[2] = su.u.has_tail ? su.u.inst : -1;              // the instance whose tail it holds, or -1
         o[3] = su.n_users;
         for (int k = 0; k < kMaxSharedUsers; ++k) {
-            o[4 + 2 * k] = k < su.n_users ? su.users[k].inst : -1;
-            o[5 + 2 * k] = k < su.n_users ? su.users[k].slot : -1;
+            o[4 + 3 * k] = k < su.n_users ? su.users[k].inst : -1;
+            o[5 + 3 * k] = k < su.n_users ? su.users[k].slot : -1;
+            o[6 + 3 * k] = k < su.n_users ? user_tokens[(size_t)u * kMaxSharedUsers + k] : 0;
         }
     }
     if (slots_out && n > 0)

@@ -31,7 +31,7 @@ struct Item {              // 32 bytes: a run of tokens inside one page, or the 
     int32_t ntok;          // tokens of this piece (tail: capacity, clipped by tail_len)
     int32_t fmt;           // matkv_page_format of the page
     int32_t scales16;      // compressed page: byte offset of its scale table inside the blob, / 16
-    int32_t pad;
+    int32_t umask;         // shared decode units: bit k = the unit's k-th user sees this piece
 };
 
 struct Unit {              // 64 bytes: the work of one workgroup = consecutive items of one instance
@@ -46,15 +46,16 @@ struct Unit {              // 64 bytes: the work of one workgroup = consecutive 
     Item first;            // copy of items[item0]: one fetch is enough to start streaming
 };
 
-// A shared decode unit (instances of a batch that retrieved the same chunk read it once): one
-// piece of one page, or one instance's tail, and the instances whose newest tokens attend to
-// it in this workgroup.  Every (unit, user) pair owns one partial slot of that user; an
-// instance's slots are consecutive (InstanceInfo::sslot0 .. + n_sslots).
+// A shared decode unit (instances of a batch that retrieved the same chunk read it once): a run
+// of pieces of the batch's distinct pages (and at most one tail) and the instances whose newest
+// tokens attend to some of them in this workgroup; Item::umask says which of the unit's users
+// see a piece.  Every (unit, user) pair owns one partial slot of that user; an instance's slots
+// are consecutive (InstanceInfo::sslot0 .. + n_sslots).
 constexpr int kMaxSharedUsers = 16;             // rows of one matrix tile / smallest group size
 constexpr int kMaxSharedUnitsPerInstance = 64;  // table capacity per instance of max_batch
 
 struct SUnit {             // 208 bytes
-    Unit u;                // one item (u.first); u.inst names the instance of a tail unit
+    Unit u;                // its pieces (pages of several users, at most one tail: u.inst names that tail's instance)
     int32_t n_users;
     int32_t pad[3];
     struct { int32_t inst, slot; } users[kMaxSharedUsers];

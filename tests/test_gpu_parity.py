@@ -1129,9 +1129,11 @@ def test_shared_partition_is_built_only_where_it_applies():
     base = dict(n_layers=1, Hq=8, Hkv=2, D=128, hidden=256, dtype="bf16", chunk_lens={0: 300, 1: 40},
                 retrieved=[[0, 1], [0], [0]], q_lens=[3, 4, 2], steps=1)
     shared = lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], [(s[0], 300)]]
-    assert units(Case("sh-yes", **base), shared) == 4      # the shared page; instance 0's private page + tail; two more tails
+    assert units(Case("sh-yes", **base), shared) >= 3      # 340 distinct of 940 page tokens; a unit holds at most one of the three tails
     assert units(Case("sh-private", **base), lambda s: [[(s[0], 300)], [(s[1], 40)], []]) == 0  # nothing shared
-    assert units(Case("sh-little", **base), lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], []]) == 0   # 340 of 640 page tokens distinct
+    assert units(Case("sh-some", **base), lambda s: [[(s[0], 300), (s[1], 40)], [(s[0], 300)], []]) >= 1    # 340 of 640 page tokens distinct
+    big = dict(base, chunk_lens={0: 300, 1: 6000})
+    assert units(Case("sh-little", **big), lambda s: [[(s[0], 300), (s[1], 6000)], [(s[0], 300)], []]) == 0  # 6300 of 6600: less than a twentieth saved
     assert units(Case("sh-units", **{**base, "decode_units": 2}), shared) == 0                  # explicit partition
     assert units(Case("sh-f32", **{**base, "dtype": "f32", "D": 64}), shared) == 0              # other kernels
 
