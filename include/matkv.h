@@ -280,8 +280,8 @@ int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids
  * tails into equal work units and notes with every piece the instances that use it: the decode
  * attention then reads a shared chunk once for up to 16 / (Hq/Hkv) instances at a time instead
  * of once per instance.  Built when the distinct pages are at least a twentieth fewer tokens
- * than all uses together, for plain pages, bf16, head_dim 128, decode_units = 0 and
- * decode_variant = 0; results are the same as without it (every instance still gets exact
+ * than all uses together, for plain or compressed pages, bf16, head_dim 128, decode_units = 0
+ * and decode_variant = 0; results are the same as without it (every instance still gets exact
  * attention over its own cache). */
 int32_t matkv_table_shared_units(matkv_ctx* ctx, const void* table);
 /* tail_len[b] += n for every instance of the table (a one-wave kernel; capturable). */

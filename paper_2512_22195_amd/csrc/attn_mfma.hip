@@ -236,7 +236,7 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && 
     constexpr int ROWS = 16 * MS;                       // (row, head) pairs per workgroup
     constexpr int NT = (FR > 0 ? 2 : 1) * NW * 64;      // threads of the workgroup
     typedef uint16_t T;
-    static_assert(!SH || (FR == 0 && MS == 1 && !F8), "shared units: plain decode tiles only");
+    static_assert(!SH || (FR == 0 && MS == 1), "shared units: decode tiles only");
     __shared__ int sm_last, sm_lastv[SH ? kMaxSharedUsers : (FR > 0 ? kFusedMaxBatch : 1)];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -485,6 +485,7 @@ __global__ __launch_bounds__((FR > 0 ? 2 : 1) * NW * 64, (FR > 0 || (MS == 1 && 
             tu.item0 = unit.item0 + unit.n_items - 1; tu.n_items = 1; tu.page_tokens = 0;
             tu.first.base = 0; tu.first.page_tokens = a.max_tail; tu.first.tok0 = 0; tu.first.ntok = a.max_tail;
             tu.first.fmt = 0; tu.first.scales16 = 0;
+            if (SH) tu.first.umask = items[tu.item0].umask;     // the users that see it (its owner)
             Walker<T, D, NW, BLK, 8> walk(a, tu, items, kvh, tail_visible, wave);
             stream(walk, PlainBuf{}, issue_plain, consume_plain);
         }
@@ -597,15 +598,16 @@ hipError_t launch_g(const AttnArgs& a, hipStream_t s) {
         const int tiles = (a.rows * G + 31) / 32;
         return f8 ? launch_v<G, 4, 2, 2, true>(a, tiles, s) : launch_v<G, 4, 2, 2>(a, tiles, s);
     }
-    if (f8) return launch_v<G, 4, 1, 2, true>(a, 1, s);
     if (a.shared) {
         const KernelArgs k = make_kernel_args(a);
-        hipLaunchKernelGGL((attn_mfma_kernel<G, 4, 1, 2, 0, false, true>), dim3(a.n_units, a.Hkv, 1), dim3(4 * 64), 0, s, k, StepArgs{},
+        auto kern = f8 ? attn_mfma_kernel<G, 4, 1, 2, 0, true, true> : attn_mfma_kernel<G, 4, 1, 2, 0, false, true>;
+        hipLaunchKernelGGL(kern, dim3(a.n_units, a.Hkv, 1), dim3(4 * 64), 0, s, k, StepArgs{},
                            reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst),
                            reinterpret_cast<const Item*>(a.table + a.off_items),
                            reinterpret_cast<const Unit*>(a.table + a.off_units));
         return hipGetLastError();
     }
+    if (f8) return launch_v<G, 4, 1, 2, true>(a, 1, s);
     // decode: variant 9000 + 10 * (blocks in flight) + waves
     switch (a.variant % 100) {
         case 24: return launch_v<G, 4, 1, 2>(a, 1, s);

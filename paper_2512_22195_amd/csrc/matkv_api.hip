@@ -347,7 +347,7 @@ int build_units(const matkv_page* pages, int n_pages, int inst, int n_units, int
 // partition does not fit the table (then the per-instance partition is used).
 int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const int32_t* n_pages, int batch,
                        int max_sunits, int max_items, InstanceInfo* insts, Item* items, int* n_items, SUnit* sunits,
-                       int32_t* tokens_out = nullptr) {
+                       int kv_fmt, int32_t* tokens_out = nullptr) {
     struct PageUse { const void* slot; int n_tokens; std::vector<int> users; };
     std::vector<PageUse> distinct;
     std::unordered_map<const void*, std::vector<int>> by_slot;   // slot -> indices into distinct
@@ -367,9 +367,10 @@ int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const i
             }
             distinct[found].users.push_back(b);
         }
-    // Worth it when the distinct pages are at least a twentieth fewer bytes than all uses together
-    // (measured at batch 16, five 1000-token chunks each, per layer: 81 % distinct 57.5 us
-    // per-instance against see the design notes).
+    // Worth it when the distinct pages are at least a twentieth fewer tokens than all uses together
+    // (measured at batch 16, five 1000-token chunks each, per layer, per-instance against shared
+    // partition: 81 % of the page tokens distinct 58.3 against 54.8 us, 41 % 43.4 against 35.5,
+    // 6 % 33.5 against 18.3).
     long all_tokens = 0, distinct_tokens = 0;
     for (const PageUse& pu : distinct) {
         distinct_tokens += pu.n_tokens;
@@ -434,6 +435,10 @@ int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const i
             if (!open) return;
             if (emit) {
                 su->u.n_items = n_it - su->u.item0;
+                // the unit's tail, if it has one, goes last (compressed pages: the kernel walks the
+                // code pages and then the plain tail)
+                for (int i = su->u.item0; i + 1 < n_it; ++i)
+                    if (items[i].base == 0) std::rotate(items + i, items + i + 1, items + n_it);
                 su->u.first = items[su->u.item0];
                 su->n_users = (int)users.size();
                 for (size_t k = 0; k < users.size(); ++k) su->users[k].inst = users[k];
@@ -482,6 +487,8 @@ int build_shared_units(const matkv_config& cfg, const matkv_page* pages, const i
                         it.page_tokens = pu.n_tokens;
                         it.tok0 = (int)(g * 8);
                         it.ntok = (int)std::min<long>(pu.n_tokens, (g + take) * 8) - it.tok0;
+                        it.fmt = kv_fmt;
+                        it.scales16 = kv_fmt == MATKV_PAGE_E4M3 ? (int32_t)(compressed_codes_bytes(cfg, pu.n_tokens) / 16) : 0;
                         su->u.page_tokens += it.ntok;
                         if (tokens_out)
                             for (int k = 0; k < kMaxSharedUsers; ++k)
@@ -1256,10 +1263,10 @@ matkv_status matkv_assemble(matkv_ctx* c, const matkv_page* pages, const int32_t
     // decode over shared pages: only where the default matrix-core decode kernel runs
     const int grp = cfg.n_q_heads / cfg.n_kv_heads;
     int n_sunits = 0;
-    if (batch >= 2 && pages && cfg.decode_units == 0 && cfg.decode_variant == 0 && kv_fmt == MATKV_PAGE_PLAIN &&
+    if (batch >= 2 && pages && cfg.decode_units == 0 && cfg.decode_variant == 0 &&
         cfg.dtype == MATKV_BF16 && cfg.head_dim == 128 && group_size_built(grp))
         n_sunits = build_shared_units(cfg, pages, n_pages, batch, c->tl.max_sunits, c->tl.max_items, insts, items, &n_items,
-                                      reinterpret_cast<SUnit*>(h + c->tl.off_sunits));
+                                      reinterpret_cast<SUnit*>(h + c->tl.off_sunits), kv_fmt);
     hdr->batch = batch; hdr->n_items = n_items; hdr->n_dunits = n_dunits; hdr->n_punits = n_punits;
     hdr->total_q = cu; hdr->max_q = max_q;
 
@@ -1372,7 +1379,7 @@ int32_t matkv_plan_shared_units(const matkv_config* cfg, const int32_t* page_ids
     int n_items = 0;
     std::vector<int32_t> user_tokens((size_t)tl.max_sunits * kMaxSharedUsers);
     const int n = build_shared_units(*cfg, pages.data(), n_pages, batch, tl.max_sunits, tl.max_items, insts.data(),
-                                     items.data(), &n_items, sunits.data(), user_tokens.data());
+                                     items.data(), &n_items, sunits.data(), MATKV_PAGE_PLAIN, user_tokens.data());
     for (int u = 0; u < n && u < cap; ++u) {
         const SUnit& su = sunits[u];
         int32_t* o = units_out + (size_t)u * (4 + 3 * kMaxSharedUsers);

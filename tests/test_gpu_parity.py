@@ -1089,13 +1089,17 @@ def test_config2_full_size_compressed_sampled():
 
 
 # ------------------------------------------------- decode over pages that instances share ---
-@pytest.mark.parametrize("name,Hq,Hkv,batch,use_graph", [
-    ("g4", 8, 2, 6, False),      # 4 users per tile: the hot page needs two groups
-    ("g1", 2, 2, 21, False),     # 16 users per tile, 21 users of the hot page
-    ("g8", 16, 2, 6, True),      # 2 users per tile
-    ("g2", 4, 2, 9, False),
+@pytest.mark.parametrize("name,Hq,Hkv,batch,use_graph,compressed", [
+    ("g4", 8, 2, 6, False, False),      # 4 users per tile: the hot page needs two groups
+    ("g1", 2, 2, 21, False, False),     # 16 users per tile, 21 users of the hot page
+    ("g8", 16, 2, 6, True, False),      # 2 users per tile
+    ("g2", 4, 2, 9, False, False),
+    ("g4-f8", 8, 2, 6, True, True),     # the same over compressed pages (the tails stay plain)
+    ("g1-f8", 2, 2, 21, False, True),
+    ("g8-f8", 16, 2, 6, False, True),
+    ("g3-f8", 6, 2, 9, False, True),
 ])
-def test_decode_over_shared_pages(name, Hq, Hkv, batch, use_graph):
+def test_decode_over_shared_pages(name, Hq, Hkv, batch, use_graph, compressed):
     """Requests of one batch that retrieved the same chunks (the paper's access-skew argument,
     Section II-C): the decode attention runs over the shared partition - every distinct page is
     read once per group of users - and every instance still gets exact attention over its own
@@ -1106,7 +1110,7 @@ def test_decode_over_shared_pages(name, Hq, Hkv, batch, use_graph):
     retrieved = [pool[i % len(pool)] if i != 4 else [] for i in range(batch)]
     case = Case(f"shared-{name}", n_layers=2, Hq=Hq, Hkv=Hkv, D=128, hidden=256, dtype="bf16",
                 chunk_lens=lens, retrieved=retrieved, q_lens=[1 + (5 * i) % 23 for i in range(batch)],
-                steps=3, scale=1.0, q_scale=1.0)
+                steps=3, scale=1.0, q_scale=1.0, compressed=compressed)
     inp = chain.make_attention_inputs(case)
     info = {}
     o_pre, o_dec = chain.run_gpu_attention(case, inp, use_graph=use_graph, info=info)
