@@ -378,6 +378,8 @@ __global__ __launch_bounds__(512, 2) void materialize_mfma8_kernel(MaterializeAr
 }
 
 // ---- skinny form: 16 .. 255 token rows (a question, a decode step of a large batch) ----------
+// (The form for hidden sizes that are a multiple of 512 but not of 1024; multiples of 1024 take
+// the staged form below.)
 // Too few rows for the tiled GEMM to fill the chip (64 rows make 16 tiles).  Here a workgroup owns
 // up to 64 rows x 16 rotary pairs (features 16g .. 16g+15 and their partners 64 further) of one
 // head of K or of V, and its eight waves split the HIDDEN axis: each wave multiplies its slice
@@ -489,20 +491,162 @@ __global__ __launch_bounds__(512) void materialize_skinny_kernel(MaterializeArgs
     }
 }
 
+
+// ---- skinny form with coalesced loads ---------------------------------------------------------
+// The kernel above loads operands straight into matrix-core layout: consecutive lanes then sit on
+// sixteen different rows, every lane's 16 bytes is a request of its own to the vector cache, and
+// the launch is bound by that request rate (64 rows, hidden 4096: 98 MB in 17 us).  Here a wave
+// loads its slice of the hidden axis row-wise instead - sixteen consecutive lanes take 256
+// consecutive bytes of one row - parks the rows in a private LDS region (272-byte rows: sixteen
+// lanes write one whole row, sixteen lanes read 16 bytes of sixteen different rows, both without a
+// bank conflict) and reads them back in operand layout.  The region belongs to one wave: no
+// workgroup barrier in the loop.  Same tile, same split of the hidden axis, same epilogue.
+template <int MI, int NB>
+__global__ __launch_bounds__(512) void materialize_skinny_staged_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int NWV = 8, SC = 128;                    // waves; hidden columns per wave and round
+    constexpr int TM = 16 * MI;
+    constexpr int NR = 32 + TM;                         // rows staged per round: 16 + 16 weight rows, TM token rows
+    constexpr int NL = NR / 4;                          // 16-byte loads per lane and round (a load covers 4 rows)
+    constexpr int RS = SC + 8;                          // bf16 per staged row
+    constexpr int STAGE_BYTES = NWV * NR * RS * 2, RED_BYTES = NWV * TM * 33 * 4;
+    __shared__ __attribute__((aligned(16))) char smem[STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const int pg = blockIdx.x & 3, head = (blockIdx.x >> 2) % a.Hkv, kv = (blockIdx.x >> 2) / a.Hkv;
+    const int row0 = blockIdx.y * TM;
+    const int kslice = a.Hd / NWV;                      // a multiple of SC (checked by the launcher)
+    const int n_rounds = kslice / SC;
+
+    // the epilogue's row and rotary entry of this thread are fixed: asked for now, not after the sums
+    static_assert(TM * 16 <= NWV * 64, "one output pair per thread");
+    const int et = tid >> 4, ep = tid & 15;
+    const RopeEntry rope_e = a.rope[16 * pg + ep];
+    RowDest edest = resolve_row(a, row0 + min(et, TM - 1));
+    if (et >= TM) edest.valid = false;
+
+    // load i of a round: row 4 i + lane / 16 of the staged rows, 16 bytes at column 8 (lane % 16)
+    const int lr = lane >> 4, lc = 8 * (lane & 15);
+    const size_t col0 = (size_t)wave * kslice + lc;
+    const uint16_t* wbase = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + ((size_t)head * D + 16 * pg + lr) * a.Hd + col0;
+    const uint16_t* xp[MI * 4];
+#pragma unroll
+    for (int i = 0; i < MI * 4; ++i)
+        xp[i] = reinterpret_cast<const uint16_t*>(a.hidden) + (size_t)min(row0 + 4 * i + lr, total_rows - 1) * a.Hd + col0;
+    auto load = [&](uint4 (&b)[NL], int r) {
+        const int off = min(r, n_rounds - 1) * SC;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            b[i] = ldg16(wbase + (size_t)(4 * i) * a.Hd + off);
+            b[4 + i] = ldg16(wbase + (size_t)(D / 2 + 4 * i) * a.Hd + off);
+        }
+#pragma unroll
+        for (int i = 0; i < MI * 4; ++i) b[8 + i] = ldg16(xp[i] + off);
+    };
+
+    uint16_t* const st = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * NR * RS;
+    f32x4 acc[MI][2];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) { acc[mi][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[mi][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    auto process = [&](const uint4 (&b)[NL]) {
+        __builtin_amdgcn_wave_barrier();                // the last round's reads stay ahead of these writes
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<uint4*>(st + (4 * i + lr) * RS + lc) = b[i];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < SC / 32; ++j) {
+            const bf16x8 wl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(st + c16 * RS + 32 * j + 8 * g4));
+            const bf16x8 wh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(st + (16 + c16) * RS + 32 * j + 8 * g4));
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const bf16x8 xa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(st + (32 + 16 * mi + c16) * RS + 32 * j + 8 * g4));
+                acc[mi][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wl, acc[mi][0], 0, 0, 0);
+                acc[mi][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wh, acc[mi][1], 0, 0, 0);
+            }
+        }
+    };
+    // NB rounds of loads in flight; no load under a branch (the launcher sees to it that the rounds
+    // are a multiple of NB), the last NB rounds are consumed without asking for more
+    {
+        uint4 b[NB][NL];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) load(b[i], i);
+        for (int r = NB; r < n_rounds; r += NB) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                process(b[i]);
+                load(b[i], r + i);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) process(b[i]);
+    }
+
+    // the eight partial tiles meet in LDS (over the staging rows, once every wave is done with its own)
+    __syncthreads();
+    float (*red)[TM][33] = reinterpret_cast<float (*)[TM][33]>(smem);
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][16 * mi + 4 * g4 + i][16 * h + c16] = acc[mi][h][i];
+    __syncthreads();
+
+    uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+    if (edest.valid) {
+        const RowDest d = edest;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) { lo += red[w][et][ep]; hi += red[w][et][16 + ep]; }
+        const int j = 16 * pg + ep;
+        if (kv == 0) {
+            float c, s;
+            rope_cs(rope_e, d.pos, c, s);
+            const float k0 = lo * c - hi * s;
+            const float k1 = lo * s + hi * c;
+            lo = k0; hi = k1;
+        }
+        out[d.elem_off + j] = f32_to_bf16_rne(lo);
+        out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
+    }
+}
+
 }  // namespace
 
 bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows) {
     return dtype == MATKV_BF16 && a.D == 128 && (a.Hd % BK) == 0 && total_rows >= 16;
 }
 
-// Skinny form: measured ahead of the tiled GEMM below a few hundred rows, where the GEMM's grid
-// leaves most compute units idle.
+// Skinny forms: measured ahead of the tiled GEMM below a few hundred rows, where the GEMM's grid
+// leaves most compute units idle.  The staged form (hidden a multiple of 1024), us per launch at
+// hidden 4096 / 8192 against the form with direct operand loads: 64 rows 8.1 / 13.8 (17.2 / -),
+// 128 rows 10.6 / 17.4, 255 rows 18.8 / 30.1 (33.9 / 61.6); against the tiled GEMM: 384 rows
+// 27.1 / 44.6 (33.1 / 59.0), 512 rows 35.3 / 57.3 (33.2 / 60.5), 768 rows 50.6 / 80.2 (33.8 / 61.6).
 constexpr int kSkinnyMaxRows = 256;
+constexpr int kStagedMaxRows = 448;
 
 hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s) {
-    if (total_rows < kSkinnyMaxRows && (a.Hd % 512) == 0) {
+    const bool staged = (a.Hd % 1024) == 0;
+    if ((a.Hd % 512) == 0 && (total_rows < kSkinnyMaxRows || (staged && (total_rows <= kStagedMaxRows || (total_rows <= 512 && a.Hd >= 8192))))) {
         const dim3 block(512);
         const int gx = 2 * a.Hkv * 4;
+        if (staged) {
+            // rows staged through LDS: 16-row tiles up to 64 rows (64 x 4 workgroups fill the chip),
+            // 32-row tiles beyond (half the workgroups, the weights re-read half as often)
+            const int rounds = a.Hd / 1024;             // per wave: an eighth of the hidden axis, 128 columns a round
+            const bool mi2 = total_rows > 64;
+            const dim3 grid(gx, mi2 ? (total_rows + 31) / 32 : (total_rows + 15) / 16);
+            if (rounds % 2 == 0) {
+                if (mi2) hipLaunchKernelGGL((materialize_skinny_staged_kernel<2, 2>), grid, block, 0, s, a, total_rows);
+                else     hipLaunchKernelGGL((materialize_skinny_staged_kernel<1, 2>), grid, block, 0, s, a, total_rows);
+            } else {
+                if (mi2) hipLaunchKernelGGL((materialize_skinny_staged_kernel<2, 1>), grid, block, 0, s, a, total_rows);
+                else     hipLaunchKernelGGL((materialize_skinny_staged_kernel<1, 1>), grid, block, 0, s, a, total_rows);
+            }
+            return hipGetLastError();
+        }
         // 16-row tiles keep every compute unit busy from 64 rows on (64 x 4 workgroups) and leave
         // registers for four chunks of loads in flight; from 512 workgroups on, 32-row tiles halve
         // the re-reading of the weights
