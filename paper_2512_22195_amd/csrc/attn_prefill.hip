@@ -31,8 +31,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
-constexpr int KSTR = D + 8;         // bf16 per LDS row of the K tile
-constexpr int VSTR = D + 16;        // bf16 per LDS row of the V tile
+// Row strides of the LDS tiles, measured on the chip with the three access patterns used here
+// (16-byte operand reads of 16 rows, transposing 8-byte reads, 16-byte staging writes of whole
+// rows; cycles per instruction with eight waves): K 272 bytes 8.8, 288 bytes 5.4; V 288 bytes
+// 6.7, 304 bytes 6.2.
+constexpr int KSTR = D + 16;        // bf16 per LDS row of the K tile
+constexpr int VSTR = D + 24;        // bf16 per LDS row of the V tile
 constexpr float kLazyLog2 = 8.0f;     // slack of the running reference exponent, in powers of two
 
 __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
