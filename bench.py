@@ -345,6 +345,15 @@ class Workload:
                 h = timed(lambda l: ctx.chunk_attn(l, q_chunk, blob, L, o_chunk))
             except self.mk.MatKVError:     # the row-per-workgroup kernel needs a workspace sized for the chunk's rows
                 h = None
+            # the whole materialization pass of one chunk (paper Section III-B steps 1-3): per layer the
+            # K/V projection with rotary, then the chunk's own causal attention over what was just
+            # written; every layer's hidden states and queries come from the caller (synthetic)
+            cp = None
+            if h:
+                def chunk_layer(l):
+                    ctx.materialize(x_chunk, self.w[l, 0], self.w[l, 1], L, 0, blob[l, 0], blob[l, 1], L)
+                    ctx.chunk_attn(l, q_chunk, blob, L, o_chunk)
+                cp = timed(chunk_layer)
             ctx.assemble(self.pages, self.q_lens, self.table)
             p = timed(lambda l: ctx.prefill_attn(l, self.q_pre[l], self.table, t[l, 0], t[l, 1], self.o_pre[l]))
             mq = timed(lambda l: ctx.materialize_tail(self.x_q[l], self.w[l, 0], self.w[l, 1], self.table, -1, t[l, 0], t[l, 1]))
@@ -370,6 +379,9 @@ class Workload:
         return {
             "materialize_chunk": dict(tokens=L, **mfma(fl_mat, m)),
             "chunk_attn": dict(tokens=L, **mfma(fl_chunk, h)) if h else None,
+            "chunk_pass": {"what": "materialize + chunk_attn back to back, every layer, one chunk", "tokens": L, "layers": nl,
+                           "us_per_layer": round(us(cp), 2), "ms_per_chunk": round(us(cp) * nl / 1e3, 3),
+                           "chunk_tokens_per_s": round(L / (us(cp) * nl / 1e6), 1)} if cp else None,
             "materialize_question": dict(rows=self.total_q, **mfma(fl_matq, mq, lambda u: {
                 "bytes": by_matq, "frac_of_hbm_peak": round(by_matq / u / 1e3 / HBM_PEAK_GBPS, 4)})),
             "prefill_attn": mfma(fl_pre, p, lambda u: {"kv_bytes": by_pre, "frac_of_hbm_peak": round(by_pre / u / 1e3 / HBM_PEAK_GBPS, 4)}),
