@@ -3,7 +3,7 @@
 // units of one (instance, KV head).
 #pragma once
 
-#include "matkv_internal.h"
+#include "device_util.h"
 
 namespace matkv {
 namespace attn {
@@ -14,31 +14,15 @@ constexpr int kPartialStride(int D) { return D + 4; }   // floats: accumulator, 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+using dev::f32_to_bf16_rne;
+using dev::ldg16;
+using dev::ldg8;
+using dev::st_agent2;
+using dev::ld_agent2;
 
 // exp2 of a non-positive argument: the bare hardware instruction (results below the normal
 // range flush to zero, which is what a softmax weight that small should be).
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// 16-byte load through the global address space (a pointer rebuilt from an integer would
-// otherwise be treated as generic and loaded with the slower flat instructions).
-__device__ __forceinline__ uint4 ldg16(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x4* gptr;
-    const u32x4 r = *(gptr)(uintptr_t)p;
-    return make_uint4(r.x, r.y, r.z, r.w);
-}
-
-// 8-byte load through the global address space.
-__device__ __forceinline__ uint2 ldg8(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x2* gptr;
-    const u32x2 r = *(gptr)(uintptr_t)p;
-    return make_uint2(r.x, r.y);
-}
 
 // Eight E4M3 codes to eight bf16 (exact: three mantissa bits fit seven), through fp32.
 __device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint2 w) {
@@ -50,16 +34,6 @@ __device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint2 w) {
                       __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2)),
                       __builtin_bit_cast(uint32_t, __builtin_convertvector(c, bf16x2)),
                       __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2)));
-}
-
-// Agent-scope relaxed accesses: coherent across the chip's L2 slices without cache flushes.
-__device__ __forceinline__ void st_agent2(float* p, float x, float y) {
-    const uint64_t v = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
-    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 ld_agent2(const float* p) {
-    const uint64_t r = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
 }
 
 // Value of the lane whose index differs in bit log2(off); off in {32, 16, 8}.  Distances 32
@@ -331,19 +305,9 @@ __device__ __forceinline__ void merge_dispatch(const KernelArgs& a, int unit0, i
 // waited for its own agent-scope stores, the barrier orders them before thread 0's ticket.
 // Returns true in every thread of the workgroup that arrived last of `expected`.
 __device__ __forceinline__ bool arrive(const KernelArgs& a, int cidx, int expected, int* sm_last) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int prev = __hip_atomic_fetch_add(&a.counters[cidx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *sm_last = (prev == expected - 1);
-    }
-    __syncthreads();
-    return *sm_last != 0;
+    return dev::arrive_at(&a.counters[cidx], expected, sm_last);
 }
-__device__ __forceinline__ void reset_counter(const KernelArgs& a, int cidx) {
-    if (threadIdx.x == 0) __hip_atomic_store(&a.counters[cidx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-}
+__device__ __forceinline__ void reset_counter(const KernelArgs& a, int cidx) { dev::reset_counter_at(&a.counters[cidx]); }
 
 // Merge of one workgroup's NS partial states per row (already in LDS: accumulators
 // sm_acc[w][row][..] with row stride ACC_STRIDE floats, running maxima sm_m[w][row], sums

@@ -5,7 +5,7 @@
 // sum on DPP adds and register swaps, the rotation on the hardware sine / cosine with the angle
 // kept in turns.
 #pragma once
-#include "matkv_internal.h"
+#include "device_util.h"
 
 namespace matkv {
 namespace gemv {
@@ -14,11 +14,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2v __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint4 ldg16(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x4v* gptr;
-    const u32x4v r = *(gptr)(uintptr_t)p;
-    return make_uint4(r.x, r.y, r.z, r.w);
-}
+using dev::ldg16;
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }

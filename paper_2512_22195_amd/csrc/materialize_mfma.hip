@@ -4,15 +4,13 @@
 // Both operands are contiguous along the contraction (hidden) axis, which is what the
 // matrix-core operand layout wants: a lane's 8 consecutive bf16 of one row.
 //
-// A workgroup owns 128 (or 64) tokens x one head of K or of V (128 features, so both halves of
-// every rotary pair are in the tile), stepping 64 hidden columns at a time through double-buffered
-// LDS tiles fed from four rotating register stages (two steps' loads stay in flight).  Its four
-// waves form a 2 x 2 grid of sub-tiles 64 features wide; a wave's features are the 16-wide
-// blocks {2w, 2w+1} and their rotary partners {2w+4, 2w+5}, so the rotation is lane-local on
-// the fp32 accumulators.  One rounding to bf16 on store.
+// Three forms by row count: the tiled GEMM (128 x 128 tiles, below), and two skinny forms for a
+// few hundred rows at most (a question, a decode step of a large batch), whose eight waves split
+// the hidden axis.  In all of them the two features of a rotary pair sit in the same lane, so the
+// rotation is lane-local on the fp32 accumulators, and values are rounded to bf16 once, on store.
 #include <type_traits>
 
-#include "matkv_internal.h"
+#include "device_util.h"
 
 namespace matkv {
 namespace {
@@ -21,21 +19,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int D = 128, BK = 64;
-constexpr int LDS_STRIDE = BK + 16;         // bf16 per LDS row: 160 bytes (the 16-byte operand reads measured 4.5 cycles per instruction, 8.6 with 144 bytes)
+constexpr int D = 128, BK = 64;             // BK: hidden columns per step of the tiled GEMM
 
-__device__ __forceinline__ uint4 ldg16(const void* p) {
-    typedef const __attribute__((address_space(1))) u32x4* gptr;
-    const u32x4 r = *(gptr)(uintptr_t)p;
-    return make_uint4(r.x, r.y, r.z, r.w);
-}
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+using dev::ldg16;
+using dev::f32_to_bf16_rne;
 
 struct RowDest {
     float pos;          // rotary position (exact in fp32: below 2^24)
@@ -85,228 +72,95 @@ __device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, f
     s = __builtin_amdgcn_sinf(fr);
 }
 
-// BM = token rows per workgroup (128, or 64 when 128-row tiles would leave compute units idle)
-template <int BM>
-__global__ __launch_bounds__(256) void materialize_mfma_kernel(MaterializeArgs a, int total_rows) {
-    constexpr int MI = BM / 32;              // 16-row token blocks per wave
-    constexpr int LR = BM / 32;              // staging rows per thread for the token tile
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][D * LDS_STRIDE];
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int c16 = lane & 15, g4 = lane >> 4;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
-    const int row0 = blockIdx.y * BM;
-
-    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden);
-    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd;
-
-    // global -> LDS staging: thread t moves 16 bytes of rows t/8 + 32i (i < 4), columns 8*(t%8)
-    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
-    const uint16_t* xg[LR];
-    const uint16_t* wg[4];
-#pragma unroll
-    for (int i = 0; i < LR; ++i) {
-        const int r = min(row0 + ld_row + 32 * i, total_rows - 1);       // rows past the end repeat the last
-        xg[i] = X + (size_t)r * a.Hd + ld_col;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
-    // NS register stages rotate through the hidden axis: while block k is multiplied out of one
-    // LDS tile, block k+1 moves from its stage into the other tile and blocks k+2 .. k+NS-1 are
-    // in flight - a step of 64 columns is far shorter than a trip to the L2, so several steps'
-    // worth of loads have to be outstanding.  Loads and LDS stores carry no branch (past the end
-    // they repeat the last block) and the loop has one exit, so that the compiler can count the
-    // loads in flight instead of draining them at every step.
-    constexpr int NS = 4;                       // measured: 6 stages gain nothing over 4
-    struct Stage { uint4 x[LR], w[4]; };
-    Stage st[NS];
-    const int nk = a.Hd / BK;
-    auto load_global = [&](Stage& g, int ks) {
-        const int k0 = min(ks, nk - 1) * BK;
-#pragma unroll
-        for (int i = 0; i < LR; ++i) g.x[i] = ldg16(xg[i] + k0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) g.w[i] = ldg16(wg[i] + k0);
-    };
-    auto store_lds = [&](int buf, const Stage& g) {
-#pragma unroll
-        for (int i = 0; i < LR; ++i)
-            *reinterpret_cast<uint4*>(&As[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = g.x[i];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4*>(&Bs[buf][(ld_row + 32 * i) * LDS_STRIDE + ld_col]) = g.w[i];
-    };
-
-    f32x4 acc[MI][4];           // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto compute = [&](int buf) {
-#pragma unroll
-        for (int k2 = 0; k2 < BK / 32; ++k2) {
-            bf16x8 av[MI], bv[4];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                av[mi] = *reinterpret_cast<const bf16x8*>(&As[buf][(16 * MI * wm + 16 * mi + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
-                bv[ni] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(16 * tn + c16) * LDS_STRIDE + 32 * k2 + 8 * g4]);
-            }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
-        }
-    };
-
-#pragma unroll
-    for (int i = 0; i < NS - 1; ++i) load_global(st[i], i);
-    store_lds(0, st[0]);
-    lds_barrier();
-    int ks = 0;
-    // block ks sits in LDS tile ks & 1; its stage index S = ks % NS is a compile-time constant
-    auto step = [&](auto stage_tag) {
-        constexpr int S = decltype(stage_tag)::value;
-        load_global(st[(S + NS - 1) % NS], ks + NS - 1);
-        if (ks < nk) compute(ks & 1);
-        store_lds((ks + 1) & 1, st[(S + 1) % NS]);
-        lds_barrier();
-        ++ks;
-    };
-    do {
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
-    } while (ks < nk);
-
-    // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16
-    uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const RowDest d = resolve_row(a, row0 + 16 * MI * wm + 16 * mi + 4 * g4 + i);
-            if (!d.valid) continue;
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int j = 16 * (2 * wn + p) + c16;           // rotary pair index, features j and j + 64
-                float lo = acc[mi][p][i], hi = acc[mi][p + 2][i];
-                if (kv == 0) {
-                    float c, s;
-                    rope_cs(a.rope[j], d.pos, c, s);
-                    const float k0 = lo * c - hi * s;
-                    const float k1 = lo * s + hi * c;
-                    lo = k0; hi = k1;
-                }
-                out[d.elem_off + j] = f32_to_bf16_rne(lo);
-                out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
-            }
-        }
-    }
-}
-
-// ---- the same tile on eight waves ------------------------------------------------------------
-// One wave per SIMD leaves every latency of a step in the open: the operand reads from LDS, the
-// matrix instructions that wait for them, the stores of the next tile and the barrier follow
-// one another (measured: about 980 cycles per 64-column step around 256 cycles of matrix work).
-// Here the workgroup has two wave groups of 2 x 2 waves each; a step covers 128 hidden columns
-// and group g multiplies columns 64g .. 64g+63 of it, so every SIMD holds two waves whose
-// reads and matrix instructions overlap, and there is one barrier per 128 columns.  Rows of the
-// LDS tiles are 256 + 32 bytes: 16 lanes store one whole row at a time and 16 lanes read 16
-// bytes of 16 different rows without a bank conflict.  The two groups' partial sums meet in LDS
-// once, at the end: each group hands over the token blocks the other one finishes, so all eight
-// waves share the rotary epilogue.  (128-row tiles in this form - 238 registers, 139 KB of LDS -
-// measured 167 us for a 1000-token chunk against 37 us: not built.)
-constexpr int BK8 = 128;
-constexpr int STR8 = BK8 + 16;      // 288-byte rows: the 16-byte operand reads measured 5.4 cycles against 8.8 with 272
-
-template <int BM>
-__global__ __launch_bounds__(512, 2) void materialize_mfma8_kernel(MaterializeArgs a, int total_rows) {
-    constexpr int MI = BM / 32;              // 16-row token blocks per wave
-    constexpr int LRA = BM / 32;             // 16-byte pieces per thread and step: token tile
-    constexpr int LRB = D / 32;              //                                    weight tile
-    constexpr int A_ELEMS = BM * STR8, B_ELEMS = D * STR8;
+// ---- tiled GEMM: 128 x 128 tiles, the hidden axis split over SK workgroups ---------------------
+// A workgroup owns 128 tokens x one head of K or of V (128 features: both halves of every rotary
+// pair).  Eight waves as 2 x 4: a wave owns 64 tokens x the 16-feature blocks {wn, wn + 4}
+// (rotary partners); 64 hidden columns per step through double-buffered LDS tiles fed from four
+// rotating register stages (loads carry no branch - past the end they repeat the last step -
+// and the loop has one exit, so the compiler counts the loads in flight instead of draining them).
+// LDS rows are 160 bytes: the 16-byte operand reads of 16 rows measured 4.5 cycles per
+// instruction with them, 8.6 with 144.
+// The launch is bound by what the L2s hand to the compute units, every workgroup reading its
+// token rows and its weight rows over the whole hidden axis: 64 x 128 tiles (the earlier form)
+// moved 393 MB for a 1000-token chunk at hidden 4096 against 25 MB of distinct operands, these
+// tiles a third less.  Where 128 x 128 tiles alone would leave half of the chip idle (up to 1024
+// rows with 8 KV heads), two workgroups share a tile, each over half of the hidden axis: both
+// leave their fp32 partial in the workspace (agent-scope stores), arrive at the tile's counter,
+// and the one that arrives second adds the other's partial to its own and runs the epilogue.
+// Measured, us per launch at hidden 4096 / 8192 (8 KV heads), against the 64 x 128 forms this
+// replaced (eight waves up to 1000 rows, four waves beyond): 512 rows 30.6 / - (33.1 / -),
+// 1000 rows 34.0 / 57.9 (35.9 / 67.6), 1206 rows 46.9 / 88.7 (56.7 / 103.4), 2048 rows
+// 50.2 / 96.0 (62.8 / 111.4), 8192 rows 173 / 315 (185 / 327).
+template <int SK>
+__global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int BM = 128, BKS = BK, STR = BKS + 16;
+    constexpr int A_ELEMS = BM * STR, B_ELEMS = D * STR;
     __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * (A_ELEMS + B_ELEMS)];
-    static_assert(MI == 2, "the two wave groups split the token blocks of a wave in the epilogue");
-    static_assert(sizeof(float) * 8 * (MI / 2) * 4 * 64 * 4 <= sizeof(uint16_t) * 2 * (A_ELEMS + B_ELEMS), "exchange buffer");
+    __shared__ int sm_last;
+    __shared__ RowDest sm_dest[BM];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int kg = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;
     const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
     const int row0 = blockIdx.y * BM;
+    // where the tile's rows go and their rotary positions: looked up once per row, now, and read
+    // by the epilogue from LDS (in the tail form a lookup walks the batch's instances)
+    if (tid < BM) sm_dest[tid] = resolve_row(a, row0 + tid);
+    const int part = blockIdx.z;
+    const int nk = a.Hd / (BKS * SK);                   // steps of this workgroup
+    const size_t kbase = (size_t)part * nk * BKS;
 
-    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden);
-    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd;
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden) + kbase;
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd + kbase;
 
-    // global -> LDS staging: thread t moves 16 bytes of rows t/16 + 32i, columns 8*(t%16)
-    const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
-    const uint16_t* xg[LRA];
-    const uint16_t* wg[LRB];
+    // global -> LDS staging: thread t moves 16 bytes of rows t/8 + 64i, columns 8*(t%8)
+    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
+    const uint16_t* xg[2];
+    const uint16_t* wg[2];
 #pragma unroll
-    for (int i = 0; i < LRA; ++i) {
-        const int r = min(row0 + ld_row + 32 * i, total_rows - 1);       // rows past the end repeat the last
+    for (int i = 0; i < 2; ++i) {
+        const int r = min(row0 + ld_row + 64 * i, total_rows - 1);       // rows past the end repeat the last
         xg[i] = X + (size_t)r * a.Hd + ld_col;
+        wg[i] = W + (size_t)(ld_row + 64 * i) * a.Hd + ld_col;
     }
-#pragma unroll
-    for (int i = 0; i < LRB; ++i) wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
-
     constexpr int NS = 4;
-    struct Stage { uint4 x[LRA], w[LRB]; };
+    struct Stage { uint4 x[2], w[2]; };
     Stage st[NS];
-    const int nk = a.Hd / BK8;
     auto load_global = [&](Stage& g, int ks) {
-        const int k0 = min(ks, nk - 1) * BK8;
+        const int k0 = min(ks, nk - 1) * BKS;
 #pragma unroll
-        for (int i = 0; i < LRA; ++i) g.x[i] = ldg16(xg[i] + k0);
-#pragma unroll
-        for (int i = 0; i < LRB; ++i) g.w[i] = ldg16(wg[i] + k0);
+        for (int i = 0; i < 2; ++i) { g.x[i] = ldg16(xg[i] + k0); g.w[i] = ldg16(wg[i] + k0); }
     };
     auto a_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS); };
     auto b_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS) + A_ELEMS; };
     auto store_lds = [&](int buf, const Stage& g) {
 #pragma unroll
-        for (int i = 0; i < LRA; ++i)
-            *reinterpret_cast<uint4*>(a_tile(buf) + (ld_row + 32 * i) * STR8 + ld_col) = g.x[i];
-#pragma unroll
-        for (int i = 0; i < LRB; ++i)
-            *reinterpret_cast<uint4*>(b_tile(buf) + (ld_row + 32 * i) * STR8 + ld_col) = g.w[i];
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<uint4*>(a_tile(buf) + (ld_row + 64 * i) * STR + ld_col) = g.x[i];
+            *reinterpret_cast<uint4*>(b_tile(buf) + (ld_row + 64 * i) * STR + ld_col) = g.w[i];
+        }
     };
 
-    f32x4 acc[MI][4];           // [token block mi][feature block: 2wn, 2wn+1, 2wn+4, 2wn+5]
+    f32x4 acc[4][2];            // [token block 4 wm + mi][0: feature block wn, 1: its partner wn + 4]
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+    for (int mi = 0; mi < 4; ++mi) { acc[mi][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[mi][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     auto compute = [&](int buf) {
-        const uint16_t* At = a_tile(buf) + (16 * MI * wm + c16) * STR8 + 64 * kg + 8 * g4;
-        const uint16_t* Bt = b_tile(buf) + c16 * STR8 + 64 * kg + 8 * g4;
+        const uint16_t* At = a_tile(buf) + (64 * wm + c16) * STR + 8 * g4;
+        const uint16_t* Bt = b_tile(buf) + (16 * wn + c16) * STR + 8 * g4;
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-            bf16x8 av[MI], bv[4];
+            bf16x8 av[4], bv[2];
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                av[mi] = *reinterpret_cast<const bf16x8*>(At + 16 * mi * STR8 + 32 * k2);
+            for (int mi = 0; mi < 4; ++mi) av[mi] = *reinterpret_cast<const bf16x8*>(At + 16 * mi * STR + 32 * k2);
+            bv[0] = *reinterpret_cast<const bf16x8*>(Bt + 32 * k2);
+            bv[1] = *reinterpret_cast<const bf16x8*>(Bt + 64 * STR + 32 * k2);
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
-                bv[ni] = *reinterpret_cast<const bf16x8*>(Bt + 16 * tn * STR8 + 32 * k2);
+            for (int mi = 0; mi < 4; ++mi) {
+                acc[mi][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[0], acc[mi][0], 0, 0, 0);
+                acc[mi][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[1], acc[mi][1], 0, 0, 0);
             }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
         }
     };
 
@@ -330,51 +184,54 @@ __global__ __launch_bounds__(512, 2) void materialize_mfma8_kernel(MaterializeAr
         step(std::integral_constant<int, 3>{});
     } while (ks < nk);
 
-    // the two groups' sums meet: group g keeps token blocks [g * MI/2, (g+1) * MI/2) and hands
-    // the others to its partner wave (same wm, wn; the tiles are dead after the last barrier)
-    constexpr int MH = MI / 2;
-    float4* xch = reinterpret_cast<float4*>(tiles);
-    __syncthreads();
+    if constexpr (SK > 1) {
+        static_assert(SK == 2, "two workgroups per tile");
+        const int tile = blockIdx.y * gridDim.x + blockIdx.x;
+        float* mine = a.ws_partials + ((size_t)(tile * SK + part) * 8 + wave) * (16 * 128) + lane * 2;
 #pragma unroll
-    for (int m = 0; m < MH; ++m)
+        for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const f32x4 v = acc[(1 - kg) * MH + m][ni];
-            xch[((wave * MH + m) * 4 + ni) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
-        }
-    __syncthreads();
-    // epilogue: lane holds tokens 16*MI*wm + 16mi + 4*g4 + i, features 16*tn + c16
+            for (int ni = 0; ni < 2; ++ni) {
+                dev::st_agent2(mine + ((mi * 2 + ni) * 2 + 0) * 128, acc[mi][ni][0], acc[mi][ni][1]);
+                dev::st_agent2(mine + ((mi * 2 + ni) * 2 + 1) * 128, acc[mi][ni][2], acc[mi][ni][3]);
+            }
+        int32_t* counter = a.ws_counters + (size_t)tile * kDecodeCounterStride;
+        if (!dev::arrive_at(counter, SK, &sm_last)) return;
+        dev::reset_counter_at(counter);
+        const float* theirs = a.ws_partials + ((size_t)(tile * SK + (part ^ 1)) * 8 + wave) * (16 * 128) + lane * 2;
+        float2 o[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[r] = dev::ld_agent2(theirs + r * 128);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const float2 lo = o[(mi * 2 + ni) * 2], hi = o[(mi * 2 + ni) * 2 + 1];
+                acc[mi][ni][0] += lo.x; acc[mi][ni][1] += lo.y; acc[mi][ni][2] += hi.x; acc[mi][ni][3] += hi.y;
+            }
+    }
+
+    // epilogue: lane holds tokens 64 wm + 16 mi + 4 g4 + i, rotary pair j = 16 wn + c16 (features j, j + 64)
     uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+    const int j = 16 * wn + c16;
+    const RopeEntry rope_e = a.rope[j];
 #pragma unroll
-    for (int m = 0; m < MH; ++m) {
-        const int mi = kg * MH + m;
-        f32x4 sum[4];
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const float4 o = xch[(((wave ^ 4) * MH + m) * 4 + ni) * 64 + lane];
-            sum[ni] = acc[mi][ni];
-            sum[ni][0] += o.x; sum[ni][1] += o.y; sum[ni][2] += o.z; sum[ni][3] += o.w;
-        }
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const RowDest d = resolve_row(a, row0 + 16 * MI * wm + 16 * mi + 4 * g4 + i);
+            const RowDest d = sm_dest[64 * wm + 16 * mi + 4 * g4 + i];
             if (!d.valid) continue;
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int j = 16 * (2 * wn + p) + c16;           // rotary pair index, features j and j + 64
-                float lo = sum[p][i], hi = sum[p + 2][i];
-                if (kv == 0) {
-                    float c, s;
-                    rope_cs(a.rope[j], d.pos, c, s);
-                    const float k0 = lo * c - hi * s;
-                    const float k1 = lo * s + hi * c;
-                    lo = k0; hi = k1;
-                }
-                out[d.elem_off + j] = f32_to_bf16_rne(lo);
-                out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
+            float lo = acc[mi][0][i], hi = acc[mi][1][i];
+            if (kv == 0) {
+                float c, s;
+                rope_cs(rope_e, d.pos, c, s);
+                const float k0 = lo * c - hi * s;
+                const float k1 = lo * s + hi * c;
+                lo = k0; hi = k1;
             }
+            out[d.elem_off + j] = f32_to_bf16_rne(lo);
+            out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
         }
-    }
 }
 
 // ---- skinny form: 16 .. 255 token rows (a question, a decode step of a large batch) ----------
@@ -623,7 +480,7 @@ bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_r
 // leaves most compute units idle.  The staged form (hidden a multiple of 1024), us per launch at
 // hidden 4096 / 8192 against the form with direct operand loads: 64 rows 8.1 / 13.8 (17.2 / -),
 // 128 rows 10.6 / 17.4, 255 rows 18.8 / 30.1 (33.9 / 61.6); against the tiled GEMM: 384 rows
-// 27.1 / 44.6 (33.1 / 59.0), 512 rows 35.3 / 57.3 (33.2 / 60.5), 768 rows 50.6 / 80.2 (33.8 / 61.6).
+// 27.1 / 44.6 (about 30 / 58), 512 rows 35.3 / 57.3 (30.6 / 58), 768 rows 50.6 / 80.2 (about 33 / 58).
 constexpr int kSkinnyMaxRows = 256;
 constexpr int kStagedMaxRows = 448;
 
@@ -654,24 +511,14 @@ hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hip
         else                   hipLaunchKernelGGL(materialize_skinny_kernel<2>, dim3(gx, (total_rows + 31) / 32), block, 0, s, a, total_rows);
         return hipGetLastError();
     }
-    // Measured (8 KV heads, TFLOP/s at hidden 4096 / 8192): the launch is bound by what the L2 can
-    // hand to the compute units (64 x 128 tiles re-read every operand 16 times: 454 MB for a
-    // 1000-token chunk at hidden 4096, 81 % of it L2 hits, about 12 TB/s), so larger tiles win as
-    // soon as there are enough of them: 128-row tiles 715 / 765 at 4096 rows and 721 / 817 at 8192,
-    // against 549 / 610 and 585 / 666 with 64-row tiles.  While 64-row tiles make no more
-    // workgroups than there are compute units, the eight-wave form of the same tile is ahead
-    // (1000 rows: 444 / 519 against 394 / 440); with more, it holds one workgroup per compute unit
-    // where the four-wave form holds two or three, and falls behind (1206 rows: 295 against 335).
-    const int wgs64 = 2 * a.Hkv * ((total_rows + 63) / 64);
-    if ((a.Hd % BK8) == 0 && wgs64 <= 256) {
-        hipLaunchKernelGGL(materialize_mfma8_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), dim3(512), 0, s, a, total_rows);
-        return hipGetLastError();
-    }
-    const dim3 block(256);
-    if (2 * a.Hkv * ((total_rows + 127) / 128) >= 256)
-        hipLaunchKernelGGL(materialize_mfma_kernel<128>, dim3(2 * a.Hkv, (total_rows + 127) / 128), block, 0, s, a, total_rows);
+    // two workgroups per tile while that fills the chip at most once (and the workspace has room)
+    const int tiles = 2 * a.Hkv * ((total_rows + 127) / 128);
+    const bool room = a.ws_partials && (int64_t)tiles * 2 * 128 * 128 <= a.ws_partial_floats &&
+                      (int64_t)tiles * kDecodeCounterStride <= a.ws_n_counters;
+    if (tiles * 2 <= 256 && (a.Hd % (2 * BK)) == 0 && room)
+        hipLaunchKernelGGL(materialize_mfma128_kernel<2>, dim3(2 * a.Hkv, (total_rows + 127) / 128, 2), dim3(512), 0, s, a, total_rows);
     else
-        hipLaunchKernelGGL(materialize_mfma_kernel<64>, dim3(2 * a.Hkv, (total_rows + 63) / 64), block, 0, s, a, total_rows);
+        hipLaunchKernelGGL(materialize_mfma128_kernel<1>, dim3(2 * a.Hkv, (total_rows + 127) / 128, 1), dim3(512), 0, s, a, total_rows);
     return hipGetLastError();
 }
 

@@ -712,6 +712,15 @@ const char* matkv_last_error(const matkv_ctx* c) { return c ? c->err : "context 
 
 // ------------------------------------------------------------------------------------ M ----
 
+// The workspace's partial and counter regions as scratch of a projection launch (every call runs
+// on the compute stream, so it never overlaps an attention launch that uses them).
+static void materialize_scratch(matkv_ctx* c, MaterializeArgs& a) {
+    a.ws_partials = reinterpret_cast<float*>(c->workspace + c->wl.off_partials);
+    a.ws_counters = reinterpret_cast<int32_t*>(c->workspace + c->wl.off_counters);
+    a.ws_partial_floats = (int64_t)c->wl.partial_floats;
+    a.ws_n_counters = (int32_t)std::min<size_t>(c->wl.n_counters, 1u << 30);
+}
+
 matkv_status matkv_materialize(matkv_ctx* c, const void* hidden, const void* w_k, const void* w_v,
                                int32_t n_tokens, int64_t pos0, void* k_out, void* v_out,
                                int64_t token_stride) {
@@ -732,6 +741,7 @@ matkv_status matkv_materialize(matkv_ctx* c, const void* hidden, const void* w_k
     a.pos0 = pos0; a.token_stride = token_stride; a.n_tokens = n_tokens;
     a.rows_per_instance = 0; a.batch = 1;
     a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim; a.Hd = c->cfg.hidden;
+    materialize_scratch(c, a);
     HIP_TRY(c, launch_materialize(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
 }
@@ -776,6 +786,7 @@ matkv_status matkv_materialize_tail(matkv_ctx* c, const void* hidden, const void
     a.rows_per_instance = rows_per_instance; a.batch = th->batch;
     a.n_tokens = rows_per_instance > 0 ? th->batch * rows_per_instance : th->total_q;
     a.Hkv = c->cfg.n_kv_heads; a.D = c->cfg.head_dim; a.Hd = c->cfg.hidden;
+    materialize_scratch(c, a);
     HIP_TRY(c, launch_materialize(a, c->cfg.dtype, c->compute));
     return MATKV_OK;
     MATKV_CATCH(c, "materialize_tail")

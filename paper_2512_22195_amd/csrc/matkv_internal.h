@@ -119,6 +119,7 @@ struct WorkspaceLayout {
 };
 
 inline int max_q_rows(const matkv_config& c) { return c.max_tail_tokens; }
+constexpr int kSplitTiles = 128;    // half the compute units: two workgroups per tile
 
 inline WorkspaceLayout workspace_layout(const matkv_config& c) {
     WorkspaceLayout W;
@@ -130,12 +131,17 @@ inline WorkspaceLayout workspace_layout(const matkv_config& c) {
     // on a 128-byte line of its own (the two kinds of launch never overlap, and every counter is
     // back at zero when its launch ends)
     W.n_counters = (size_t)c.max_batch * c.n_kv_heads * (size_t)std::max(max_q_rows(c), kDecodeCounterStride);
+    // (bf16, head_dim 128: the projection GEMM may split the hidden axis over two workgroups per
+    // 128 x 128 tile, up to kSplitTiles tiles: a counter line and two fp32 partial tiles each)
+    const bool gemm_split = c.dtype == MATKV_BF16 && c.head_dim == 128;
+    if (gemm_split) W.n_counters = std::max(W.n_counters, (size_t)kSplitTiles * kDecodeCounterStride);
     o += ((W.n_counters * sizeof(int32_t)) + 255) & ~(size_t)255;
     W.off_partials = o;
     size_t stride = (size_t)c.n_q_heads * (c.head_dim + 4);   // acc[D] + {m, l} (padded)
     size_t dec = (size_t)c.max_batch * kMaxDecodeUnitsPerInstance * stride;
     size_t pre = (size_t)c.max_batch * kMaxPrefillUnitsPerInstance * (size_t)max_q_rows(c) * stride;
     W.partial_floats = dec > pre ? dec : pre;
+    if (gemm_split) W.partial_floats = std::max(W.partial_floats, (size_t)kSplitTiles * 2 * 128 * 128);
     o += W.partial_floats * sizeof(float);
     W.bytes = (o + 255) & ~(size_t)255;
     return W;
@@ -205,6 +211,12 @@ struct MaterializeArgs {
     int32_t rows_per_instance;  // tail form: <0 ragged question rows, >0 uniform newest rows
     int32_t batch;              // tail form
     int32_t Hkv, D, Hd;
+    // scratch for launches that split the hidden axis over two workgroups (null: none): partial
+    // tiles and arrival counters (all zero between launches), shared with the attention kernels
+    float* ws_partials;
+    int32_t* ws_counters;
+    int64_t ws_partial_floats;
+    int32_t ws_n_counters;
 };
 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s);

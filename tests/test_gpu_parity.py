@@ -141,12 +141,14 @@ def test_decode_step_other_shapes_run_two_launches():
     _chain_parity(case, fused=True)
 
 
-@pytest.mark.parametrize("T", [16, 37, 64, 150, 255, 300, 2100])
+@pytest.mark.parametrize("T", [16, 37, 64, 150, 255, 300, 1000, 1100, 2100])
 def test_materialize_row_count_forms_bf16(T):
     """The bf16 projection picks its kernel by row count: skinny split-hidden form (16..255 rows;
-    one, two and four 16-row blocks, several row tiles, ragged ends), tiled GEMM with 64-row
-    tiles (300) and with 128-row tiles (2100, where they fill the chip).  Each against the
-    oracle, K with rotary positions starting at 1000."""
+    one, two and four 16-row blocks, several row tiles, ragged ends), tiled GEMM with two
+    workgroups per 128 x 128 tile, each over half of the hidden axis (300, 1000: ragged last
+    tiles) and with one (1100, 2100).  Each against the oracle, K with rotary positions starting
+    at 1000; run twice, the second time into fresh outputs: the arrival counters of the split
+    form must be back at zero."""
     case = Case("bf16-rows", n_layers=1, Hq=16, Hkv=8, D=128, hidden=512, dtype="bf16",
                 chunk_lens={0: 8}, retrieved=[[0]], q_lens=[1], steps=0, rope_base=500000.0, scale=1.0 / 4.0)
     from workload import normal, to_f64
@@ -156,13 +158,17 @@ def test_materialize_row_count_forms_bf16(T):
         with torch.cuda.stream(ctx.compute_stream):
             w = normal(("rows", "w"), (2, 8 * 128, 512), 0.25, torch.bfloat16).cuda()
             x = normal(("rows", "x", T), (T, 512), 0.25, torch.bfloat16).cuda()
-            k = torch.zeros((8, T, 128), dtype=torch.bfloat16, device="cuda")
-            v = torch.zeros_like(k)
-            ctx.materialize(x, w[0], w[1], T, 1000, k, v, T)
+            outs = []
+            for _ in range(2):
+                k = torch.zeros((8, T, 128), dtype=torch.bfloat16, device="cuda")
+                v = torch.zeros_like(k)
+                ctx.materialize(x, w[0], w[1], T, 1000, k, v, T)
+                outs.append((k, v))
             ctx.compute_stream.synchronize()
         K, V = oracle.materialize(to_f64(x), to_f64(w[0]), to_f64(w[1]), 8, 128, 1000.0, 500000.0)
-        chain.compare_materialized(case, k.cpu(), K, f"K, {T} rows")
-        chain.compare_materialized(case, v.cpu(), V, f"V, {T} rows")
+        for r, (k, v) in enumerate(outs):
+            chain.compare_materialized(case, k.cpu(), K, f"K, {T} rows, run {r}")
+            chain.compare_materialized(case, v.cpu(), V, f"V, {T} rows, run {r}")
     finally:
         ctx.close()
 
@@ -170,7 +176,7 @@ def test_materialize_row_count_forms_bf16(T):
 @pytest.mark.parametrize("hidden,T", [(3072, 1), (3072, 3), (3072, 9), (6144, 2), (6144, 5), (3072, 40), (3072, 300), (4096, 7),
                                       (8192, 1), (8192, 2), (8192, 4), (8192, 9),
                                       (4096, 64), (4096, 100), (4096, 448), (8192, 37), (8192, 500), (6144, 70),
-                                      (2048, 130), (1024, 20), (1536, 50)])
+                                      (2048, 130), (1024, 20), (1536, 50), (4096, 1000), (8192, 700), (3072, 1300), (192, 300)])
 def test_materialize_hidden_sizes_bf16(hidden, T):
     """Hidden sizes of the paper's models: 3072 (the 3B model; passes of six loads in the GEMV
     form) and a multiple of it, 4096, and 8192 (the 70B model: in the GEMV form two waves share
