@@ -270,11 +270,13 @@ hipError_t launch_rows(const MaterializeArgs& a, int total_rows, hipStream_t s) 
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s) {
     const int total_rows = a.n_tokens;
     if (total_rows <= 0) return hipSuccess;
-    // a decode step of a batch: the GEMV form, which reads the weights once per 4 rows, is ahead
-    // up to about 24 rows (16 rows: 11.7 us against the skinny form's flat 16 us); from 32 rows on
-    // the matrix cores take over (skinny form, then the tiled GEMM)
+    // a decode step of a batch: the GEMV form reads the weights once per 4 rows; from 16 rows on
+    // the matrix cores take over where the skinny form that stages rows through LDS exists (hidden
+    // a multiple of 1024; 16 rows at hidden 4096 / 8192: 8.0 / 14.8 us against 9.7 / 20.7, 31 rows
+    // 8.0 / 13.5 against 16.1 / 33.6), from 32 rows on elsewhere (skinny forms, then the tiled GEMM)
+    const int skinny_min = (a.Hd % 1024) == 0 ? 16 : kSkinnyMinRows;
     if (gemv_supported(a, dtype) && total_rows < kGemmMinRows &&
-        !(total_rows >= kSkinnyMinRows && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))
+        !(total_rows >= skinny_min && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))
         return launch_gemv(a, total_rows, s);
     if (materialize_mfma_supported(a, dtype, total_rows)) return launch_materialize_mfma(a, total_rows, s);
     if (dtype == MATKV_F32) return launch_rows<float>(a, total_rows, s);
