@@ -95,9 +95,13 @@ template <int SK>
 __global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(MaterializeArgs a, int total_rows) {
     constexpr int BM = 128, BKS = BK, STR = BKS + 16;
     constexpr int A_ELEMS = BM * STR, B_ELEMS = D * STR;
+    // exactly half of a compute unit's LDS, so that two workgroups fit where the registers allow
+    // (with 2 KB more the 8192-row launch took 205 us instead of 173); the row destinations and
+    // the arrival flag move in once the tiles are dead
     __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * (A_ELEMS + B_ELEMS)];
-    __shared__ int sm_last;
-    __shared__ RowDest sm_dest[BM];
+    RowDest* const sm_dest = reinterpret_cast<RowDest*>(tiles);
+    int* const sm_last = reinterpret_cast<int*>(sm_dest + BM);
+    static_assert(sizeof(RowDest) * BM + sizeof(int) <= sizeof(uint16_t) * 2 * (A_ELEMS + B_ELEMS), "fits the tiles");
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -105,9 +109,9 @@ __global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(Materialize
     const int wm = wave >> 2, wn = wave & 3;
     const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
     const int row0 = blockIdx.y * BM;
-    // where the tile's rows go and their rotary positions: looked up once per row, now, and read
-    // by the epilogue from LDS (in the tail form a lookup walks the batch's instances)
-    if (tid < BM) sm_dest[tid] = resolve_row(a, row0 + tid);
+    // where the tile's rows go and their rotary positions: looked up once per row, now (in the
+    // tail form a lookup walks the batch's instances), handed to the epilogue through LDS
+    const RowDest my_dest = resolve_row(a, row0 + min(tid, BM - 1));
     const int part = blockIdx.z;
     const int nk = a.Hd / (BKS * SK);                   // steps of this workgroup
     const size_t kbase = (size_t)part * nk * BKS;
@@ -183,6 +187,8 @@ __global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(Materialize
         step(std::integral_constant<int, 2>{});
         step(std::integral_constant<int, 3>{});
     } while (ks < nk);
+    if (tid < BM) sm_dest[tid] = my_dest;               // (the loop's last barrier is behind every read of the tiles)
+    __syncthreads();
 
     if constexpr (SK > 1) {
         static_assert(SK == 2, "two workgroups per tile");
@@ -196,7 +202,7 @@ __global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(Materialize
                 dev::st_agent2(mine + ((mi * 2 + ni) * 2 + 1) * 128, acc[mi][ni][2], acc[mi][ni][3]);
             }
         int32_t* counter = a.ws_counters + (size_t)tile * kDecodeCounterStride;
-        if (!dev::arrive_at(counter, SK, &sm_last)) return;
+        if (!dev::arrive_at(counter, SK, sm_last)) return;
         dev::reset_counter_at(counter);
         const float* theirs = a.ws_partials + ((size_t)(tile * SK + (part ^ 1)) * 8 + wave) * (16 * 128) + lane * 2;
         float2 o[16];
