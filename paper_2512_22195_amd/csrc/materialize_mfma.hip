@@ -74,10 +74,9 @@ __device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, f
 
 // ---- tiled GEMM: 128 x 128 tiles, the hidden axis split over SK workgroups ---------------------
 // A workgroup owns 128 tokens x one head of K or of V (128 features: both halves of every rotary
-// pair).  Eight waves as 2 x 4: a wave owns 64 tokens x the 16-feature blocks {wn, wn + 4}
-// (rotary partners); 64 hidden columns per step through double-buffered LDS tiles fed from four
-// rotating register stages (loads carry no branch - past the end they repeat the last step -
-// and the loop has one exit, so the compiler counts the loads in flight instead of draining them).
+// pair); 64 hidden columns per step through double-buffered LDS tiles fed from four rotating
+// register stages (loads carry no branch - past the end they repeat the last step - and the
+// loop has one exit, so the compiler counts the loads in flight instead of draining them).
 // LDS rows are 160 bytes: the 16-byte operand reads of 16 rows measured 4.5 cycles per
 // instruction with them, 8.6 with 144.
 // The launch is bound by what the L2s hand to the compute units, every workgroup reading its
@@ -91,152 +90,176 @@ __device__ __forceinline__ void rope_cs(const RopeEntry& e, float p, float& c, f
 // replaced (eight waves up to 1000 rows, four waves beyond): 512 rows 30.6 / - (33.1 / -),
 // 1000 rows 34.0 / 57.9 (35.9 / 67.6), 1206 rows 46.9 / 88.7 (56.7 / 103.4), 2048 rows
 // 50.2 / 96.0 (62.8 / 111.4), 8192 rows 173 / 315 (185 / 327).
+// The work is split between waves.  In a first form every wave did everything - requested the
+// next operands, moved a tile into LDS, read operands back, multiplied - and the barrier kept
+// all eight in the same phase, so a step lasted as long as its phases added up.  Now waves 4-7
+// only move data (global -> registers -> LDS, four steps of loads in flight) and waves 0-3, one
+// per SIMD, only read operands and multiply (2 x 2 waves, 64 tokens x the 16-feature blocks
+// {2wn, 2wn+1, 2wn+4, 2wn+5} each), so the load path and the LDS writes of step i + 1 run beside
+// the matrix work of step i (1206 rows at hidden 4096 / 8192: 48.9 / 90.0 -> 45.8 / 80.0 us, 2048
+// rows 52.1 / 95.4 -> 48.5 / 86.0; 1000 rows and 8192 rows unchanged).
 template <int SK>
 __global__ __launch_bounds__(512, 2) void materialize_mfma128_kernel(MaterializeArgs a, int total_rows) {
     constexpr int BM = 128, BKS = BK, STR = BKS + 16;
     constexpr int A_ELEMS = BM * STR, B_ELEMS = D * STR;
-    // exactly half of a compute unit's LDS, so that two workgroups fit where the registers allow
-    // (with 2 KB more the 8192-row launch took 205 us instead of 173); the row destinations and
-    // the arrival flag move in once the tiles are dead
     __shared__ __attribute__((aligned(16))) uint16_t tiles[2 * (A_ELEMS + B_ELEMS)];
     RowDest* const sm_dest = reinterpret_cast<RowDest*>(tiles);
     int* const sm_last = reinterpret_cast<int*>(sm_dest + BM);
-    static_assert(sizeof(RowDest) * BM + sizeof(int) <= sizeof(uint16_t) * 2 * (A_ELEMS + B_ELEMS), "fits the tiles");
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int wm = wave >> 2, wn = wave & 3;
     const int kv = blockIdx.x / a.Hkv, head = blockIdx.x % a.Hkv;
     const int row0 = blockIdx.y * BM;
-    // where the tile's rows go and their rotary positions: looked up once per row, now (in the
-    // tail form a lookup walks the batch's instances), handed to the epilogue through LDS
-    const RowDest my_dest = resolve_row(a, row0 + min(tid, BM - 1));
     const int part = blockIdx.z;
     const int nk = a.Hd / (BKS * SK);                   // steps of this workgroup
     const size_t kbase = (size_t)part * nk * BKS;
-
-    const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden) + kbase;
-    const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd + kbase;
-
-    // global -> LDS staging: thread t moves 16 bytes of rows t/8 + 64i, columns 8*(t%8)
-    const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
-    const uint16_t* xg[2];
-    const uint16_t* wg[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = min(row0 + ld_row + 64 * i, total_rows - 1);       // rows past the end repeat the last
-        xg[i] = X + (size_t)r * a.Hd + ld_col;
-        wg[i] = W + (size_t)(ld_row + 64 * i) * a.Hd + ld_col;
-    }
-    constexpr int NS = 4;
-    struct Stage { uint4 x[2], w[2]; };
-    Stage st[NS];
-    auto load_global = [&](Stage& g, int ks) {
-        const int k0 = min(ks, nk - 1) * BKS;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) { g.x[i] = ldg16(xg[i] + k0); g.w[i] = ldg16(wg[i] + k0); }
-    };
     auto a_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS); };
     auto b_tile = [&](int buf) { return tiles + buf * (A_ELEMS + B_ELEMS) + A_ELEMS; };
-    auto store_lds = [&](int buf, const Stage& g) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<uint4*>(a_tile(buf) + (ld_row + 64 * i) * STR + ld_col) = g.x[i];
-            *reinterpret_cast<uint4*>(b_tile(buf) + (ld_row + 64 * i) * STR + ld_col) = g.w[i];
-        }
-    };
 
-    f32x4 acc[4][2];            // [token block 4 wm + mi][0: feature block wn, 1: its partner wn + 4]
+    const int wm = (wave >> 1) & 1, wn = wave & 1;      // of the multiplying waves
+    f32x4 acc[4][4];            // [token block 4 wm + mi][feature block 2wn, 2wn+1, 2wn+4, 2wn+5]
+    // where the tile's rows go and their rotary positions: looked up once per row, now
+    const RowDest my_dest = resolve_row(a, row0 + min(tid, BM - 1));
+
+    if (wave >= 4) {
+        // ---- moving waves: thread t of 256 moves 16 bytes of rows t/8 + 32i, columns 8*(t%8) ----
+        const int lt = tid - 256;
+        const int ld_row = lt >> 3, ld_col = (lt & 7) * 8;
+        const uint16_t* X = reinterpret_cast<const uint16_t*>(a.hidden) + kbase;
+        const uint16_t* W = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + (size_t)head * D * a.Hd + kbase;
+        const uint16_t* xg[4];
+        const uint16_t* wg[4];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) { acc[mi][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[mi][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-    auto compute = [&](int buf) {
-        const uint16_t* At = a_tile(buf) + (64 * wm + c16) * STR + 8 * g4;
-        const uint16_t* Bt = b_tile(buf) + (16 * wn + c16) * STR + 8 * g4;
+        for (int i = 0; i < 4; ++i) {
+            const int r = min(row0 + ld_row + 32 * i, total_rows - 1);   // rows past the end repeat the last
+            xg[i] = X + (size_t)r * a.Hd + ld_col;
+            wg[i] = W + (size_t)(ld_row + 32 * i) * a.Hd + ld_col;
+        }
+        constexpr int NS = 4;
+        struct Stage { uint4 x[4], w[4]; };
+        Stage st[NS];
+        auto load_global = [&](Stage& g, int ks) {
+            const int k0 = min(ks, nk - 1) * BKS;
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-            bf16x8 av[4], bv[2];
+            for (int i = 0; i < 4; ++i) { g.x[i] = ldg16(xg[i] + k0); g.w[i] = ldg16(wg[i] + k0); }
+        };
+        auto store_lds = [&](int buf, const Stage& g) {
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi) av[mi] = *reinterpret_cast<const bf16x8*>(At + 16 * mi * STR + 32 * k2);
-            bv[0] = *reinterpret_cast<const bf16x8*>(Bt + 32 * k2);
-            bv[1] = *reinterpret_cast<const bf16x8*>(Bt + 64 * STR + 32 * k2);
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                acc[mi][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[0], acc[mi][0], 0, 0, 0);
-                acc[mi][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[1], acc[mi][1], 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                *reinterpret_cast<uint4*>(a_tile(buf) + (ld_row + 32 * i) * STR + ld_col) = g.x[i];
+                *reinterpret_cast<uint4*>(b_tile(buf) + (ld_row + 32 * i) * STR + ld_col) = g.w[i];
             }
-        }
-    };
-
+        };
 #pragma unroll
-    for (int i = 0; i < NS - 1; ++i) load_global(st[i], i);
-    store_lds(0, st[0]);
-    lds_barrier();
-    int ks = 0;
-    auto step = [&](auto stage_tag) {
-        constexpr int S = decltype(stage_tag)::value;
-        load_global(st[(S + NS - 1) % NS], ks + NS - 1);
-        if (ks < nk) compute(ks & 1);
-        store_lds((ks + 1) & 1, st[(S + 1) % NS]);
+        for (int i = 0; i < NS - 1; ++i) load_global(st[i], i);
+        store_lds(0, st[0]);
         lds_barrier();
-        ++ks;
-    };
-    do {
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
-    } while (ks < nk);
+        int ks = 0;
+        auto step = [&](auto stage_tag) {
+            constexpr int S = decltype(stage_tag)::value;
+            load_global(st[(S + NS - 1) % NS], ks + NS - 1);
+            store_lds((ks + 1) & 1, st[(S + 1) % NS]);
+            lds_barrier();
+            ++ks;
+        };
+        do {
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+        } while (ks < nk);
+    } else {
+        // ---- multiplying waves ----
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto compute = [&](int buf) {
+            const uint16_t* At = a_tile(buf) + (64 * wm + c16) * STR + 8 * g4;
+            const uint16_t* Bt = b_tile(buf) + c16 * STR + 8 * g4;
+#pragma unroll
+            for (int k2 = 0; k2 < BKS / 32; ++k2) {
+                bf16x8 av[4], bv[4];
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi) av[mi] = *reinterpret_cast<const bf16x8*>(At + 16 * mi * STR + 32 * k2);
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) {
+                    const int tn = 2 * wn + (ni & 1) + 4 * (ni >> 1);
+                    bv[ni] = *reinterpret_cast<const bf16x8*>(Bt + 16 * tn * STR + 32 * k2);
+                }
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 4; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+            }
+        };
+        lds_barrier();                                  // tile 0 is in place
+        const int n_bar = (nk + 3) / 4 * 4;             // the moving waves run whole rounds of four steps
+        for (int ks = 0; ks < n_bar; ++ks) {
+            if (ks < nk) compute(ks & 1);
+            lds_barrier();
+        }
+    }
     if (tid < BM) sm_dest[tid] = my_dest;               // (the loop's last barrier is behind every read of the tiles)
     __syncthreads();
 
     if constexpr (SK > 1) {
         static_assert(SK == 2, "two workgroups per tile");
         const int tile = blockIdx.y * gridDim.x + blockIdx.x;
-        float* mine = a.ws_partials + ((size_t)(tile * SK + part) * 8 + wave) * (16 * 128) + lane * 2;
+        if (wave < 4) {
+            float* mine = a.ws_partials + ((size_t)(tile * SK + part) * 4 + wave) * (32 * 128) + lane * 2;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+            for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                dev::st_agent2(mine + ((mi * 2 + ni) * 2 + 0) * 128, acc[mi][ni][0], acc[mi][ni][1]);
-                dev::st_agent2(mine + ((mi * 2 + ni) * 2 + 1) * 128, acc[mi][ni][2], acc[mi][ni][3]);
-            }
+                for (int ni = 0; ni < 4; ++ni) {
+                    dev::st_agent2(mine + ((mi * 4 + ni) * 2 + 0) * 128, acc[mi][ni][0], acc[mi][ni][1]);
+                    dev::st_agent2(mine + ((mi * 4 + ni) * 2 + 1) * 128, acc[mi][ni][2], acc[mi][ni][3]);
+                }
+        }
         int32_t* counter = a.ws_counters + (size_t)tile * kDecodeCounterStride;
         if (!dev::arrive_at(counter, SK, sm_last)) return;
         dev::reset_counter_at(counter);
-        const float* theirs = a.ws_partials + ((size_t)(tile * SK + (part ^ 1)) * 8 + wave) * (16 * 128) + lane * 2;
-        float2 o[16];
+        if (wave < 4) {
+            const float* theirs = a.ws_partials + ((size_t)(tile * SK + (part ^ 1)) * 4 + wave) * (32 * 128) + lane * 2;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[r] = dev::ld_agent2(theirs + r * 128);
+            for (int mi = 0; mi < 4; ++mi) {
+                float2 o[8];
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+                for (int r = 0; r < 8; ++r) o[r] = dev::ld_agent2(theirs + (mi * 8 + r) * 128);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const float2 lo = o[(mi * 2 + ni) * 2], hi = o[(mi * 2 + ni) * 2 + 1];
-                acc[mi][ni][0] += lo.x; acc[mi][ni][1] += lo.y; acc[mi][ni][2] += hi.x; acc[mi][ni][3] += hi.y;
+                for (int ni = 0; ni < 4; ++ni) {
+                    acc[mi][ni][0] += o[2 * ni].x; acc[mi][ni][1] += o[2 * ni].y;
+                    acc[mi][ni][2] += o[2 * ni + 1].x; acc[mi][ni][3] += o[2 * ni + 1].y;
+                }
             }
+        }
     }
+    if (wave >= 4) return;
 
-    // epilogue: lane holds tokens 64 wm + 16 mi + 4 g4 + i, rotary pair j = 16 wn + c16 (features j, j + 64)
+    // epilogue: lane holds tokens 64 wm + 16 mi + 4 g4 + i, features 16 tn + c16
     uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
-    const int j = 16 * wn + c16;
-    const RopeEntry rope_e = a.rope[j];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const RowDest d = sm_dest[64 * wm + 16 * mi + 4 * g4 + i];
             if (!d.valid) continue;
-            float lo = acc[mi][0][i], hi = acc[mi][1][i];
-            if (kv == 0) {
-                float c, s;
-                rope_cs(rope_e, d.pos, c, s);
-                const float k0 = lo * c - hi * s;
-                const float k1 = lo * s + hi * c;
-                lo = k0; hi = k1;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int j = 16 * (2 * wn + p) + c16;           // rotary pair index, features j and j + 64
+                float lo = acc[mi][p][i], hi = acc[mi][p + 2][i];
+                if (kv == 0) {
+                    float c, s;
+                    rope_cs(a.rope[j], d.pos, c, s);
+                    const float k0 = lo * c - hi * s;
+                    const float k1 = lo * s + hi * c;
+                    lo = k0; hi = k1;
+                }
+                out[d.elem_off + j] = f32_to_bf16_rne(lo);
+                out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
             }
-            out[d.elem_off + j] = f32_to_bf16_rne(lo);
-            out[d.elem_off + j + 64] = f32_to_bf16_rne(hi);
         }
 }
 
