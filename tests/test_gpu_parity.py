@@ -215,6 +215,20 @@ def test_bf16_chain_batch17_decode_rows_on_matrix_cores():
     _chain_parity(case)
 
 
+@pytest.mark.parametrize("hidden,q_lens", [(512, [150, 90, 128, 130, 110]), (512, [300, 290, 310, 280]),
+                                           (1024, [100, 37, 64, 90]), (1024, [20, 30, 25, 1, 9, 40, 33, 16, 28, 30, 17, 5, 31, 29, 30, 22, 19])])
+def test_bf16_chain_long_questions_take_the_tiled_and_staged_projections(hidden, q_lens):
+    """Question rows of a whole batch through the tail form of the projection (rows of several
+    instances in one launch, each row looked up in the table): 608 rows on 128 x 128 tiles with
+    two workgroups per tile, 1180 rows with one, 291 rows on the staged skinny form with 32-row
+    tiles; then decode steps of 17 instances, whose 17 new rows take the staged form too."""
+    B = len(q_lens)
+    case = Case(f"bf16-chain-longq-{hidden}-{B}", n_layers=1, Hq=8, Hkv=2, D=128, hidden=hidden, dtype="bf16",
+                chunk_lens={0: 40, 1: 25}, retrieved=[[i % 2] for i in range(B)], q_lens=q_lens, steps=2,
+                rope_base=500000.0, scale=1.0 / 8.0, q_scale=1.0)
+    _chain_parity(case)
+
+
 def test_materialize_large_positions_bf16():
     """Question/decode tokens sit at positions ~20 000: rotary angles must stay accurate."""
     case = Case("bf16-farpos", n_layers=1, Hq=4, Hkv=1, D=128, hidden=256, dtype="bf16",
