@@ -274,6 +274,11 @@ hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s
     // the matrix cores take over where the skinny form that stages rows through LDS exists (hidden
     // a multiple of 1024; 16 rows at hidden 4096 / 8192: 8.0 / 14.8 us against 9.7 / 20.7, 31 rows
     // 8.0 / 13.5 against 16.1 / 33.6), from 32 rows on elsewhere (skinny forms, then the tiled GEMM)
+    // up to 16 rows (a decode step): the staged form cut into 256 workgroups where it is ahead of the
+    // GEMV form (per layer, every layer's weights from HBM: 4 rows at hidden 8192 10.9 -> 9.0 us,
+    // 16 rows at hidden 4096 10.4 -> 7.9 us; one row at hidden 4096 5.8 us against 6.1: GEMV kept)
+    if ((total_rows >= 8 || a.Hd >= 8192) && materialize_fewrows_supported(a, dtype, total_rows))
+        return launch_materialize_fewrows(a, total_rows, s);
     const int skinny_min = (a.Hd % 1024) == 0 ? 16 : kSkinnyMinRows;
     if (gemv_supported(a, dtype) && total_rows < kGemmMinRows &&
         !(total_rows >= skinny_min && materialize_mfma_supported(a, dtype, total_rows) && (a.Hd % 512) == 0))

@@ -499,7 +499,137 @@ __global__ __launch_bounds__(512) void materialize_skinny_staged_kernel(Material
     }
 }
 
+
+// ---- a handful of rows (a decode step) on the staged form ---------------------------------------
+// The same scheme cut finer, so that a launch with 1 .. 16 token rows still has 256 workgroups: a
+// workgroup owns NP rotary pairs (2 NP weight rows: NP "low" features and their partners) and TMR
+// token rows, which together fill part of one 16 x 16 matrix tile - lanes beyond repeat a row and
+// their results are dropped.  Eight waves split the hidden axis as above; only the TMR real token
+// rows are staged.
+template <int NP, int TMR, int NB>
+__global__ __launch_bounds__(512) void materialize_fewrows_kernel(MaterializeArgs a, int total_rows) {
+    constexpr int NWV = 8, SC = 128;                    // waves; hidden columns per wave and round
+    constexpr int NR = 2 * NP + TMR;                    // rows staged per round
+    static_assert(NP % 4 == 0 && TMR % 4 == 0 && 2 * NP <= 16 && TMR <= 16, "whole loads of four rows; one matrix tile");
+    constexpr int NL = NR / 4;                          // 16-byte loads per lane and round
+    constexpr int RS = SC + 8;                          // bf16 per staged row
+    constexpr int STAGE_BYTES = NWV * NR * RS * 2, RED_BYTES = NWV * TMR * (2 * NP + 1) * 4;
+    __shared__ __attribute__((aligned(16))) char smem[STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    constexpr int GPH = (D / 2) / NP;                   // pair groups per head
+    const int pg = blockIdx.x % GPH, head = (blockIdx.x / GPH) % a.Hkv, kv = (blockIdx.x / GPH) / a.Hkv;
+    const int row0 = blockIdx.y * TMR;
+    const int kslice = a.Hd / NWV;                      // a multiple of SC (checked by the launcher)
+    const int n_rounds = kslice / SC;
+
+    // the epilogue's row and rotary entry of this thread are fixed: asked for now, not after the sums
+    const int et = tid / NP, ep = tid % NP;
+    const RopeEntry rope_e = a.rope[NP * pg + ep];
+    RowDest edest = resolve_row(a, row0 + min(et, TMR - 1));
+    if (et >= TMR) edest.valid = false;
+
+    // load i of a round: staged row 4 i + lane / 16, 16 bytes at column 8 (lane % 16)
+    const int lr = lane >> 4, lc = 8 * (lane & 15);
+    const size_t col0 = (size_t)wave * kslice + lc;
+    const uint16_t* wbase = reinterpret_cast<const uint16_t*>(kv == 0 ? a.w_k : a.w_v) + ((size_t)head * D + NP * pg + lr) * a.Hd + col0;
+    const uint16_t* xp[TMR / 4];
+#pragma unroll
+    for (int i = 0; i < TMR / 4; ++i)
+        xp[i] = reinterpret_cast<const uint16_t*>(a.hidden) + (size_t)min(row0 + 4 * i + lr, total_rows - 1) * a.Hd + col0;
+    auto load = [&](uint4 (&b)[NL], int r) {
+        const int off = min(r, n_rounds - 1) * SC;
+#pragma unroll
+        for (int i = 0; i < NP / 4; ++i) {
+            b[i] = ldg16(wbase + (size_t)(4 * i) * a.Hd + off);
+            b[NP / 4 + i] = ldg16(wbase + (size_t)(D / 2 + 4 * i) * a.Hd + off);
+        }
+#pragma unroll
+        for (int i = 0; i < TMR / 4; ++i) b[NP / 2 + i] = ldg16(xp[i] + off);
+    };
+
+    uint16_t* const st = reinterpret_cast<uint16_t*>(smem) + (size_t)wave * NR * RS;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int brow = c16 < 2 * NP ? c16 : 0;            // weight row of this lane's column (columns beyond: dropped)
+    const int arow = 2 * NP + min(c16, TMR - 1);        // token row of this lane's operand row
+    auto process = [&](const uint4 (&b)[NL]) {
+        __builtin_amdgcn_wave_barrier();                // the last round's reads stay ahead of these writes
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<uint4*>(st + (4 * i + lr) * RS + lc) = b[i];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < SC / 32; ++j) {
+            const bf16x8 wv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(st + brow * RS + 32 * j + 8 * g4));
+            const bf16x8 xa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(st + arow * RS + 32 * j + 8 * g4));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wv, acc, 0, 0, 0);
+        }
+    };
+    {
+        uint4 b[NB][NL];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) load(b[i], i);
+        for (int r = NB; r < n_rounds; r += NB) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                process(b[i]);
+                load(b[i], r + i);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) process(b[i]);
+    }
+
+    // the eight partial tiles meet in LDS (over the staging rows, once every wave is done with its own)
+    __syncthreads();
+    float (*red)[TMR][2 * NP + 1] = reinterpret_cast<float (*)[TMR][2 * NP + 1]>(smem);
+    // lane holds tokens 4 g4 + i, column c16
+    if (c16 < 2 * NP)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * g4 + i < TMR) red[wave][4 * g4 + i][c16] = acc[i];
+    __syncthreads();
+
+    if (edest.valid) {
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) { lo += red[w][et][ep]; hi += red[w][et][NP + ep]; }
+        const int j = NP * pg + ep;
+        if (kv == 0) {
+            float c, s;
+            rope_cs(rope_e, edest.pos, c, s);
+            const float k0 = lo * c - hi * s;
+            const float k1 = lo * s + hi * c;
+            lo = k0; hi = k1;
+        }
+        uint16_t* out = reinterpret_cast<uint16_t*>(kv == 0 ? a.k_out : a.v_out) + (size_t)head * a.token_stride * D;
+        out[edest.elem_off + j] = f32_to_bf16_rne(lo);
+        out[edest.elem_off + j + 64] = f32_to_bf16_rne(hi);
+    }
+}
+
+template <int TMR>
+hipError_t launch_fewrows_t(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    constexpr int NP = 4;
+    const dim3 grid(2 * a.Hkv * (64 / NP), (total_rows + TMR - 1) / TMR), block(512);
+    const int rounds = a.Hd / 1024;
+    if (rounds % 4 == 0) hipLaunchKernelGGL((materialize_fewrows_kernel<NP, TMR, 4>), grid, block, 0, s, a, total_rows);
+    else if (rounds % 2 == 0) hipLaunchKernelGGL((materialize_fewrows_kernel<NP, TMR, 2>), grid, block, 0, s, a, total_rows);
+    else hipLaunchKernelGGL((materialize_fewrows_kernel<NP, TMR, 1>), grid, block, 0, s, a, total_rows);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+bool materialize_fewrows_supported(const MaterializeArgs& a, int dtype, int total_rows) {
+    return dtype == MATKV_BF16 && a.D == 128 && (a.Hd % 1024) == 0 && total_rows >= 1 && total_rows <= 16;
+}
+hipError_t launch_materialize_fewrows(const MaterializeArgs& a, int total_rows, hipStream_t s) {
+    if (total_rows <= 4) return launch_fewrows_t<4>(a, total_rows, s);
+    if (total_rows <= 8) return launch_fewrows_t<8>(a, total_rows, s);
+    return launch_fewrows_t<16>(a, total_rows, s);
+}
 
 bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows) {
     return dtype == MATKV_BF16 && a.D == 128 && (a.Hd % BK) == 0 && total_rows >= 16;

@@ -222,6 +222,8 @@ struct MaterializeArgs {
 hipError_t launch_materialize(const MaterializeArgs& a, int dtype, hipStream_t s);
 bool materialize_mfma_supported(const MaterializeArgs& a, int dtype, int total_rows);
 hipError_t launch_materialize_mfma(const MaterializeArgs& a, int total_rows, hipStream_t s);
+bool materialize_fewrows_supported(const MaterializeArgs& a, int dtype, int total_rows);
+hipError_t launch_materialize_fewrows(const MaterializeArgs& a, int total_rows, hipStream_t s);
 bool decode_step_supported(const AttnArgs& a, const MaterializeArgs& m, int dtype);
 hipError_t launch_decode_step(const AttnArgs& a, const MaterializeArgs& m, int dtype, hipStream_t s);   // projection + attention
 hipError_t launch_probe_read(const void* src, size_t bytes, unsigned* sink, hipStream_t s);

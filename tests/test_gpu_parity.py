@@ -176,14 +176,17 @@ def test_materialize_row_count_forms_bf16(T):
 @pytest.mark.parametrize("hidden,T", [(3072, 1), (3072, 3), (3072, 9), (6144, 2), (6144, 5), (3072, 40), (3072, 300), (4096, 7),
                                       (8192, 1), (8192, 2), (8192, 4), (8192, 9),
                                       (4096, 64), (4096, 100), (4096, 448), (8192, 37), (8192, 500), (6144, 70),
-                                      (2048, 130), (1024, 20), (1536, 50), (4096, 1000), (8192, 700), (3072, 1300), (192, 300)])
+                                      (2048, 130), (1024, 20), (1536, 50), (4096, 1000), (8192, 700), (3072, 1300), (192, 300),
+                                      (4096, 8), (4096, 13), (2048, 16), (8192, 16), (6144, 12), (8192, 6)])
 def test_materialize_hidden_sizes_bf16(hidden, T):
     """Hidden sizes of the paper's models: 3072 (the 3B model; passes of six loads in the GEMV
     form) and a multiple of it, 4096, and 8192 (the 70B model: in the GEMV form two waves share
     a rotary pair, each with half of the hidden axis), at row counts that take the GEMV form,
     the skinny forms and the tiled GEMM.  Multiples of 1024 take the skinny form that stages rows
     through LDS (16-row tiles to 64 rows, 32-row tiles beyond, ragged last tiles; one, two, three,
-    four, six and eight rounds per wave); 1536 the one with direct operand loads."""
+    four, six and eight rounds per wave); 1536 the one with direct operand loads.  Up to 16 rows
+    (from 8 rows on, at hidden 8192 from one) the staged form cut into 256 workgroups of four rotary
+    pairs x 4, 8 or 16 token rows."""
     case = Case(f"bf16-hidden-{hidden}", n_layers=1, Hq=6, Hkv=2, D=128, hidden=hidden, dtype="bf16",
                 chunk_lens={0: 8}, retrieved=[[0]], q_lens=[1], steps=0, rope_base=500000.0, scale=1.0 / 8.0)
     from workload import normal, to_f64
