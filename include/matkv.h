@@ -115,7 +115,9 @@ size_t matkv_blob_bytes(const matkv_config* cfg, int32_t n_tokens);
 size_t matkv_compressed_blob_bytes(const matkv_config* cfg, int32_t n_tokens);
 /* Bytes of one layer's tail buffer (K or V): max_batch * Hkv * max_tail_tokens * D * s. */
 size_t matkv_tail_bytes(const matkv_config* cfg);
-/* Device bytes the caller must provide as workspace (split partials and counters). */
+/* Device bytes the caller must provide as workspace: rotary table, arrival counters and the
+ * split partials of the attention kernels; for bf16 / head_dim 128 at least 16 MiB of partials,
+ * which the tiled projection uses when two workgroups share a tile. */
 size_t matkv_workspace_bytes(const matkv_config* cfg);
 /* Device bytes of one cache table (matkv_assemble's output). */
 size_t matkv_table_bytes(const matkv_config* cfg);

@@ -65,6 +65,10 @@ def test_workspace_and_table_sizes_are_positive_and_aligned(mk):
     c = mk.make_config(32, 32, 8, 128, 4096, "bf16", 500000.0, 16, 5, 192)
     assert mk.workspace_bytes(c) % 256 == 0 and mk.workspace_bytes(c) > 0
     assert mk.table_bytes(c) % 256 == 0 and mk.table_bytes(c) > 0
+    # bf16 / head_dim 128: room for the projection's split tiles (128 tiles x two fp32 partials of
+    # 128 x 128) however small the attention's own needs are
+    small = mk.make_config(1, 8, 2, 128, 512, "bf16", 500000.0, 1, 1, 8)
+    assert mk.workspace_bytes(small) >= 128 * 2 * 128 * 128 * 4
 
 
 def test_null_context_is_an_error_not_a_crash(mk):
