@@ -990,14 +990,16 @@ def test_full_size_chunk_attention(L, Hq, Hkv, rows):
 
 
 # ------------------------------------------------------------------ compressed chunk blobs --
-def test_compress_is_bit_exact():
+@pytest.mark.parametrize("L", [77, 1000, 1024, 1100])
+def test_compress_is_bit_exact(L):
     """matkv_compress against the oracle: every code byte and every scale.  Heads of very
     different magnitudes, one head of zeros, one tiny head on the scale floor, values on exact
-    ties of the 8-bit grid, a largest value just above a power-of-two boundary."""
+    ties of the 8-bit grid, a largest value just above a power-of-two boundary.  Chunks of up to
+    1024 tokens take the kernel that keeps a head in registers, longer ones the two-pass kernel."""
     from paper_2512_22195_amd import binding as mk
     from workload import normal, to_f64
     import oracle
-    nl, Hkv, L, D = 2, 4, 77, 128
+    nl, Hkv, D = 2, 4, 128
     case = Case("compress", n_layers=nl, Hq=8, Hkv=Hkv, D=D, hidden=256, dtype="bf16",
                 chunk_lens={0: L}, retrieved=[[0]], q_lens=[1], steps=0)
     blob = normal(("compress", "blob"), (nl, 2, Hkv, L, D), 1.0, torch.bfloat16)
