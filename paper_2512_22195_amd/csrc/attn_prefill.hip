@@ -380,6 +380,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(
 // units: out = sum_u 2^(m_u - M) acc_u / sum_u 2^(m_u - M) l_u,  M = max_u m_u.
 // Half a wave owns one row: lane k first fetches (m, l) of unit k, the half wave agrees on M
 // and on every unit's weight, then each lane accumulates its 4 dims over the units.
+// NU: units requested per round (the smallest of 2, 4, 8, 16 that covers the launch's largest
+// instance: rounds beyond an instance's units would only re-read its last partial).
+template <int NU>
 __global__ __launch_bounds__(256) void prefill_merge_kernel(
         KernelArgs a, const InstanceInfo* __restrict__ insts, int batch, int total_pairs) {
     constexpr int PS = kPartialStride(D);
@@ -394,18 +397,18 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     const float* base = a.partials + (((size_t)inst.punit0 * a.rows + (q_row - inst.cu_q)) * a.Hq + head) * PS;
     const size_t ustride = (size_t)a.rows * a.Hq * PS;
 
-    // the first 16 units' accumulators are requested together with the (m, l) pairs, before
-    // anything is consumed: one memory round trip for up to 16 units, two for up to 32
-    auto load16 = [&](int u0, float4 (&v)[16]) {
+    // the first NU units' accumulators are requested together with the (m, l) pairs, before
+    // anything is consumed: one memory round trip for up to NU units, two for up to 2 NU
+    auto load16 = [&](int u0, float4 (&v)[NU]) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < NU; ++k) {
             const int u = min(u0 + k, max(n_units, 1) - 1);
             v[k] = *reinterpret_cast<const float4*>(base + (size_t)u * ustride + 4 * hl);
         }
     };
     float2 ml = make_float2(kNegBig, 0.f);
     if (hl < n_units) ml = *reinterpret_cast<const float2*>(base + (size_t)hl * ustride + D);
-    float4 v[16];
+    float4 v[NU];
     load16(0, v);
     float M = ml.x;
 #pragma unroll
@@ -418,10 +421,10 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(
     // both halves of the wave run the same number of steps (shuffles need every lane)
     const int steps = max(n_units, __shfl_xor(n_units, 32));
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int u0 = 0; u0 < steps; u0 += 16) {
+    for (int u0 = 0; u0 < steps; u0 += NU) {
         if (u0 > 0) load16(u0, v);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < NU; ++k) {
             const float c = __shfl(w, (lane & 32) + ((u0 + k) & 31));
             const float cc = (u0 + k < n_units) ? c : 0.f;
             acc.x = fmaf(v[k].x, cc, acc.x); acc.y = fmaf(v[k].y, cc, acc.y);
@@ -447,8 +450,12 @@ hipError_t launch_v(const AttnArgs& a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.max_units_inst <= 1) return e;
     const int total_pairs = a.total_q * a.Hq;
-    hipLaunchKernelGGL(prefill_merge_kernel, dim3((total_pairs + 7) / 8), dim3(256), 0, s, k,
-                       reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst), a.batch, total_pairs);
+    const dim3 mgrid((total_pairs + 7) / 8), mblock(256);
+    const InstanceInfo* insts = reinterpret_cast<const InstanceInfo*>(a.table + a.off_inst);
+    if (a.max_units_inst <= 2)      hipLaunchKernelGGL(prefill_merge_kernel<2>, mgrid, mblock, 0, s, k, insts, a.batch, total_pairs);
+    else if (a.max_units_inst <= 4) hipLaunchKernelGGL(prefill_merge_kernel<4>, mgrid, mblock, 0, s, k, insts, a.batch, total_pairs);
+    else if (a.max_units_inst <= 8) hipLaunchKernelGGL(prefill_merge_kernel<8>, mgrid, mblock, 0, s, k, insts, a.batch, total_pairs);
+    else                            hipLaunchKernelGGL(prefill_merge_kernel<16>, mgrid, mblock, 0, s, k, insts, a.batch, total_pairs);
     return hipGetLastError();
 }
 
