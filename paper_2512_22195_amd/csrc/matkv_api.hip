@@ -150,6 +150,7 @@ struct matkv_ctx {
     hipEvent_t release_ev[kReleaseRing] = {};
     int release_next = 0;
     bool capturing = false;
+    int chunk_table_tokens = -1;   // chunk length the workspace's one-instance table was last written for (-1: unknown)
     matkv_graph* cap = nullptr;
     std::vector<matkv_graph*> graphs;
 };
@@ -1587,7 +1588,13 @@ matkv_status matkv_chunk_attn(matkv_ctx* c, int32_t layer, const void* q, const 
             return fail(c, MATKV_ENOMEM, "chunk_attn: the workspace of this configuration holds the partial results of %zu rows, the chunk has %d",
                         std::min(c->wl.partial_floats / ((size_t)cfg.n_q_heads * (cfg.head_dim + 4)), c->wl.n_counters / cfg.n_kv_heads), n_tokens);
     }
-    HIP_TRY(c, launch_chunk_table(c->workspace + c->wl.off_chunk, n_tokens, c->compute));
+    // the one-instance table depends on the chunk's length alone: written again only when that
+    // changes (a launch of its own costs 4-5 us per layer), always inside a capture (a replay
+    // must not depend on what ran before it), and after any replay
+    if (c->capturing || c->chunk_table_tokens != n_tokens) {
+        HIP_TRY(c, launch_chunk_table(c->workspace + c->wl.off_chunk, n_tokens, c->compute));
+        c->chunk_table_tokens = c->capturing ? -1 : n_tokens;
+    }
     if (tiles) HIP_TRY(c, launch_attn_prefill(a, cfg.dtype, c->compute));
     else HIP_TRY(c, launch_attn_rows(a, cfg.dtype, c->compute));
     return MATKV_OK;
@@ -1669,6 +1676,7 @@ matkv_status matkv_graph_launch(matkv_ctx* c, matkv_graph* g) {
         TableHost* th = find_table(c, adv.first);
         th->max_tail_len += adv.second; th->min_tail_len += adv.second;
     }
+    c->chunk_table_tokens = -1;                // the replay may hold a chunk attention of another length
     HIP_TRY(c, hipGraphLaunch(g->exec, c->compute));
     return MATKV_OK;
 }

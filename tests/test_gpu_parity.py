@@ -924,6 +924,44 @@ def test_chunk_prefill_attention(name, Hq, Hkv, D, dtype, lens, max_tail):
     print(f"{name}: worst abs err {worst:.3e}")
 
 
+def test_chunk_attention_table_follows_the_chunk_length_across_graph_replays():
+    """The one-instance table behind matkv_chunk_attn is rewritten only when the chunk length
+    changes; a recorded chunk attention carries its own write, and a replay must not leave a
+    later eager call of another length with the replay's table."""
+    case = Case("chunk-graph", n_layers=1, Hq=8, Hkv=2, D=128, hidden=256, dtype="bf16",
+                chunk_lens={0: 150, 1: 70}, retrieved=[[0]], q_lens=[1], steps=0, scale=1.0 / 4.0, q_scale=1.0)
+    inp = chain.make_chain_inputs(case)
+    q_chunk = chain.make_chunk_queries(case)
+    ref = chain.run_oracle_chunk_prefill(case, inp, q_chunk)
+    ctx = chain.make_context(case)
+    try:
+        with torch.cuda.stream(ctx.compute_stream):
+            w = inp["w"].cuda()
+            blob, q, o = {}, {}, {}
+            for cid, n in case.chunk_lens.items():
+                blob[cid] = torch.zeros((1, 2, case.Hkv, n, case.D), dtype=case.tdtype, device="cuda")
+                q[cid] = q_chunk[cid].cuda()
+                ctx.materialize(inp["x_chunk"][cid].cuda()[0], w[0, 0], w[0, 1], n, 0, blob[cid][0, 0], blob[cid][0, 1], n)
+                o[cid] = [torch.full_like(q[cid][0], float("nan"), dtype=case.odtype) for _ in range(3)]
+            ctx.graph_begin()
+            ctx.chunk_attn(0, q[0][0], blob[0], 150, o[0][0])               # recorded: length 150
+            g = ctx.graph_end()
+            ctx.chunk_attn(0, q[1][0], blob[1], 70, o[1][0])                # eager: length 70
+            ctx.graph_launch(g)                                             # the table holds 150 again
+            ctx.chunk_attn(0, q[1][0], blob[1], 70, o[1][1])                # must not run with it
+            ctx.chunk_attn(0, q[1][0], blob[1], 70, o[1][2])                # same length again: table kept
+            ctx.chunk_attn(0, q[0][0], blob[0], 150, o[0][1])
+            ctx.compute_stream.synchronize()
+            ctx.graph_destroy(g)
+        outs0 = {0: torch.stack([o[0][0].cpu()]), 1: torch.stack([o[1][0].cpu()])}
+        chain.compare_chunk_prefill(case, outs0, ref)
+        for t in (o[1][1], o[1][2]):
+            assert torch.equal(t.cpu(), o[1][0].cpu())
+        assert torch.equal(o[0][1].cpu(), o[0][0].cpu())
+    finally:
+        ctx.close()
+
+
 def test_chunk_attn_arguments_and_workspace_limit():
     from paper_2512_22195_amd import binding as mk
     case = Case("chunk-args", n_layers=1, Hq=4, Hkv=2, D=64, hidden=128, dtype="f32",
