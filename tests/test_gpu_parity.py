@@ -1321,3 +1321,25 @@ def test_random_small_chain(seed):
                 decode_units=int(rng.choice([0, 0, 0, 1, 3])), max_tail=None)
     print(case)
     _chain_parity(case, fused=bool(rng.random() < 0.5))
+
+
+@pytest.mark.parametrize("seed", list(range(20)))
+def test_random_larger_chain(seed):
+    """The same net over the shapes that take the tiled projection (one and two workgroups per
+    tile), the staged skinny and few-rows forms and the shared decode partition: longer chunks
+    and questions, larger batches, hidden sizes that are multiples of 512 and of 1024."""
+    rng = np.random.default_rng(7000 + seed)
+    G = int(rng.choice([1, 4, 8]))
+    Hkv = int(rng.choice([2, 8]))
+    hidden = int(rng.choice([512, 1024, 2048, 4096]))
+    batch = int(rng.integers(1, 21))
+    n_chunks = int(rng.integers(1, 4))
+    lens = {c: int(rng.integers(200, 1201)) for c in range(n_chunks)}
+    retrieved = [sorted(rng.choice(n_chunks, size=int(rng.integers(0, n_chunks + 1)), replace=False).tolist()) for _ in range(batch)]
+    q_lens = [int(rng.integers(1, 151)) for _ in range(batch)]
+    case = Case(f"rand-large-{seed}", n_layers=1, Hq=G * Hkv, Hkv=Hkv, D=128, hidden=hidden, dtype="bf16",
+                chunk_lens=lens, retrieved=retrieved, q_lens=q_lens, steps=int(rng.integers(1, 3)),
+                rope_base=500000.0, scale=1.0 / np.sqrt(hidden) * 2.0, q_scale=1.0,
+                compressed=bool(rng.random() < 0.3), max_tail=None)
+    print(case)
+    _chain_parity(case, fused=bool(rng.random() < 0.5))
